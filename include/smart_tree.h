@@ -1,0 +1,256 @@
+/*
+ * smart_tree.h -- C ABI of the tree-verification hot path of SMART speculative
+ * decoding on AMD MI355X (gfx950).
+ *
+ * One speculative-decoding step, as the paper frames it (Sec. 1; Sec. 3.2;
+ * Algorithm 1): a draft model proposes candidate continuations, a tree of them
+ * is chosen, the target model verifies the whole tree in one forward pass, and
+ * the longest accepted path is kept.  This library provides the four
+ * data-parallel pieces of that step which do not need model weights:
+ *
+ *   smart_select_tree      which candidates form each sequence's tree
+ *                          (Sec. 3.2, Eqs. "definition" .. "decision_rule",
+ *                          Algorithm 1)
+ *   tree_pack              depth / position ids / ancestor bitmasks of the
+ *                          chosen trees (what "verify the tree in a single
+ *                          forward pass", Sec. 1, needs as mask and positions)
+ *   tree_verify_attention  attention of every tree node over its sequence's
+ *                          paged KV prefix plus its own ancestors (the
+ *                          attention sub-step of that forward pass)
+ *   tree_accept            greedy longest accepted path ("accepted" prefix by
+ *                          prefix, Sec. 3.1 below Eq. "cum_prob")
+ *   kv_cache_write         writes token K/V rows into the paged cache in the
+ *                          layout tree_verify_attention streams fastest
+ *
+ * Conventions
+ *   - Every function returns int32_t: SMART_OK (0) or a negative error code.
+ *     All argument checks happen on the host before anything is enqueued, so a
+ *     non-zero return means no kernel was launched and no output was touched.
+ *   - Pointers named d_* are device memory, h_* host memory.  The caller owns
+ *     every buffer passed in; the library neither frees nor retains them.
+ *   - A smart_ctx owns only internal device workspace (split-KV partial
+ *     results and the launch plan).  It is bound to one device.
+ *   - Device entry points are asynchronous on the given hipStream_t (passed as
+ *     void*; NULL is the default stream) and never synchronise, except that
+ *     growing the workspace inside tree_verify_attention synchronises the
+ *     stream once (avoid by calling smart_reserve up front).
+ *   - Calls that share one smart_ctx must be issued on one stream or otherwise
+ *     serialised by the caller: they share its workspace.
+ *   - Element types: SMART_F32 (float) or SMART_BF16 (bfloat16, upper half of
+ *     an IEEE binary32, round-to-nearest-even on output).
+ *   - Trees: local node 0 of every sequence is the root; parent[i] < i
+ *     (any topological order); at most SMART_MAX_NODES nodes per sequence.
+ */
+#ifndef SMART_TREE_H_
+#define SMART_TREE_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SMART_MAX_NODES 128
+
+enum {
+  SMART_OK = 0,
+  SMART_EINVAL = -1, /* null pointer, bad shape / stride / dtype / option        */
+  SMART_ETREE = -2,  /* malformed candidate forest or tree (host-checked inputs) */
+  SMART_ECAP = -3,   /* an output buffer's stated capacity is too small          */
+  SMART_EHIP = -4,   /* a HIP runtime call failed; see smart_last_hip_error      */
+  SMART_ENOMEM = -5  /* workspace allocation failed                              */
+};
+
+enum { SMART_F32 = 0, SMART_BF16 = 1 };
+
+/* Paged KV-cache layouts.  A page is the block_size x head_dim elements of one
+ * (physical block, kv head); pages are addressed by block_stride / head_stride
+ * (in elements).
+ *   SMART_KV_PLAIN        element (slot, d) at slot * token_stride + d
+ *   SMART_KV_INTERLEAVED  groups of 8 elements are matrix-core operand vectors:
+ *                         K: ((d / 8) * block_size + slot) * 8 + d % 8
+ *                         V: ((slot / 8) * head_dim + d) * 8 + slot % 8
+ *                         (page contiguous; block_size and head_dim multiples of 8)
+ * The bf16 matrix-core kernel requires SMART_KV_INTERLEAVED, block_size 16 and
+ * head_dim 128; every other combination runs a slower general kernel. */
+enum { SMART_KV_PLAIN = 0, SMART_KV_INTERLEAVED = 1 };
+
+/* smart_select_tree modes */
+enum { SMART_BEST_FIRST = 0, SMART_LAYERWISE = 1 };
+enum { SMART_DILUTION_NONE = 0, SMART_DILUTION_PATH_MEAN = 1 };
+
+/* smart_set_option keys */
+enum {
+  SMART_OPT_TVA_WORKERS = 1,      /* number of split-KV workers (waves); 0 = automatic   */
+  SMART_OPT_TVA_FORCE_GENERAL = 2 /* 1 = always run the general (non matrix-core) kernel */
+};
+
+typedef struct smart_ctx smart_ctx;
+
+const char* smart_strerror(int32_t code);
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int32_t smart_last_hip_error(void);
+
+/* Creates a context on device `device_id` (must be a gfx950 device for the
+ * device entry points to work).  Allocates nothing on the device yet. */
+int32_t smart_create(smart_ctx** out_ctx, int32_t device_id);
+/* Frees the workspace.  Synchronises the device. */
+int32_t smart_destroy(smart_ctx* ctx);
+/* Pre-sizes the attention workspace for calls with at most this many sequences,
+ * total tree nodes, query heads and kv heads (head_dim <= 128), so that later
+ * tree_verify_attention calls do not allocate. */
+int32_t smart_reserve(smart_ctx* ctx, int32_t max_batch, int32_t max_total_nodes,
+                      int32_t max_q_heads, int32_t max_kv_heads);
+int32_t smart_set_option(smart_ctx* ctx, int32_t key, int64_t value);
+
+/* ---------------------------------------------------------------------------
+ * smart_select_tree (host, batched over sequences)
+ *
+ * Sec. 3.2 of the paper.  Per sequence, a candidate forest (the draft model's
+ * top-k expansions with conditional probabilities p(u | path), Sec. 3.2
+ * "Sequential Decision Formulation") is reduced to a tree S by the marginal
+ * rule of Eq. "decision_rule": candidate u is kept iff
+ *        alpha * dL(u) / dC(n)  >  L(S) / cost[n]          (strict, fp64)
+ * with n = |S| (root included), cost[n] = C_spec(n) / c_T (Eq. "definition"),
+ * dC(n) = h_dcost[n] if given (Eq. "marginal_cost") else cost[n+1] - cost[n],
+ * P(u) the cumulative path probability (Eq. "cum_prob"),
+ *   dilution NONE:      L = sum_{u in S} P(u),                  dL(u) = P(u)
+ *   dilution PATH_MEAN: L = Eq. "expected_acc_length" literally, dL(u) = P(u) / #paths
+ *                       (Eq. "marginal_benefit").
+ *   schedule BEST_FIRST: node by node; always the unselected candidate with the
+ *     largest P whose parent is selected (ties: smaller index); stops at the
+ *     first failed test, at |S| = budget, or when nothing is left.
+ *   schedule LAYERWISE:  Algorithm 1: per layer the terms L, n, #paths are
+ *     frozen, all children of the previous layer's survivors are tested, and
+ *     survivors beyond the budget are dropped lowest-P first (ties: larger
+ *     index first), so |S| <= budget always (Eq. "optimization").
+ * Depth is capped at max_depth.  Arithmetic is IEEE binary64, evaluated as
+ * ((alpha * dL) / dC) > (L / cost[n]), no fused multiply-add; L (NONE) is
+ * accumulated in selection order starting from 1.0.
+ *
+ * Inputs (host): h_cand_cu[batch+1] CSR offsets; per candidate, local parent
+ * index (-1 only for candidate 0, the root; otherwise < own index),
+ * conditional probability in [0,1] (ignored for the root), token id.
+ * h_cost[budget+2]; h_dcost[budget+1] or NULL.
+ * Outputs (host): tree CSR h_out_cu[batch+1]; per node (node id = selection
+ * rank for BEST_FIRST; layer then candidate index for LAYERWISE): local parent
+ * node id, token, candidate index, P(u); per sequence L and R = L / cost[|S|].
+ * out_cap = capacity (nodes) of the per-node outputs.
+ * Errors: SMART_EINVAL (null, batch < 0, budget < 1 or > SMART_MAX_NODES,
+ * alpha outside (0,1], max_depth < 0, unknown mode), SMART_ETREE (bad forest),
+ * SMART_ECAP (out_cap too small; nothing is written in that case).
+ * ------------------------------------------------------------------------- */
+int32_t smart_select_tree(
+    int32_t batch, const int32_t* h_cand_cu, const int32_t* h_cand_parent,
+    const double* h_cand_prob, const int32_t* h_cand_token,
+    const double* h_cost, const double* h_dcost,
+    double alpha, int32_t max_depth, int32_t budget, int32_t schedule, int32_t dilution,
+    int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
+    int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
+    double* h_out_L, double* h_out_R);
+
+/* ---------------------------------------------------------------------------
+ * tree_pack (device)
+ *
+ * For every node i of every sequence b (local ids):
+ *   depth[i]    = 0 for the root, depth[parent[i]] + 1 otherwise
+ *   position[i] = prefix_len[b] + depth[i]          (the node's position id)
+ *   node_seq[i] = b
+ *   anc_mask[i] = 128-bit set {i} U ancestors(i): word 0 holds bits 0..63,
+ *                 word 1 bits 64..127; layout [total_nodes][2]
+ * d_status[b] = 0, or SMART_ETREE if sequence b's tree is malformed (no node,
+ * more than SMART_MAX_NODES nodes, parent[0] != -1, parent[i] outside [0, i));
+ * outputs of a malformed sequence are zero-filled.
+ * Host errors: SMART_EINVAL (null pointers, negative sizes).
+ * ------------------------------------------------------------------------- */
+int32_t tree_pack(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nodes,
+                  const int32_t* d_cu_nodes, const int32_t* d_parent, const int32_t* d_prefix_len,
+                  int32_t* d_depth, int32_t* d_position, int32_t* d_node_seq,
+                  uint64_t* d_anc_mask, int32_t* d_status);
+
+/* ---------------------------------------------------------------------------
+ * kv_cache_write (device)
+ *
+ * Copies n_tokens rows of K and V ([n_tokens][num_kv_heads][head_dim]) into the
+ * paged cache: row t goes to physical block d_slot_mapping[t] / block_size,
+ * slot d_slot_mapping[t] % block_size, in the given layout (negative mapping
+ * entries are skipped).  This is how a prefix is laid down and how accepted
+ * tree nodes are committed after tree_accept.
+ * ------------------------------------------------------------------------- */
+int32_t kv_cache_write(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layout,
+                       int32_t n_tokens, int32_t num_kv_heads, int32_t head_dim,
+                       int32_t block_size, int32_t num_blocks,
+                       const void* d_k_src, const void* d_v_src, const int64_t* d_slot_mapping,
+                       void* d_k_cache, void* d_v_cache,
+                       int64_t cache_block_stride, int64_t cache_head_stride,
+                       int64_t cache_token_stride /* PLAIN only */);
+
+/* ---------------------------------------------------------------------------
+ * tree_verify_attention (device)
+ *
+ * For every sequence b, node i of its tree, query head h (kv head g = h / G,
+ * G = num_q_heads / num_kv_heads):
+ *   keys   = cache tokens 0 .. prefix_len[b]-1 of b (token t lives in physical
+ *            block d_block_table[b][t / block_size], slot t % block_size)
+ *            followed by the tree nodes j of b with bit j set in anc_mask[i]
+ *            (i itself and its ancestors)
+ *   out[i,h,:] = softmax_keys(softmax_scale * <q[i,h,:], k[g,:]>) . v[g,:]
+ *   lse[i,h]   = log sum_keys exp(score)                      (optional)
+ * Scores, softmax and accumulation are fp32 (bf16 inputs are multiplied on
+ * the matrix cores with fp32 accumulation; softmax weights are rounded to
+ * bf16 before the second product).
+ *
+ * Shapes: q, out [total_nodes][Hq][D]; k_tree, v_tree [total_nodes][Hkv][D]
+ * (tree K/V are not in the cache yet); block_table [batch][max_blocks_per_seq]
+ * (entries past a sequence's prefix are never read; read entries are clamped
+ * to [0, num_blocks)); prefix_len is clamped to
+ * [0, max_blocks_per_seq * block_size]; anc_mask as written by tree_pack.
+ * Host errors: SMART_EINVAL for null pointers, Hq % Hkv != 0, G > 16,
+ * head_dim not in {64, 128}, block_size not a multiple of 8 or > 64,
+ * unknown dtype / layout, strides smaller than a page; SMART_ENOMEM / SMART_EHIP.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+  int32_t dtype;     /* SMART_F32 | SMART_BF16: q, k, v, out share it */
+  int32_t kv_layout; /* SMART_KV_PLAIN | SMART_KV_INTERLEAVED        */
+  int32_t batch, total_nodes, num_q_heads, num_kv_heads, head_dim;
+  int32_t block_size, max_blocks_per_seq, num_blocks;
+  float softmax_scale;
+  int32_t reserved0;
+  const void* d_q;
+  const void* d_k_tree;
+  const void* d_v_tree;
+  const void* d_k_cache;
+  const void* d_v_cache;
+  int64_t cache_block_stride, cache_head_stride, cache_token_stride; /* elements */
+  const int32_t* d_block_table;
+  const int32_t* d_prefix_len; /* [batch]   */
+  const int32_t* d_cu_nodes;   /* [batch+1] */
+  const uint64_t* d_anc_mask;  /* [total_nodes][2] */
+  void* d_out;
+  float* d_lse; /* [total_nodes][Hq] or NULL */
+} tva_params;
+
+int32_t tree_verify_attention(smart_ctx* ctx, void* stream, const tva_params* params);
+
+/* ---------------------------------------------------------------------------
+ * tree_accept (device)
+ *
+ * Greedy verification walk per sequence.  d_target_next[i] is the target
+ * model's own next token after node i.  Start at the root; from node cur move
+ * to the child whose drafted token equals d_target_next[cur] (smallest node id
+ * among equal siblings); stop when there is none or max_depth drafts are
+ * accepted.
+ *   d_accept_len[b]   accepted draft nodes (root excluded)
+ *   d_accept_path[b][0..max_depth]  visited local node ids, root first, -1 padded
+ *   d_bonus_token[b]  d_target_next at the last node reached
+ * Sequences with no node or more than SMART_MAX_NODES nodes get accept_len -1.
+ * ------------------------------------------------------------------------- */
+int32_t tree_accept(smart_ctx* ctx, void* stream, int32_t batch, int32_t max_depth,
+                    const int32_t* d_cu_nodes, const int32_t* d_parent, const int32_t* d_token,
+                    const int32_t* d_target_next,
+                    int32_t* d_accept_len, int32_t* d_accept_path, int32_t* d_bonus_token);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMART_TREE_H_ */

@@ -1,0 +1,287 @@
+"""Thin ctypes binding of libsmart_tree.so (argument marshalling only).
+
+Every step runs in the library's kernels (or, for selection, its host C++).
+PyTorch supplies device memory and streams.  There is no fallback: if the
+library has not been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsmart_tree.so")
+
+SMART_OK, SMART_EINVAL, SMART_ETREE, SMART_ECAP, SMART_EHIP, SMART_ENOMEM = 0, -1, -2, -3, -4, -5
+SMART_F32, SMART_BF16 = 0, 1
+SMART_KV_PLAIN, SMART_KV_INTERLEAVED = 0, 1
+SMART_BEST_FIRST, SMART_LAYERWISE = 0, 1
+SMART_DILUTION_NONE, SMART_DILUTION_PATH_MEAN = 0, 1
+SMART_OPT_TVA_WORKERS, SMART_OPT_TVA_FORCE_GENERAL = 1, 2
+SMART_MAX_NODES = 128
+
+EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
+           "smart_reserve", "smart_set_option", "smart_select_tree", "tree_pack",
+           "kv_cache_write", "tree_verify_attention", "tree_accept"]
+
+
+class SmartError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {_strerror(code)} (code {code}, hip error {_lib().smart_last_hip_error()})")
+
+
+class TvaParams(ctypes.Structure):
+    _fields_ = [
+        ("dtype", ctypes.c_int32), ("kv_layout", ctypes.c_int32),
+        ("batch", ctypes.c_int32), ("total_nodes", ctypes.c_int32),
+        ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("reserved0", ctypes.c_int32),
+        ("d_q", ctypes.c_void_p), ("d_k_tree", ctypes.c_void_p), ("d_v_tree", ctypes.c_void_p),
+        ("d_k_cache", ctypes.c_void_p), ("d_v_cache", ctypes.c_void_p),
+        ("cache_block_stride", ctypes.c_int64), ("cache_head_stride", ctypes.c_int64),
+        ("cache_token_stride", ctypes.c_int64),
+        ("d_block_table", ctypes.c_void_p), ("d_prefix_len", ctypes.c_void_p),
+        ("d_cu_nodes", ctypes.c_void_p), ("d_anc_mask", ctypes.c_void_p),
+        ("d_out", ctypes.c_void_p), ("d_lse", ctypes.c_void_p),
+    ]
+
+
+_libh = None
+
+
+def _lib():
+    global _libh
+    if _libh is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2604_09731_amd.build` (there is no fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+        lib.smart_strerror.restype = ctypes.c_char_p
+        lib.smart_strerror.argtypes = [i32]
+        lib.smart_last_hip_error.restype = i32
+        lib.smart_create.restype = i32
+        lib.smart_create.argtypes = [ctypes.POINTER(vp), i32]
+        lib.smart_destroy.restype = i32
+        lib.smart_destroy.argtypes = [vp]
+        lib.smart_reserve.restype = i32
+        lib.smart_reserve.argtypes = [vp, i32, i32, i32, i32]
+        lib.smart_set_option.restype = i32
+        lib.smart_set_option.argtypes = [vp, i32, i64]
+        lib.smart_select_tree.restype = i32
+        lib.smart_select_tree.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, i32, i32,
+                                          vp, vp, vp, vp, vp, i64, vp, vp]
+        lib.tree_pack.restype = i32
+        lib.tree_pack.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.kv_cache_write.restype = i32
+        lib.kv_cache_write.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp,
+                                       i64, i64, i64]
+        lib.tree_verify_attention.restype = i32
+        lib.tree_verify_attention.argtypes = [vp, vp, ctypes.POINTER(TvaParams)]
+        lib.tree_accept.restype = i32
+        lib.tree_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        _libh = lib
+    return _libh
+
+
+def _strerror(code: int) -> str:
+    return _lib().smart_strerror(code).decode()
+
+
+def _check(code: int, what: str):
+    if code != SMART_OK:
+        raise SmartError(code, what)
+
+
+# ---------------------------------------------------------------------------
+# host: selection
+# ---------------------------------------------------------------------------
+def smart_select_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, dcost=None, alpha=0.8,
+                      max_depth=8, budget=64, schedule=SMART_BEST_FIRST,
+                      dilution=SMART_DILUTION_NONE, out_cap: Optional[int] = None):
+    """Returns dict(cu_nodes, parent, token, cand_index, pathprob, L, R) of numpy arrays."""
+    cand_cu = np.ascontiguousarray(cand_cu, np.int32)
+    cand_parent = np.ascontiguousarray(cand_parent, np.int32)
+    cand_prob = np.ascontiguousarray(cand_prob, np.float64)
+    cand_token = np.ascontiguousarray(cand_token, np.int32)
+    cost = np.ascontiguousarray(cost, np.float64)
+    if dcost is not None:
+        dcost = np.ascontiguousarray(dcost, np.float64)
+        if dcost.shape[0] < budget + 1:
+            raise ValueError("dcost needs budget + 1 entries")
+    if cost.shape[0] < budget + 2:
+        raise ValueError("cost needs budget + 2 entries")
+    batch = cand_cu.shape[0] - 1
+    cap = int(out_cap if out_cap is not None else batch * max(budget, 1))
+    o_cu = np.zeros(batch + 1, np.int32)
+    o_parent = np.zeros(max(cap, 1), np.int32)
+    o_token = np.zeros(max(cap, 1), np.int32)
+    o_cand = np.zeros(max(cap, 1), np.int32)
+    o_pp = np.zeros(max(cap, 1), np.float64)
+    o_L = np.zeros(max(batch, 1), np.float64)
+    o_R = np.zeros(max(batch, 1), np.float64)
+    p = lambda a: ctypes.c_void_p(a.ctypes.data) if a is not None else None
+    rc = _lib().smart_select_tree(batch, p(cand_cu), p(cand_parent), p(cand_prob), p(cand_token),
+                                  p(cost), p(dcost), float(alpha), int(max_depth), int(budget),
+                                  int(schedule), int(dilution), p(o_cu), p(o_parent), p(o_token),
+                                  p(o_cand), p(o_pp), cap, p(o_L), p(o_R))
+    _check(rc, "smart_select_tree")
+    n = int(o_cu[-1])
+    return dict(cu_nodes=o_cu, parent=o_parent[:n], token=o_token[:n], cand_index=o_cand[:n],
+                pathprob=o_pp[:n], L=o_L[:batch], R=o_R[:batch])
+
+
+# ---------------------------------------------------------------------------
+# device
+# ---------------------------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _stream_ptr():
+    torch = _torch()
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _dtype_code(t):
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return SMART_F32
+    if t.dtype == torch.bfloat16:
+        return SMART_BF16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def interleave_kv_cache(k_plain, v_plain):
+    """[num_blocks, Hkv, block_size, D] plain caches -> the interleaved layout
+    (pure data movement; shapes [nb, Hkv, D/8, bs, 8] and [nb, Hkv, bs/8, D, 8])."""
+    nb, Hkv, bs, D = k_plain.shape
+    k = k_plain.reshape(nb, Hkv, bs, D // 8, 8).permute(0, 1, 3, 2, 4).contiguous()
+    v = v_plain.reshape(nb, Hkv, bs // 8, 8, D).permute(0, 1, 2, 4, 3).contiguous()
+    return k, v
+
+
+class SmartTree:
+    """Owns one smart_ctx on one device."""
+
+    def __init__(self, device: int = 0):
+        torch = _torch()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the tree-verification library needs an MI355X")
+        self.device = int(device)
+        torch.cuda.set_device(self.device)
+        torch.cuda.init()
+        h = ctypes.c_void_p()
+        _check(_lib().smart_create(ctypes.byref(h), self.device), "smart_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _check(_lib().smart_destroy(self._h), "smart_destroy")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_option(self, key: int, value: int):
+        _check(_lib().smart_set_option(self._h, key, int(value)), "smart_set_option")
+
+    def reserve(self, max_batch, max_total_nodes, max_q_heads, max_kv_heads):
+        _check(_lib().smart_reserve(self._h, max_batch, max_total_nodes, max_q_heads, max_kv_heads),
+               "smart_reserve")
+
+    # -- tree_pack ---------------------------------------------------------
+    def tree_pack(self, cu_nodes, parent, prefix_len):
+        torch = _torch()
+        B = cu_nodes.shape[0] - 1
+        N = parent.shape[0]
+        dev = cu_nodes.device
+        depth = torch.empty(N, dtype=torch.int32, device=dev)
+        position = torch.empty(N, dtype=torch.int32, device=dev)
+        node_seq = torch.empty(N, dtype=torch.int32, device=dev)
+        anc_mask = torch.empty((N, 2), dtype=torch.int64, device=dev)
+        status = torch.empty(B, dtype=torch.int32, device=dev)
+        rc = _lib().tree_pack(self._h, _stream_ptr(), B, N, _ptr(cu_nodes), _ptr(parent),
+                              _ptr(prefix_len), _ptr(depth), _ptr(position), _ptr(node_seq),
+                              _ptr(anc_mask), _ptr(status))
+        _check(rc, "tree_pack")
+        return depth, position, node_seq, anc_mask, status
+
+    # -- kv_cache_write ----------------------------------------------------
+    def kv_cache_write(self, k_src, v_src, slot_mapping, k_cache, v_cache, layout, block_size,
+                       num_blocks, block_stride, head_stride, token_stride=0):
+        n, Hkv, D = k_src.shape
+        rc = _lib().kv_cache_write(self._h, _stream_ptr(), _dtype_code(k_src), layout, n, Hkv, D,
+                                   block_size, num_blocks, _ptr(k_src), _ptr(v_src),
+                                   _ptr(slot_mapping), _ptr(k_cache), _ptr(v_cache),
+                                   block_stride, head_stride, token_stride)
+        _check(rc, "kv_cache_write")
+
+    # -- tree_verify_attention ---------------------------------------------
+    def tree_verify_attention(self, q, k_tree, v_tree, k_cache, v_cache, block_table, prefix_len,
+                              cu_nodes, anc_mask, softmax_scale, kv_layout, block_size=16,
+                              out=None, lse=None, want_lse=False):
+        """k_cache / v_cache: [num_blocks, Hkv, ...] with one contiguous page of
+        block_size * D elements per (block, head) (any of the two layouts)."""
+        torch = _torch()
+        N, Hq, D = q.shape
+        Hkv = k_tree.shape[1]
+        B = cu_nodes.shape[0] - 1
+        if out is None:
+            out = torch.empty_like(q)
+        if lse is None and want_lse:
+            lse = torch.empty((N, Hq), dtype=torch.float32, device=q.device)
+        p = TvaParams()
+        p.dtype = _dtype_code(q)
+        p.kv_layout = kv_layout
+        p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, p.head_dim = B, N, Hq, Hkv, D
+        p.block_size = block_size
+        p.max_blocks_per_seq = block_table.shape[1] if block_table is not None else 0
+        p.num_blocks = k_cache.shape[0] if k_cache is not None else 0
+        p.softmax_scale = float(softmax_scale)
+        p.d_q, p.d_k_tree, p.d_v_tree = q.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr()
+        if k_cache is not None:
+            assert k_cache.stride(0) == v_cache.stride(0) and k_cache.stride(1) == v_cache.stride(1)
+            p.d_k_cache, p.d_v_cache = k_cache.data_ptr(), v_cache.data_ptr()
+            p.cache_block_stride, p.cache_head_stride = k_cache.stride(0), k_cache.stride(1)
+            p.cache_token_stride = k_cache.stride(2) if kv_layout == SMART_KV_PLAIN else D
+            p.d_block_table = block_table.data_ptr()
+        else:
+            p.cache_block_stride = p.cache_head_stride = block_size * D
+            p.cache_token_stride = D
+        p.d_prefix_len, p.d_cu_nodes = prefix_len.data_ptr(), cu_nodes.data_ptr()
+        p.d_anc_mask = anc_mask.data_ptr()
+        p.d_out = out.data_ptr()
+        p.d_lse = lse.data_ptr() if lse is not None else None
+        _check(_lib().tree_verify_attention(self._h, _stream_ptr(), ctypes.byref(p)),
+               "tree_verify_attention")
+        return (out, lse) if (want_lse or lse is not None) else out
+
+    # -- tree_accept -------------------------------------------------------
+    def tree_accept(self, cu_nodes, parent, token, target_next, max_depth):
+        torch = _torch()
+        B = cu_nodes.shape[0] - 1
+        dev = cu_nodes.device
+        accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+        accept_path = torch.empty((B, max_depth + 1), dtype=torch.int32, device=dev)
+        bonus = torch.empty(B, dtype=torch.int32, device=dev)
+        rc = _lib().tree_accept(self._h, _stream_ptr(), B, max_depth, _ptr(cu_nodes), _ptr(parent),
+                                _ptr(token), _ptr(target_next), _ptr(accept_len), _ptr(accept_path),
+                                _ptr(bonus))
+        _check(rc, "tree_accept")
+        return accept_len, accept_path, bonus

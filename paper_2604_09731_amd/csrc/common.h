@@ -1,0 +1,52 @@
+// Internal declarations shared by the library's translation units (not part of
+// the C ABI).
+#ifndef SMART_COMMON_H_
+#define SMART_COMMON_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "smart_tree.h"
+
+struct smart_ctx {
+  int32_t device = 0;
+  int32_t num_cus = 0;
+  // attention workspace
+  void* ws = nullptr;         // split-KV partial results
+  size_t ws_bytes = 0;
+  int32_t* plan = nullptr;    // launch plan written by the planning kernel
+  size_t plan_bytes = 0;
+  // options
+  int64_t opt_workers = 0;
+  int64_t opt_force_general = 0;
+};
+
+namespace smart {
+
+void set_last_hip_error(hipError_t e);
+
+// Records the error and returns SMART_EHIP from the enclosing function.
+#define SMART_HIP_CHECK(expr)                      \
+  do {                                             \
+    hipError_t _e = (expr);                        \
+    if (_e != hipSuccess) {                        \
+      ::smart::set_last_hip_error(_e);             \
+      return SMART_EHIP;                           \
+    }                                              \
+  } while (0)
+
+// Makes sure the context's workspace holds at least the given sizes.  May
+// synchronise `stream` (only when it has to grow).
+int32_t ensure_workspace(smart_ctx* ctx, hipStream_t stream, size_t ws_bytes, size_t plan_bytes);
+
+// Entry points of the two attention implementations (validated params).
+int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
+int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
+bool tva_mfma_supported(const tva_params& p);
+// Workspace the matrix-core path needs for a problem of this size.
+void tva_mfma_workspace(int32_t batch, int32_t total_nodes, int32_t num_q_heads,
+                        int32_t num_kv_heads, int32_t workers, size_t* ws_bytes, size_t* plan_bytes);
+int32_t tva_mfma_default_workers(const smart_ctx* ctx);
+
+}  // namespace smart
+#endif

@@ -1,0 +1,134 @@
+// tree_pack and tree_accept: integer-only kernels, one 64-lane wavefront per
+// sequence (trees hold at most 128 nodes, so a lane owns nodes lane, lane+64).
+//
+// The paper verifies "an entire tree in a single forward pass" (Sec. 1) and
+// keeps the prefix of a draft path the target agrees with (Sec. 3.1, below
+// Eq. "cum_prob"); these kernels produce what that pass needs (positions,
+// ancestor masks) and what it yields (the accepted path).
+#include "common.h"
+
+namespace {
+
+constexpr int kWave = 64;
+
+__global__ __launch_bounds__(kWave) void tree_pack_kernel(
+    int batch, int total_nodes, const int32_t* __restrict__ cu_nodes,
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ prefix_len,
+    int32_t* __restrict__ depth, int32_t* __restrict__ position, int32_t* __restrict__ node_seq,
+    uint64_t* __restrict__ anc_mask, int32_t* __restrict__ status) {
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (b >= batch) return;
+  int base = cu_nodes[b];
+  int end = cu_nodes[b + 1];
+  // keep every access inside the arrays whatever the offsets say
+  const bool bad_range = base < 0 || end < base || end > total_nodes;
+  if (bad_range) {
+    if (lane == 0) status[b] = SMART_ETREE;
+    return;
+  }
+  const int n = end - base;
+  bool ok = n >= 1 && n <= SMART_MAX_NODES;
+  const int n_clamped = n < SMART_MAX_NODES ? n : SMART_MAX_NODES;
+  // validate parents (lane-parallel), then agree across the wavefront
+  bool mine_ok = true;
+  for (int i = lane; i < n_clamped; i += kWave) {
+    const int p = parent[base + i];
+    mine_ok = mine_ok && (i == 0 ? p == -1 : (p >= 0 && p < i));
+  }
+  ok = ok && __all(mine_ok);
+  const int len = prefix_len[b];
+  for (int i = lane; i < n; i += kWave) {
+    int d = 0;
+    uint64_t lo = 0, hi = 0;
+    if (ok) {
+      // walk to the root; parent < child, so the walk is at most i steps
+      for (int j = i; j >= 0; j = parent[base + j]) {
+        if (j < 64) lo |= 1ull << j; else hi |= 1ull << (j - 64);
+        ++d;
+      }
+      d -= 1;
+    }
+    depth[base + i] = d;
+    position[base + i] = ok ? len + d : 0;
+    node_seq[base + i] = ok ? b : 0;
+    anc_mask[2 * (size_t)(base + i)] = lo;
+    anc_mask[2 * (size_t)(base + i) + 1] = hi;
+  }
+  if (lane == 0) status[b] = ok ? SMART_OK : SMART_ETREE;
+}
+
+__global__ __launch_bounds__(kWave) void tree_accept_kernel(
+    int batch, int max_depth, const int32_t* __restrict__ cu_nodes,
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ token,
+    const int32_t* __restrict__ target_next, int32_t* __restrict__ accept_len,
+    int32_t* __restrict__ accept_path, int32_t* __restrict__ bonus_token) {
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (b >= batch) return;
+  const int base = cu_nodes[b];
+  const int n = cu_nodes[b + 1] - base;
+  int32_t* path = accept_path + (size_t)b * (max_depth + 1);
+  for (int d = lane; d <= max_depth; d += kWave) path[d] = -1;
+  if (base < 0 || n < 1 || n > SMART_MAX_NODES) {
+    if (lane == 0) { accept_len[b] = -1; bonus_token[b] = -1; }
+    return;
+  }
+  // this lane's two nodes
+  const int i0 = lane, i1 = lane + kWave;
+  const int p0 = i0 < n ? parent[base + i0] : -2, t0 = i0 < n ? token[base + i0] : 0;
+  const int p1 = i1 < n ? parent[base + i1] : -2, t1 = i1 < n ? token[base + i1] : 0;
+  int cur = 0, len = 0;
+  while (len < max_depth) {  // at most max_depth iterations, wave-uniform
+    const int want = target_next[base + cur];
+    const uint64_t m0 = __ballot(p0 == cur && t0 == want);
+    const uint64_t m1 = __ballot(p1 == cur && t1 == want);
+    int nxt;
+    if (m0) nxt = __ffsll((unsigned long long)m0) - 1;
+    else if (m1) nxt = kWave + __ffsll((unsigned long long)m1) - 1;
+    else break;
+    cur = nxt;
+    ++len;
+    if (lane == 0) path[len] = cur;
+  }
+  if (lane == 0) {
+    path[0] = 0;
+    accept_len[b] = len;
+    bonus_token[b] = target_next[base + cur];
+  }
+}
+
+}  // namespace
+
+extern "C" int32_t tree_pack(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nodes,
+                             const int32_t* d_cu_nodes, const int32_t* d_parent,
+                             const int32_t* d_prefix_len, int32_t* d_depth, int32_t* d_position,
+                             int32_t* d_node_seq, uint64_t* d_anc_mask, int32_t* d_status) {
+  if (!ctx || batch < 0 || total_nodes < 0) return SMART_EINVAL;
+  if (!d_cu_nodes || !d_prefix_len || !d_status) return SMART_EINVAL;
+  if (total_nodes > 0 && (!d_parent || !d_depth || !d_position || !d_node_seq || !d_anc_mask))
+    return SMART_EINVAL;
+  if (batch == 0) return SMART_OK;
+  hipLaunchKernelGGL(tree_pack_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch,
+                     total_nodes, d_cu_nodes, d_parent, d_prefix_len, d_depth, d_position,
+                     d_node_seq, d_anc_mask, d_status);
+  SMART_HIP_CHECK(hipGetLastError());
+  return SMART_OK;
+}
+
+extern "C" int32_t tree_accept(smart_ctx* ctx, void* stream, int32_t batch, int32_t max_depth,
+                               const int32_t* d_cu_nodes, const int32_t* d_parent,
+                               const int32_t* d_token, const int32_t* d_target_next,
+                               int32_t* d_accept_len, int32_t* d_accept_path,
+                               int32_t* d_bonus_token) {
+  if (!ctx || batch < 0 || max_depth < 0 || max_depth > SMART_MAX_NODES) return SMART_EINVAL;
+  if (!d_cu_nodes || !d_parent || !d_token || !d_target_next || !d_accept_len || !d_accept_path ||
+      !d_bonus_token)
+    return SMART_EINVAL;
+  if (batch == 0) return SMART_OK;
+  hipLaunchKernelGGL(tree_accept_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch,
+                     max_depth, d_cu_nodes, d_parent, d_token, d_target_next, d_accept_len,
+                     d_accept_path, d_bonus_token);
+  SMART_HIP_CHECK(hipGetLastError());
+  return SMART_OK;
+}

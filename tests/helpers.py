@@ -1,0 +1,79 @@
+"""Shared test plumbing: builds trees with the oracle and with the library,
+moves workload inputs to the GPU, error metric.  No arithmetic of the method."""
+from __future__ import annotations
+
+import numpy as np
+
+from paper_2604_09731_amd import workloads as W
+
+
+def trees_from_oracle(w: W.Workload, forest=None):
+    """cu_nodes, parent, token, cand_index (numpy) chosen by the oracle."""
+    from oracle import selection as S
+    if w.tree == "binary3":
+        cu, parent, token = W.fixed_tree(w)
+        return cu, parent, token, np.zeros_like(parent)
+    forest = forest or W.make_forest(w)
+    cost = W.cost_table(w)
+    budgets = W.topn_budgets(w) if w.tree == "topn" else np.full(w.batch, w.budget, np.int32)
+    cu, parent, token, cand = [0], [], [], []
+    for b in range(w.batch):
+        lo, hi = int(forest.cand_cu[b]), int(forest.cand_cu[b + 1])
+        t = S.select_tree(forest.cand_parent[lo:hi].tolist(), forest.cand_prob[lo:hi].tolist(),
+                          forest.cand_token[lo:hi].tolist(), cost, alpha=w.alpha,
+                          max_depth=w.max_depth, budget=int(budgets[b]))
+        parent += t.parent
+        token += t.token
+        cand += t.cand_index
+        cu.append(len(parent))
+    return (np.array(cu, np.int32), np.array(parent, np.int32), np.array(token, np.int32),
+            np.array(cand, np.int32))
+
+
+def trees_from_library(w: W.Workload, forest=None):
+    from paper_2604_09731_amd import binding as B
+    if w.tree == "binary3":
+        cu, parent, token = W.fixed_tree(w)
+        return cu, parent, token, np.zeros_like(parent)
+    forest = forest or W.make_forest(w)
+    cost = W.cost_table(w)
+    if w.tree == "rule":
+        r = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob,
+                                forest.cand_token, cost, alpha=w.alpha, max_depth=w.max_depth,
+                                budget=w.budget)
+        return r["cu_nodes"], r["parent"], r["token"], r["cand_index"]
+    budgets = W.topn_budgets(w)
+    cu, parent, token, cand = [0], [], [], []
+    for b in range(w.batch):
+        lo, hi = int(forest.cand_cu[b]), int(forest.cand_cu[b + 1])
+        r = B.smart_select_tree(np.array([0, hi - lo], np.int32), forest.cand_parent[lo:hi],
+                                forest.cand_prob[lo:hi], forest.cand_token[lo:hi], cost,
+                                alpha=w.alpha, max_depth=w.max_depth, budget=int(budgets[b]))
+        parent += r["parent"].tolist()
+        token += r["token"].tolist()
+        cand += r["cand_index"].tolist()
+        cu.append(len(parent))
+    return (np.array(cu, np.int32), np.array(parent, np.int32), np.array(token, np.int32),
+            np.array(cand, np.int32))
+
+
+def torch_elems(arr: np.ndarray, dtype: str, device):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(arr))
+    if dtype == "bf16":
+        t = t.view(torch.int16).view(torch.bfloat16)
+    return t.to(device)
+
+
+def out_to_f64(t, dtype: str) -> np.ndarray:
+    import torch
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def rel_err(out: np.ndarray, ref: np.ndarray) -> float:
+    """max |out - ref| / max |ref| over the whole tensor (the stated metric)."""
+    scale = float(np.abs(ref).max())
+    return float(np.abs(out - ref).max()) / (scale if scale > 0 else 1.0)
+
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}

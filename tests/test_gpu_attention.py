@@ -1,0 +1,266 @@
+"""GPU parity of tree_verify_attention against the fp64 CPU oracle, through the
+C ABI.  Tolerances (max |out - ref| / max |ref| over the output tensor):
+1e-5 for fp32 inputs, 2e-2 for bf16 inputs with fp32 accumulation."""
+import numpy as np
+import pytest
+
+from oracle import pack_accept as PA
+from paper_2604_09731_amd import binding as B
+from paper_2604_09731_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return B.SmartTree(0)
+
+
+class Case:
+    """A workload instance on the host (numpy) and on the GPU (torch)."""
+
+    def __init__(self, w, cu, parent, inp, layout):
+        import torch
+        self.w, self.cu, self.parent, self.inp, self.layout = w, cu, parent, inp, layout
+        dev = "cuda"
+        self.q = H.torch_elems(inp.q, w.dtype, dev)
+        self.k_tree = H.torch_elems(inp.k_tree, w.dtype, dev)
+        self.v_tree = H.torch_elems(inp.v_tree, w.dtype, dev)
+        kc = H.torch_elems(inp.k_cache, w.dtype, dev)
+        vc = H.torch_elems(inp.v_cache, w.dtype, dev)
+        if layout == B.SMART_KV_INTERLEAVED:
+            kc, vc = B.interleave_kv_cache(kc, vc)
+        self.k_cache, self.v_cache = kc, vc
+        self.block_table = torch.from_numpy(inp.block_table).to(dev)
+        self.prefix_len = torch.from_numpy(inp.prefix_len).to(dev)
+        self.cu_nodes = torch.from_numpy(np.ascontiguousarray(cu)).to(dev)
+        self.parent_d = torch.from_numpy(np.ascontiguousarray(parent)).to(dev)
+
+    def run(self, lib, want_lse=True):
+        _, _, _, mask, status = lib.tree_pack(self.cu_nodes, self.parent_d, self.prefix_len)
+        assert not status.cpu().numpy().any()
+        out, lse = lib.tree_verify_attention(self.q, self.k_tree, self.v_tree, self.k_cache,
+                                             self.v_cache, self.block_table, self.prefix_len,
+                                             self.cu_nodes, mask, self.inp.scale, self.layout,
+                                             want_lse=True)
+        import torch
+        torch.cuda.synchronize()
+        return out, lse
+
+    def oracle(self, oracle_attention, sel=None):
+        i = self.inp
+        return oracle_attention.tree_attention(i.q, i.k_tree, i.v_tree, i.k_cache, i.v_cache,
+                                               i.block_table, i.prefix_len, self.cu, self.parent,
+                                               i.scale, sel=sel)
+
+
+def make_case(w, layout, prefix_len=None, trees=None, seed=None):
+    if trees is None:
+        cu, parent, _, _ = H.trees_from_library(w)
+    else:
+        cu, parent = trees
+    inp = W.make_attention_inputs(w, cu, seed=seed, prefix_len=prefix_len)
+    return Case(w, cu, parent, inp, layout)
+
+
+def check_full(lib, oracle_attention, case, tol=None):
+    out, lse = case.run(lib)
+    ref, ref_lse = case.oracle(oracle_attention)
+    err = H.rel_err(H.out_to_f64(out, case.w.dtype), ref)
+    tol = tol or H.TOL[case.w.dtype]
+    assert np.isfinite(H.out_to_f64(out, case.w.dtype)).all()
+    assert err <= tol, f"{case.w.name}: rel err {err:.3e} > {tol}"
+    lse_err = np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max()
+    assert lse_err <= (1e-4 if case.w.dtype == "f32" else 2e-2), lse_err
+    return err
+
+
+# ----- the two small fp32 configurations, both cache layouts ---------------------------
+@pytest.mark.parametrize("name", ["cfg1", "cfg1_sharp"])
+@pytest.mark.parametrize("layout", [B.SMART_KV_PLAIN, B.SMART_KV_INTERLEAVED])
+def test_fp32_tiny_configs(lib, oracle_attention, name, layout):
+    check_full(lib, oracle_attention, make_case(W.WORKLOADS[name], layout))
+
+
+# ----- bf16: small shapes spanning several tiles with ragged tails, both kernels --------
+def _ragged_case(layout, dtype="bf16", Hq=8, Hkv=2, D=128, seed=21):
+    rng = np.random.default_rng(seed)
+    sizes = [1, 3, 9, 17, 40, 2]
+    shapes = ["random", "chain", "random", "star", "random", "random"]
+    trees = [W.random_tree(n, rng, s) for n, s in zip(sizes, shapes)]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate(trees).astype(np.int32)
+    lens = np.array([0, 1, 31, 32, 33, 517], np.int32)         # empty, sub-tile, exact, ragged, multi-tile
+    w = W.Workload("ragged", dtype, len(sizes), Hq, Hkv, D, 0, 0, seed=seed)
+    return make_case(w, layout, prefix_len=lens, trees=(cu, parent), seed=seed)
+
+
+@pytest.mark.parametrize("force_general", [0, 1])
+def test_bf16_ragged_small(lib, oracle_attention, force_general):
+    lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, force_general)
+    try:
+        check_full(lib, oracle_attention, _ragged_case(B.SMART_KV_INTERLEAVED))
+        if force_general:
+            check_full(lib, oracle_attention, _ragged_case(B.SMART_KV_PLAIN))
+            check_full(lib, oracle_attention, _ragged_case(B.SMART_KV_PLAIN, D=64))
+            check_full(lib, oracle_attention, _ragged_case(B.SMART_KV_INTERLEAVED, dtype="f32", D=64))
+    finally:
+        lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 0)
+
+
+@pytest.mark.parametrize("G,Hkv", [(4, 8), (7, 4), (8, 2), (1, 4)])
+def test_bf16_group_sizes_and_big_trees(lib, oracle_attention, G, Hkv):
+    rng = np.random.default_rng(G)
+    sizes = [128, 96, 5, 33]
+    trees = [W.random_tree(n, rng, "chain" if i == 1 else "random") for i, n in enumerate(sizes)]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    w = W.Workload("groups", "bf16", 4, G * Hkv, Hkv, 128, 0, 0, seed=30 + G)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([300, 77, 1000, 64], np.int32),
+                     trees=(cu, np.concatenate(trees).astype(np.int32)))
+    check_full(lib, oracle_attention, case)
+
+
+# ----- the bf16 configurations ------------------------------------------------------------
+def test_cfg2_full(lib, oracle_attention):
+    check_full(lib, oracle_attention, make_case(W.WORKLOADS["cfg2"], B.SMART_KV_INTERLEAVED))
+
+
+@pytest.mark.parametrize("name", ["cfg3a", "cfg3b", "cfg4", "cfg5a", "cfg5b"])
+def test_reduced_configs_full_compare(lib, oracle_attention, name):
+    """Same shapes and tree recipe, fewer sequences and a shorter (still ragged,
+    multi-tile) prefix, so the oracle covers every output element."""
+    w = W.WORKLOADS[name]
+    w = w.scaled(batch=min(w.batch, 6), prefix_min=max(200, w.prefix_min // 16),
+                 prefix_max=w.prefix_max // 16 + 13, image_prefix=w.image_prefix // 16)
+    check_full(lib, oracle_attention, make_case(w, B.SMART_KV_INTERLEAVED))
+
+
+@pytest.mark.parametrize("name", ["cfg3a", "cfg3b", "cfg4", "cfg5a", "cfg5b"])
+def test_full_size_configs_sampled(lib, oracle_attention, name):
+    """Full size, in the launch configuration the benchmark times; the oracle
+    computes a seeded sample of (node, head) rows one by one, plus the row-sum
+    property on every row (lse finite, outputs finite)."""
+    w = W.WORKLOADS[name]
+    case = make_case(w, B.SMART_KV_INTERLEAVED)
+    out, lse = case.run(lib)
+    o = H.out_to_f64(out, w.dtype)
+    assert np.isfinite(o).all() and np.isfinite(lse.cpu().numpy()).all()
+    rng = np.random.default_rng(9)
+    N = int(case.cu[-1])
+    n_sel = 96
+    nodes = rng.integers(0, N, n_sel).astype(np.int32)
+    # make sure first / last node of some sequences and the largest tree are sampled
+    big = int(np.argmax(np.diff(case.cu)))
+    nodes[:4] = [0, N - 1, case.cu[big], case.cu[big + 1] - 1]
+    heads = rng.integers(0, w.num_q_heads, n_sel).astype(np.int32)
+    ref, ref_lse = case.oracle(oracle_attention, sel=(nodes, heads))
+    got = o[nodes, heads]
+    scale = np.abs(ref).max()
+    err = np.abs(got - ref).max() / scale
+    assert err <= H.TOL[w.dtype], f"{name}: rel err {err:.3e}"
+    assert np.abs(lse.cpu().numpy()[nodes, heads] - ref_lse).max() <= 2e-2
+
+
+# ----- invariances the kernel must have at any size ---------------------------------------
+def test_paging_split_and_determinism(lib, oracle_attention):
+    import torch
+    w = W.WORKLOADS["cfg3b"].scaled(batch=5, prefix_min=300, prefix_max=900)
+    case = make_case(w, B.SMART_KV_INTERLEAVED)
+    out1, lse1 = case.run(lib)
+    out2, _ = case.run(lib)
+    assert torch.equal(out1, out2)                              # determinism
+    # paging invariance: permute physical blocks and the table -> bit-identical
+    nb = case.k_cache.shape[0]
+    perm = torch.randperm(nb, device="cuda", generator=torch.Generator("cuda").manual_seed(1))
+    k2 = torch.empty_like(case.k_cache)
+    v2 = torch.empty_like(case.v_cache)
+    k2[perm] = case.k_cache
+    v2[perm] = case.v_cache
+    bt = case.block_table.clone()
+    valid = bt >= 0
+    bt[valid] = perm[bt[valid].long()].int()
+    keep = (case.k_cache, case.v_cache, case.block_table)
+    case.k_cache, case.v_cache, case.block_table = k2, v2, bt
+    out3, _ = case.run(lib)
+    case.k_cache, case.v_cache, case.block_table = keep
+    assert torch.equal(out1, out3)
+    # split invariance: any number of workers gives the same result up to fp32 merge order
+    ref = out1.float()
+    for workers in (1, 7, 64, 4096):
+        lib.set_option(B.SMART_OPT_TVA_WORKERS, workers)
+        try:
+            o, l = case.run(lib)
+        finally:
+            lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
+        assert (o.float() - ref).abs().max().item() <= 2 ** -7 * ref.abs().max().item()
+        assert (l - lse1).abs().max().item() <= 1e-4
+    # matrix-core path and general kernel agree to bf16 output rounding
+    lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 1)
+    try:
+        og, _ = case.run(lib)
+    finally:
+        lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 0)
+    assert (og.float() - ref).abs().max().item() <= 2e-2 * ref.abs().max().item()
+
+
+def test_tree_masking_perturbation_and_relabelling(lib, oracle_attention):
+    import torch
+    rng = np.random.default_rng(5)
+    n = 24
+    tree = W.random_tree(n, rng)
+    w = W.Workload("mask", "bf16", 1, 8, 2, 128, 0, 0, seed=41)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([75], np.int32),
+                     trees=(np.array([0, n], np.int32), tree))
+    out, _ = case.run(lib)
+    anc = []
+    for i in range(n):
+        s, j = set(), i
+        while j >= 0:
+            s.add(j)
+            j = int(tree[j])
+        anc.append(s)
+    for j in (3, 11, 23):
+        kt, vt = case.k_tree.clone(), case.v_tree.clone()
+        case.k_tree[j] = -case.k_tree[j] * 2
+        case.v_tree[j] = case.v_tree[j] + 3
+        out2, _ = case.run(lib)
+        case.k_tree, case.v_tree = kt, vt
+        for i in range(n):
+            same = torch.equal(out[i], out2[i])
+            assert same == (j not in anc[i]), (i, j)
+    # topological relabelling permutes the outputs
+    placed, order = set(), []
+    while len(order) < n:
+        ready = [i for i in range(n) if i not in placed and (tree[i] < 0 or tree[i] in placed)]
+        pick = int(rng.choice(ready))
+        placed.add(pick)
+        order.append(pick)
+    new_of_old = {o: i for i, o in enumerate(order)}
+    tree2 = np.array([-1 if tree[o] < 0 else new_of_old[int(tree[o])] for o in order], np.int32)
+    idx = torch.tensor(order, device="cuda")
+    case2 = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([75], np.int32),
+                      trees=(np.array([0, n], np.int32), tree2))
+    case2.q, case2.k_tree, case2.v_tree = case.q[idx], case.k_tree[idx], case.v_tree[idx]
+    out3, _ = case2.run(lib)
+    assert (out3.float() - out[idx].float()).abs().max().item() <= 2 ** -7 * out.float().abs().max().item()
+
+
+def test_chain_single_node_and_empty_batch(lib, oracle_attention):
+    import torch
+    w = W.Workload("chain", "bf16", 3, 32, 8, 128, 0, 0, seed=43)
+    trees = [W.random_tree(1, None, "chain"), W.random_tree(20, None, "chain"), W.random_tree(1, None, "chain")]
+    cu = np.array([0, 1, 21, 22], np.int32)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([130, 64, 0], np.int32),
+                     trees=(cu, np.concatenate(trees).astype(np.int32)))
+    check_full(lib, oracle_attention, case)
+    # empty batch / no nodes: nothing launched, nothing written
+    empty = torch.empty((0, 32, 128), dtype=torch.bfloat16, device="cuda")
+    out = lib.tree_verify_attention(empty, empty[:, :8], empty[:, :8], case.k_cache, case.v_cache,
+                                    case.block_table[:0], case.prefix_len[:0],
+                                    torch.zeros(1, dtype=torch.int32, device="cuda"),
+                                    torch.empty((0, 2), dtype=torch.int64, device="cuda"),
+                                    0.1, B.SMART_KV_INTERLEAVED)
+    assert out.shape[0] == 0

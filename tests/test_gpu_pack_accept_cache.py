@@ -1,0 +1,153 @@
+"""GPU parity (bit-exact) of tree_pack, tree_accept and kv_cache_write against
+the CPU oracle, called through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import kv_layout as KL
+from oracle import pack_accept as PA
+from paper_2604_09731_amd import binding as B
+from paper_2604_09731_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return B.SmartTree(0)
+
+
+def _dev(a, dtype=None):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def _random_batch(seed, sizes, shapes=None):
+    rng = np.random.default_rng(seed)
+    ts = [W.random_tree(n, rng, (shapes or ["random"] * len(sizes))[i]) for i, n in enumerate(sizes)]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    return cu, np.concatenate(ts).astype(np.int32), rng
+
+
+def _mask_words(mask):
+    lo = np.array([m[0] for m in mask], dtype=np.uint64)
+    hi = np.array([m[1] for m in mask], dtype=np.uint64)
+    return np.stack([lo, hi], 1)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_tree_pack_bit_exact(lib, seed):
+    sizes = [1, 2, 15, 63, 64, 65, 127, 128, 40, 7] + list(np.random.default_rng(seed).integers(1, 129, 40))
+    shapes = ["random"] * len(sizes)
+    shapes[5], shapes[7], shapes[8] = "chain", "chain", "star"
+    cu, parent, rng = _random_batch(seed, sizes, shapes)
+    plen = rng.integers(0, 20000, len(sizes)).astype(np.int32)
+    depth, pos, seq, mask = PA.pack(cu, parent, plen)
+    d, p, s, m, st = lib.tree_pack(_dev(cu), _dev(parent), _dev(plen))
+    assert st.cpu().numpy().tolist() == [0] * len(sizes)
+    assert d.cpu().numpy().tolist() == depth
+    assert p.cpu().numpy().tolist() == pos
+    assert s.cpu().numpy().tolist() == seq
+    assert np.array_equal(m.cpu().numpy().view(np.uint64), _mask_words(mask))
+
+
+def test_tree_pack_workload_trees_and_malformed(lib):
+    w = W.WORKLOADS["cfg4"]
+    cu, parent, token, _ = H.trees_from_library(w)
+    plen = W.make_prefix_len(w)
+    depth, pos, seq, mask = PA.pack(cu, parent, plen)
+    d, p, s, m, st = lib.tree_pack(_dev(cu), _dev(parent), _dev(plen))
+    assert d.cpu().numpy().tolist() == depth and p.cpu().numpy().tolist() == pos
+    assert np.array_equal(m.cpu().numpy().view(np.uint64), _mask_words(mask))
+    # malformed sequences are flagged and zero-filled; the others are untouched
+    cu2 = np.array([0, 3, 6, 6, 10, 140], np.int32)         # seq 2 empty, seq 4 has 130 nodes
+    par2 = np.concatenate([[-1, 0, 1], [-1, 2, 0], [0, 0, 1, 2], [-1] + list(range(129))]).astype(np.int32)
+    plen2 = np.array([5, 6, 7, 8, 9], np.int32)
+    d, p, s, m, st = lib.tree_pack(_dev(cu2), _dev(par2), _dev(plen2))
+    assert st.cpu().numpy().tolist() == [0, B.SMART_ETREE, B.SMART_ETREE, B.SMART_ETREE, B.SMART_ETREE]
+    assert d.cpu().numpy()[:3].tolist() == [0, 1, 2]
+    assert not m.cpu().numpy()[3:].any() and not d.cpu().numpy()[3:].any()
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_tree_accept_bit_exact(lib, seed):
+    sizes = [1, 5, 12, 30, 64, 65, 128, 100]
+    cu, parent, rng = _random_batch(seed, sizes, ["random"] * 6 + ["chain", "random"])
+    N = cu[-1]
+    token = rng.integers(0, 6, N).astype(np.int32)
+    target = rng.integers(0, 6, N).astype(np.int32)
+    for b in range(len(sizes)):
+        for i in range(1, sizes[b]):
+            if rng.random() < 0.7:
+                target[cu[b] + parent[cu[b] + i]] = token[cu[b] + i]
+    for max_depth in (128, 8, 0):
+        alen, paths, bonus = PA.accept(cu, parent, token, target, max_depth)
+        a, p, bo = lib.tree_accept(_dev(cu), _dev(parent), _dev(token), _dev(target), max_depth)
+        assert a.cpu().numpy().tolist() == alen
+        assert p.cpu().numpy().tolist() == paths
+        assert bo.cpu().numpy().tolist() == bonus
+
+
+def test_tree_accept_on_workload_and_expected_length(lib):
+    """Monte-Carlo form of the acceptance-length identity: with acceptance
+    probability = draft probability, mean(accept_len + 1) over many target
+    draws approaches sum_u P(u) (the L that selection reports)."""
+    w = W.WORKLOADS["cfg2"].scaled(batch=64)
+    forest = W.make_forest(w)
+    r = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token,
+                            W.cost_table(w), alpha=w.alpha, max_depth=w.max_depth, budget=w.budget)
+    cu, parent, token, cand = r["cu_nodes"], r["parent"], r["token"], r["cand_index"]
+    dcu, dpar, dtok = _dev(cu), _dev(parent), _dev(token)
+    emitted = np.zeros(w.batch)
+    trials = 300
+    for trial in range(trials):
+        target = W.make_target_next(forest, cu, cand, seed=5000 + trial)
+        a, p, bo = lib.tree_accept(dcu, dpar, dtok, _dev(target), w.max_depth)
+        if trial < 3:
+            alen, paths, bonus = PA.accept(cu, parent, token, target, w.max_depth)
+            assert a.cpu().numpy().tolist() == alen and bo.cpu().numpy().tolist() == bonus
+            assert p.cpu().numpy().tolist() == paths
+        emitted += a.cpu().numpy() + 1
+    mean = emitted.sum() / (trials * w.batch)
+    expect = r["L"].mean()
+    # per-draw std of emitted tokens is < 3; 19200 draws -> 3 sigma < 0.07
+    assert abs(mean - expect) < 0.07, (mean, expect)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("D", [64, 128])
+def test_kv_cache_write_layouts(lib, dtype, D):
+    import torch
+    rng = np.random.default_rng(3)
+    nb, Hkv, bs, n = 9, 3, 16, 70
+    w = W.Workload("t", dtype, 1, Hkv, Hkv, D, 0, 0)
+    k_src = W._normal(1, 1, (n, Hkv, D), 1.0, dtype)
+    v_src = W._normal(1, 2, (n, Hkv, D), 1.0, dtype)
+    slots = rng.permutation(nb * bs)[:n].astype(np.int64)
+    slots[5] = -1                                            # skipped
+    zero = np.zeros((nb, Hkv, bs, D), k_src.dtype)
+    plain_k, plain_v = zero.copy(), zero.copy()
+    for t in range(n):
+        if slots[t] >= 0:
+            plain_k[slots[t] // bs, :, slots[t] % bs] = k_src[t]
+            plain_v[slots[t] // bs, :, slots[t] % bs] = v_src[t]
+    tk = H.torch_elems(k_src, dtype, "cuda")
+    tv = H.torch_elems(v_src, dtype, "cuda")
+    raw = lambda t: t.cpu().view(torch.int16 if dtype == "bf16" else torch.float32).numpy().view(k_src.dtype)
+    for layout in (B.SMART_KV_PLAIN, B.SMART_KV_INTERLEAVED):
+        kc = torch.zeros((nb, Hkv, bs * D), dtype=tk.dtype, device="cuda")
+        vc = torch.zeros_like(kc)
+        lib.kv_cache_write(tk, tv, _dev(slots), kc, vc, layout, bs, nb, Hkv * bs * D, bs * D, D)
+        if layout == B.SMART_KV_PLAIN:
+            assert np.array_equal(raw(kc).reshape(plain_k.shape), plain_k)
+            assert np.array_equal(raw(vc).reshape(plain_v.shape), plain_v)
+        else:
+            assert np.array_equal(raw(kc), KL.interleave_plain_cache(plain_k, "k"))
+            assert np.array_equal(raw(vc), KL.interleave_plain_cache(plain_v, "v"))
+            # the binding's layout converter moves data the same way
+            ik, iv = B.interleave_kv_cache(H.torch_elems(plain_k, dtype, "cuda"),
+                                           H.torch_elems(plain_v, dtype, "cuda"))
+            assert np.array_equal(raw(ik).reshape(nb, Hkv, -1), raw(kc))
+            assert np.array_equal(raw(iv).reshape(nb, Hkv, -1), raw(vc))

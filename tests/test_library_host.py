@@ -1,0 +1,160 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared
+symbol, rejects bad arguments before touching a device, and its host-side
+selection is bit-exact against the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import selection as S
+from paper_2604_09731_amd import binding as B
+from paper_2604_09731_amd import workloads as W
+from tests import helpers as H
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "smart_tree.h")).read()
+    declared = set(re.findall(r"^(?:int32_t|const char\*)\s+(\w+)\s*\(", header, flags=re.M))
+    assert declared == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B._strerror(0) == "ok" and "tree" in B._strerror(B.SMART_ETREE)
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3a", "cfg3b", "cfg4", "cfg5a", "cfg5b"])
+def test_selection_bit_exact_on_workloads(name):
+    w = W.WORKLOADS[name]
+    w = w.scaled(batch=min(w.batch, 12))
+    forest = W.make_forest(w)
+    a = H.trees_from_oracle(w, forest)
+    b = H.trees_from_library(w, forest)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("schedule", [B.SMART_BEST_FIRST, B.SMART_LAYERWISE])
+@pytest.mark.parametrize("dilution", [B.SMART_DILUTION_NONE, B.SMART_DILUTION_PATH_MEAN])
+@pytest.mark.parametrize("alpha", [1.0, 0.8, 0.55])
+def test_selection_all_modes_bit_exact_including_L_R_pathprob(schedule, dilution, alpha):
+    for wname, budget, depth in [("cfg2", 128, 8), ("cfg4", 96, 6), ("cfg2", 17, 3), ("cfg4", 1, 6)]:
+        w = W.WORKLOADS[wname].scaled(batch=5)
+        f = W.make_forest(w, seed=77 + budget)
+        cost = W.cost_table(w, n_max=budget)
+        dcost = None
+        r = B.smart_select_tree(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, dcost,
+                                alpha=alpha, max_depth=depth, budget=budget, schedule=schedule,
+                                dilution=dilution)
+        trees = S.select_batch(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, dcost,
+                               alpha=alpha, max_depth=depth, budget=budget, schedule=schedule,
+                               dilution=dilution)
+        for b, t in enumerate(trees):
+            lo, hi = r["cu_nodes"][b], r["cu_nodes"][b + 1]
+            assert r["parent"][lo:hi].tolist() == t.parent
+            assert r["token"][lo:hi].tolist() == t.token
+            assert r["cand_index"][lo:hi].tolist() == t.cand_index
+            assert r["pathprob"][lo:hi].tolist() == t.pathprob      # bit-exact doubles
+            assert r["L"][b] == t.L and r["R"][b] == t.R
+
+
+def test_selection_with_derivative_table_and_knee_costs():
+    w = W.WORKLOADS["cfg3a"].scaled(batch=6)
+    f = W.make_forest(w)
+    cost = W.cost_table(w)
+    dcost = np.gradient(cost)[: w.budget + 1] * 0.9
+    r = B.smart_select_tree(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, dcost,
+                            alpha=0.9, max_depth=8, budget=w.budget)
+    trees = S.select_batch(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, dcost,
+                           alpha=0.9, max_depth=8, budget=w.budget)
+    assert r["cand_index"].tolist() == sum((t.cand_index for t in trees), [])
+
+
+def test_selection_error_paths():
+    w = W.WORKLOADS["cfg2"].scaled(batch=2)
+    f = W.make_forest(w)
+    cost = W.cost_table(w)
+    ok = dict(alpha=0.8, max_depth=8, budget=64)
+    call = lambda **kw: B.smart_select_tree(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost,
+                                            **{**ok, **kw})
+    for bad in (dict(alpha=0.0), dict(alpha=1.5), dict(alpha=float("nan")), dict(budget=0),
+                dict(budget=129), dict(max_depth=-1), dict(schedule=7), dict(dilution=-1)):
+        if bad.get("budget") == 129:
+            with pytest.raises((B.SmartError, ValueError)):
+                call(**bad)
+            continue
+        with pytest.raises(B.SmartError) as e:
+            call(**bad)
+        assert e.value.code == B.SMART_EINVAL
+    with pytest.raises(B.SmartError) as e:
+        call(out_cap=10)
+    assert e.value.code == B.SMART_ECAP
+    bad_parent = f.cand_parent.copy()
+    bad_parent[5] = 9
+    with pytest.raises(B.SmartError) as e:
+        B.smart_select_tree(f.cand_cu, bad_parent, f.cand_prob, f.cand_token, cost, **ok)
+    assert e.value.code == B.SMART_ETREE
+    bad_prob = f.cand_prob.copy()
+    bad_prob[3] = 1.5
+    with pytest.raises(B.SmartError) as e:
+        B.smart_select_tree(f.cand_cu, f.cand_parent, bad_prob, f.cand_token, cost, **ok)
+    assert e.value.code == B.SMART_ETREE
+    two_roots = f.cand_parent.copy()
+    two_roots[1] = -1
+    with pytest.raises(B.SmartError) as e:
+        B.smart_select_tree(f.cand_cu, two_roots, f.cand_prob, f.cand_token, cost, **ok)
+    assert e.value.code == B.SMART_ETREE
+    # empty batch is fine
+    r = B.smart_select_tree(np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0), np.zeros(0, np.int32),
+                            cost, **ok)
+    assert r["cu_nodes"].tolist() == [0]
+
+
+def test_device_entry_points_validate_on_the_host_first():
+    """Every case below is invalid, so each call must return its error code
+    before it looks at the context or the device (there is no GPU here): a
+    zeroed buffer stands in for the context."""
+    lib = B._lib()
+    fake = ctypes.create_string_buffer(512)
+    ctx = ctypes.cast(fake, ctypes.c_void_p)
+    one = ctypes.create_string_buffer(64)
+    ptr = ctypes.cast(one, ctypes.c_void_p)
+    assert lib.tree_pack(None, None, 1, 1, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert lib.tree_pack(ctx, None, -1, 1, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert lib.tree_pack(ctx, None, 1, 1, None, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert lib.tree_pack(ctx, None, 1, 1, ptr, ptr, ptr, ptr, ptr, ptr, None, ptr) == B.SMART_EINVAL
+    assert lib.tree_accept(ctx, None, 1, -1, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert lib.tree_accept(ctx, None, 1, 8, ptr, None, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert lib.tree_accept(None, None, 1, 8, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert lib.kv_cache_write(ctx, None, 5, 0, 1, 8, 128, 16, 4, ptr, ptr, ptr, ptr, ptr, 16384, 2048, 128) == B.SMART_EINVAL
+    assert lib.kv_cache_write(ctx, None, 1, 1, 1, 8, 128, 12, 4, ptr, ptr, ptr, ptr, ptr, 16384, 2048, 128) == B.SMART_EINVAL
+    assert lib.kv_cache_write(ctx, None, 1, 1, 1, 8, 128, 16, 4, ptr, ptr, ptr, ptr, ptr, 16384, 100, 128) == B.SMART_EINVAL
+    assert lib.smart_set_option(None, 1, 0) == B.SMART_EINVAL
+    assert lib.smart_create(None, 0) == B.SMART_EINVAL
+    assert lib.smart_destroy(None) == B.SMART_EINVAL
+
+    def tva(**kw):
+        p = B.TvaParams()
+        base = dict(dtype=1, kv_layout=1, batch=1, total_nodes=1, num_q_heads=32, num_kv_heads=8,
+                    head_dim=128, block_size=16, max_blocks_per_seq=4, num_blocks=4,
+                    softmax_scale=0.088, cache_block_stride=8 * 2048, cache_head_stride=2048,
+                    cache_token_stride=128)
+        base.update(kw)
+        for k, v in base.items():
+            setattr(p, k, v)
+        for f in ("d_q", "d_k_tree", "d_v_tree", "d_k_cache", "d_v_cache", "d_block_table",
+                  "d_prefix_len", "d_cu_nodes", "d_anc_mask", "d_out"):
+            if f not in kw:
+                setattr(p, f, ptr.value)
+        return lib.tree_verify_attention(ctx, None, ctypes.byref(p))
+
+    assert lib.tree_verify_attention(None, None, None) == B.SMART_EINVAL
+    for bad in (dict(dtype=3), dict(kv_layout=2), dict(num_q_heads=30), dict(head_dim=96),
+                dict(block_size=12), dict(block_size=128), dict(softmax_scale=0.0),
+                dict(softmax_scale=float("nan")), dict(cache_head_stride=100),
+                dict(cache_block_stride=1024), dict(batch=-1), dict(d_q=None), dict(d_anc_mask=None),
+                dict(d_k_cache=None), dict(kv_layout=0, cache_token_stride=64), dict(num_blocks=0)):
+        assert tva(**bad) == B.SMART_EINVAL, bad
