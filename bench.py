@@ -1,0 +1,350 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input:
+  smart_select_tree (host) -> tree CSR to the GPU -> tree_pack ->
+  tree_verify_attention -> tree_accept.
+K steps are timed back to back (the device calls are asynchronous, so the host
+side of step i+1 overlaps the device side of step i, as it would in a serving
+loop); every input (draft distributions on the host, Q / K / V / paged cache /
+block table / target tokens on the GPU) is resident before the clock starts.
+
+Prints ONE JSON line.  `value` = microseconds per step.  `roofline` is for the
+dominant kernel (the prefix-streaming attention kernel), timed with HIP events
+the library records around it on the launch stream during the timed steps.
+`cpu_baseline` is the CPU oracle's attention on a bounded sample of the same
+workload, extrapolated to a full step.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs scaled by a plain copy of known size (see profiles/); bytes.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="cfg3a")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workers", type=int, default=0, help="override the number of split-KV workers (0 = automatic)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+            f"--gpus {args.gpus} is not supported.")
+        sys.exit(2)
+
+    import torch
+    from paper_2604_09731_amd import binding as B
+    from paper_2604_09731_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.workload]
+    lib = B.SmartTree(0)
+    L = B._lib()
+
+    # ---------------- inputs (all resident before timing) ----------------
+    t_setup = time.time()
+    forest = W.make_forest(w) if w.tree != "binary3" else None
+    cost = W.cost_table(w) if forest is not None else None
+    Bsz = w.batch
+    cap = Bsz * B.SMART_MAX_NODES
+
+    # pinned staging: [cu_nodes (B+1) | parent (cap) | token (cap)] x 2, plus host-only outputs
+    n_stage = (Bsz + 1) + 2 * cap
+    stage = [torch.empty(n_stage, dtype=torch.int32).pin_memory() for _ in range(2)]
+    d_stage = [torch.empty(n_stage, dtype=torch.int32, device=dev) for _ in range(2)]
+    h_cand = np.zeros(cap, np.int32)
+    h_pp = np.zeros(cap, np.float64)
+    h_L = np.zeros(Bsz, np.float64)
+    h_R = np.zeros(Bsz, np.float64)
+
+    budgets = W.topn_budgets(w) if w.tree == "topn" else None
+
+    def make_select(buf):
+        """Pre-marshalled smart_select_tree call(s) writing straight into a pinned buffer."""
+        a = buf.numpy()
+        cu, par, tok = a[:Bsz + 1], a[Bsz + 1:Bsz + 1 + cap], a[Bsz + 1 + cap:]
+        p = lambda x: ctypes.c_void_p(x.ctypes.data)
+        if w.tree == "rule":
+            argv = (Bsz, p(forest.cand_cu), p(forest.cand_parent), p(forest.cand_prob),
+                    p(forest.cand_token), p(cost), None, float(w.alpha), w.max_depth, w.budget,
+                    B.SMART_BEST_FIRST, B.SMART_DILUTION_NONE, p(cu), p(par), p(tok), p(h_cand),
+                    p(h_pp), cap, p(h_L), p(h_R))
+
+            def run():
+                rc = L.smart_select_tree(*argv)
+                if rc:
+                    raise B.SmartError(rc, "smart_select_tree")
+            return run
+        if w.tree == "topn":
+            # per-sequence budgets: one call per sequence, outputs appended
+            one_cu = np.zeros(2, np.int32)
+            cc = [np.array([0, forest.cand_cu[b + 1] - forest.cand_cu[b]], np.int32) for b in range(Bsz)]
+
+            def run():
+                off = 0
+                cu[0] = 0
+                for b in range(Bsz):
+                    lo = int(forest.cand_cu[b])
+                    rc = L.smart_select_tree(
+                        1, p(cc[b]), p(forest.cand_parent[lo:]), p(forest.cand_prob[lo:]),
+                        p(forest.cand_token[lo:]), p(cost), None, float(w.alpha), w.max_depth,
+                        int(budgets[b]), B.SMART_BEST_FIRST, B.SMART_DILUTION_NONE, p(one_cu),
+                        p(par[off:]), p(tok[off:]), p(h_cand[off:]), p(h_pp[off:]), cap - off,
+                        p(h_L[b:]), p(h_R[b:]))
+                    if rc:
+                        raise B.SmartError(rc, "smart_select_tree")
+                    off += int(one_cu[1])
+                    cu[b + 1] = off
+            return run
+
+        fcu, fpar, ftok = W.fixed_tree(w)
+
+        def run():
+            cu[:] = fcu
+            par[:len(fpar)] = fpar
+            tok[:len(ftok)] = ftok
+        return run
+
+    select = [make_select(stage[0]), make_select(stage[1])]
+    select[0]()
+    a0 = stage[0].numpy()
+    cu_nodes = a0[:Bsz + 1].copy()
+    N = int(cu_nodes[-1])
+    parent = a0[Bsz + 1:Bsz + 1 + N].copy()
+    sizes = np.diff(cu_nodes)
+
+    inp = W.make_attention_inputs(w, cu_nodes)
+    H_dtype = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def elems(x):
+        t = torch.from_numpy(np.ascontiguousarray(x))
+        if w.dtype == "bf16":
+            t = t.view(torch.int16).view(torch.bfloat16)
+        return t.to(dev)
+
+    q, k_tree, v_tree = elems(inp.q), elems(inp.k_tree), elems(inp.v_tree)
+    kc, vc = B.interleave_kv_cache(elems(inp.k_cache), elems(inp.v_cache))
+    block_table = torch.from_numpy(inp.block_table).to(dev)
+    prefix_len = torch.from_numpy(inp.prefix_len).to(dev)
+    if forest is not None:
+        target_np = W.make_target_next(forest, cu_nodes, h_cand[:N], seed=w.seed + 1)
+    else:
+        target_np = np.zeros(N, np.int32)
+    target_next = torch.from_numpy(target_np).to(dev)
+    out = torch.empty_like(q)
+    depth = torch.empty(N, dtype=torch.int32, device=dev)
+    position = torch.empty_like(depth)
+    node_seq = torch.empty_like(depth)
+    anc_mask = torch.empty((N, 2), dtype=torch.int64, device=dev)
+    status = torch.empty(Bsz, dtype=torch.int32, device=dev)
+    accept_len = torch.empty(Bsz, dtype=torch.int32, device=dev)
+    accept_path = torch.empty((Bsz, w.max_depth + 1), dtype=torch.int32, device=dev)
+    bonus = torch.empty(Bsz, dtype=torch.int32, device=dev)
+    if args.workers:
+        lib.set_option(B.SMART_OPT_TVA_WORKERS, args.workers)
+    lib.reserve(Bsz, cap, w.num_q_heads, w.num_kv_heads)
+    torch.cuda.synchronize()
+    log(f"[bench] {w.name}: batch {Bsz}, {N} tree nodes (min/median/max per sequence "
+        f"{sizes.min()}/{int(np.median(sizes))}/{sizes.max()}), prefix {inp.prefix_len.min()}..{inp.prefix_len.max()}, "
+        f"setup {time.time() - t_setup:.1f}s")
+
+    # ---------------- pre-marshalled device calls ----------------
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ctx = lib._h
+    vp = lambda t: ctypes.c_void_p(t.data_ptr())
+
+    stage_np = [stage[0].numpy(), stage[1].numpy()]
+
+    def device_calls(ds, ds_index):
+        d_cu, d_par, d_tok = ds[:Bsz + 1], ds[Bsz + 1:Bsz + 1 + cap], ds[Bsz + 1 + cap:]
+        pack_args = (ctx, stream, Bsz, N, vp(d_cu), vp(d_par), vp(prefix_len), vp(depth), vp(position),
+                     vp(node_seq), vp(anc_mask), vp(status))
+        P = B.TvaParams()
+        P.dtype = B.SMART_BF16 if w.dtype == "bf16" else B.SMART_F32
+        P.kv_layout = B.SMART_KV_INTERLEAVED
+        P.batch, P.total_nodes = Bsz, N
+        P.num_q_heads, P.num_kv_heads, P.head_dim = w.num_q_heads, w.num_kv_heads, w.head_dim
+        P.block_size, P.max_blocks_per_seq, P.num_blocks = 16, block_table.shape[1], kc.shape[0]
+        P.softmax_scale = inp.scale
+        P.d_q, P.d_k_tree, P.d_v_tree = q.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr()
+        P.d_k_cache, P.d_v_cache = kc.data_ptr(), vc.data_ptr()
+        P.cache_block_stride, P.cache_head_stride, P.cache_token_stride = kc.stride(0), kc.stride(1), w.head_dim
+        P.d_block_table, P.d_prefix_len = block_table.data_ptr(), prefix_len.data_ptr()
+        P.d_cu_nodes, P.d_anc_mask = d_cu.data_ptr(), anc_mask.data_ptr()
+        P.d_out, P.d_lse = out.data_ptr(), None
+        P.h_cu_nodes = stage_np[ds_index][:Bsz + 1].ctypes.data   # selection wrote it on the host
+        acc_args = (ctx, stream, Bsz, w.max_depth, vp(d_cu), vp(d_par), vp(d_tok), vp(target_next),
+                    vp(accept_len), vp(accept_path), vp(bonus))
+        return pack_args, P, acc_args
+
+    calls = [device_calls(d_stage[0], 0), device_calls(d_stage[1], 1)]
+    n_copy = (Bsz + 1) + 2 * cap
+
+    def step(i):
+        s = i & 1
+        select[s]()                                              # a1: host selection
+        d_stage[s].copy_(stage[s], non_blocking=True)            # tree CSR to the GPU
+        pack_args, P, acc_args = calls[s]
+        rc = L.tree_pack(*pack_args)                             # a2
+        rc = rc or L.tree_verify_attention(ctx, stream, ctypes.byref(P))   # a3 + a4
+        rc = rc or L.tree_accept(*acc_args)                      # a5
+        if rc:
+            raise B.SmartError(rc, "verify step")
+
+    # the staging buffers alternate, so a buffer is rewritten by the host two steps after its
+    # copy was enqueued; guard that with an event per buffer
+    copy_done = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def guarded_step(i):
+        s = i & 1
+        copy_done[s].synchronize()
+        step(i)
+        copy_done[s].record()
+
+    copy_done[0].record()
+    copy_done[1].record()
+    for i in range(args.warmup):
+        guarded_step(i)
+    torch.cuda.synchronize()
+
+    lib.set_option(B.SMART_OPT_TVA_PROFILE, max(1, args.steps))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        guarded_step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms = lib.profile_read()
+    lib.set_option(B.SMART_OPT_TVA_PROFILE, 0)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    assert len(kernel_ms) == args.steps
+    dom_ms = float(np.mean(kernel_ms))
+    assert not status.cpu().numpy().any()
+
+    # ---------------- breakdown (untimed region, device-side events) ----------------
+    def time_device(fn, reps=100):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    pack_args, P, acc_args = calls[0]
+    att_us = time_device(lambda: L.tree_verify_attention(ctx, stream, ctypes.byref(P)))
+    pack_us = time_device(lambda: L.tree_pack(*pack_args))
+    acc_us = time_device(lambda: L.tree_accept(*acc_args))
+    th0 = time.perf_counter()
+    for _ in range(50):
+        select[0]()
+    sel_us = (time.perf_counter() - th0) * 1e6 / 50
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB write
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # ---------------- algorithmic work ----------------
+    from paper_2604_09731_amd.workloads import algorithmic_work
+    dep = depth.cpu().numpy()
+    work = algorithmic_work(w, inp.prefix_len, cu_nodes, int((dep + 1).sum()))
+    e = 2 if w.dtype == "bf16" else 4
+    dom_bytes = work["kv_bytes"] + N * w.num_q_heads * w.head_dim * e   # prefix K/V once + Q
+    achieved_gbs = dom_bytes / (dom_ms * 1e-3) / 1e9
+    tflops = work["flops"] / (att_us * 1e-6) / 1e12
+    result = {
+        "metric": "tree-verify us/step (select + pack + attention + accept), bs=%d, prefix %d..%d, %d/%d heads x %d"
+                  % (Bsz, w.prefix_min, w.prefix_max, w.num_q_heads, w.num_kv_heads, w.head_dim),
+        "value": round(ms_per_step * 1e3, 2),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": Bsz, "tree_nodes_total": N,
+                   "tree_nodes_min_median_max": [int(sizes.min()), int(np.median(sizes)), int(sizes.max())],
+                   "prefix_len_min_max": [int(inp.prefix_len.min()), int(inp.prefix_len.max())],
+                   "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
+                   "block_size": 16, "kv_layout": "interleaved"},
+        "breakdown_us": {"select_host": round(sel_us, 1), "tree_pack": round(pack_us, 2),
+                         "tree_verify_attention": round(att_us, 2), "tree_accept": round(acc_us, 2)},
+        "attended_tokens_per_s": round(work["attended_tokens"] / (att_us * 1e-6), 1),
+        "attention_tflops": round(tflops, 2),
+        "attention_mfma_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "roofline": {"bound": "hbm", "kernel": "tva_prefix_kernel",
+                     "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+                     "kernel_us": round(dom_ms * 1e3, 2), "algorithmic_bytes": int(dom_bytes),
+                     "traffic": MEASURED_TRAFFIC.get(w.name)},
+    }
+
+    # ---------------- CPU baseline: the oracle, bounded sample ----------------
+    if not args.no_cpu_baseline:
+        from oracle import attention as OA
+        rng = np.random.default_rng(w.seed)
+        total_rows = N * w.num_q_heads
+
+        def run_sample(n_rows):
+            nodes = rng.integers(0, N, n_rows).astype(np.int32)
+            heads = rng.integers(0, w.num_q_heads, n_rows).astype(np.int32)
+            t = time.perf_counter()
+            OA.tree_attention(inp.q, inp.k_tree, inp.v_tree, inp.k_cache, inp.v_cache, inp.block_table,
+                              inp.prefix_len, cu_nodes, parent, inp.scale, sel=(nodes, heads))
+            return time.perf_counter() - t
+
+        threads = OA.num_threads()
+        pilot_rows = min(total_rows, 4 * threads)
+        pilot = run_sample(pilot_rows)
+        n_rows = int(min(total_rows, max(pilot_rows, args.cpu_seconds / max(pilot / pilot_rows, 1e-9))))
+        secs = run_sample(n_rows)
+        full_us = secs / n_rows * total_rows * 1e6
+        result["cpu_baseline"] = {
+            "value": round(full_us, 1), "unit": "us/step", "cores": threads, "kind": "oracle",
+            "sample": f"fp64 oracle attention on {n_rows} of {total_rows} (node, head) rows of this workload, "
+                      f"{secs:.1f} s measured, extrapolated by row count (attention only)"}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -82,7 +82,10 @@ enum { SMART_DILUTION_NONE = 0, SMART_DILUTION_PATH_MEAN = 1 };
 /* smart_set_option keys */
 enum {
   SMART_OPT_TVA_WORKERS = 1,      /* number of split-KV workers (waves); 0 = automatic   */
-  SMART_OPT_TVA_FORCE_GENERAL = 2 /* 1 = always run the general (non matrix-core) kernel */
+  SMART_OPT_TVA_FORCE_GENERAL = 2, /* 1 = always run the general (non matrix-core) kernel */
+  SMART_OPT_TVA_PROFILE = 3        /* n > 0: keep n pairs of HIP events and record one pair
+                                      around the dominant attention kernel of every
+                                      tree_verify_attention call (ring); 0 = off (default) */
 };
 
 typedef struct smart_ctx smart_ctx;
@@ -102,6 +105,13 @@ int32_t smart_destroy(smart_ctx* ctx);
 int32_t smart_reserve(smart_ctx* ctx, int32_t max_batch, int32_t max_total_nodes,
                       int32_t max_q_heads, int32_t max_kv_heads);
 int32_t smart_set_option(smart_ctx* ctx, int32_t key, int64_t value);
+/* Profiling read-out (see SMART_OPT_TVA_PROFILE).  The caller must have
+ * synchronised the stream(s) the recorded calls ran on.  Writes the duration in
+ * milliseconds of the dominant attention kernel (the prefix-streaming kernel of
+ * the matrix-core path, or the general kernel) of each call recorded since the
+ * last read, oldest first, at most `cap` values (only the newest n if the ring
+ * wrapped), stores their number in *h_count and clears the record. */
+int32_t smart_tva_profile_read(smart_ctx* ctx, float* h_ms, int32_t cap, int32_t* h_count);
 
 /* ---------------------------------------------------------------------------
  * smart_select_tree (host, batched over sequences)
@@ -228,6 +238,10 @@ typedef struct {
   const uint64_t* d_anc_mask;  /* [total_nodes][2] */
   void* d_out;
   float* d_lse; /* [total_nodes][Hq] or NULL */
+  /* Optional host copy of d_cu_nodes (the host that ran smart_select_tree has it), or NULL.
+   * Used only to skip launching kernels no sequence of the batch needs; results do not
+   * depend on it.  It must agree with d_cu_nodes. */
+  const int32_t* h_cu_nodes;
 } tva_params;
 
 int32_t tree_verify_attention(smart_ctx* ctx, void* stream, const tva_params* params);

@@ -13,18 +13,18 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsmart_tree.so")
+LIB_PATH = os.environ.get("SMART_TREE_LIB") or os.path.join(_HERE, "libsmart_tree.so")
 
 SMART_OK, SMART_EINVAL, SMART_ETREE, SMART_ECAP, SMART_EHIP, SMART_ENOMEM = 0, -1, -2, -3, -4, -5
 SMART_F32, SMART_BF16 = 0, 1
 SMART_KV_PLAIN, SMART_KV_INTERLEAVED = 0, 1
 SMART_BEST_FIRST, SMART_LAYERWISE = 0, 1
 SMART_DILUTION_NONE, SMART_DILUTION_PATH_MEAN = 0, 1
-SMART_OPT_TVA_WORKERS, SMART_OPT_TVA_FORCE_GENERAL = 1, 2
+SMART_OPT_TVA_WORKERS, SMART_OPT_TVA_FORCE_GENERAL, SMART_OPT_TVA_PROFILE = 1, 2, 3
 SMART_MAX_NODES = 128
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
-           "smart_reserve", "smart_set_option", "smart_select_tree", "tree_pack",
+           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept"]
 
 
@@ -50,6 +50,7 @@ class TvaParams(ctypes.Structure):
         ("d_block_table", ctypes.c_void_p), ("d_prefix_len", ctypes.c_void_p),
         ("d_cu_nodes", ctypes.c_void_p), ("d_anc_mask", ctypes.c_void_p),
         ("d_out", ctypes.c_void_p), ("d_lse", ctypes.c_void_p),
+        ("h_cu_nodes", ctypes.c_void_p),
     ]
 
 
@@ -75,6 +76,8 @@ def _lib():
         lib.smart_reserve.argtypes = [vp, i32, i32, i32, i32]
         lib.smart_set_option.restype = i32
         lib.smart_set_option.argtypes = [vp, i32, i64]
+        lib.smart_tva_profile_read.restype = i32
+        lib.smart_tva_profile_read.argtypes = [vp, vp, i32, vp]
         lib.smart_select_tree.restype = i32
         lib.smart_select_tree.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, i32, i32,
                                           vp, vp, vp, vp, vp, i64, vp, vp]
@@ -205,6 +208,15 @@ class SmartTree:
         _check(_lib().smart_reserve(self._h, max_batch, max_total_nodes, max_q_heads, max_kv_heads),
                "smart_reserve")
 
+    def profile_read(self, cap: int = 65536):
+        """Durations (ms) of the dominant attention kernel of the calls recorded
+        since the last read; the caller synchronises first."""
+        buf = (ctypes.c_float * cap)()
+        cnt = ctypes.c_int32(0)
+        _check(_lib().smart_tva_profile_read(self._h, buf, cap, ctypes.byref(cnt)),
+               "smart_tva_profile_read")
+        return [buf[i] for i in range(cnt.value)]
+
     # -- tree_pack ---------------------------------------------------------
     def tree_pack(self, cu_nodes, parent, prefix_len):
         torch = _torch()
@@ -235,7 +247,7 @@ class SmartTree:
     # -- tree_verify_attention ---------------------------------------------
     def tree_verify_attention(self, q, k_tree, v_tree, k_cache, v_cache, block_table, prefix_len,
                               cu_nodes, anc_mask, softmax_scale, kv_layout, block_size=16,
-                              out=None, lse=None, want_lse=False):
+                              out=None, lse=None, want_lse=False, h_cu_nodes=None):
         """k_cache / v_cache: [num_blocks, Hkv, ...] with one contiguous page of
         block_size * D elements per (block, head) (any of the two layouts)."""
         torch = _torch()
@@ -268,6 +280,10 @@ class SmartTree:
         p.d_anc_mask = anc_mask.data_ptr()
         p.d_out = out.data_ptr()
         p.d_lse = lse.data_ptr() if lse is not None else None
+        if h_cu_nodes is not None:      # numpy int32 [B+1], host copy of cu_nodes
+            h_cu_nodes = np.ascontiguousarray(h_cu_nodes, np.int32)
+            assert h_cu_nodes.shape[0] == B + 1
+            p.h_cu_nodes = h_cu_nodes.ctypes.data
         _check(_lib().tree_verify_attention(self._h, _stream_ptr(), ctypes.byref(p)),
                "tree_verify_attention")
         return (out, lse) if (want_lse or lse is not None) else out

@@ -19,6 +19,11 @@ struct smart_ctx {
   // options
   int64_t opt_workers = 0;
   int64_t opt_force_general = 0;
+  // profiling ring (SMART_OPT_TVA_PROFILE)
+  hipEvent_t* prof_start = nullptr;
+  hipEvent_t* prof_stop = nullptr;
+  int32_t prof_cap = 0;
+  int64_t prof_recorded = 0;  // calls recorded since the last read
 };
 
 namespace smart {
@@ -39,13 +44,17 @@ void set_last_hip_error(hipError_t e);
 // synchronise `stream` (only when it has to grow).
 int32_t ensure_workspace(smart_ctx* ctx, hipStream_t stream, size_t ws_bytes, size_t plan_bytes);
 
+// Profiling hooks: bracket the dominant kernel of the current call.
+int32_t profile_begin(smart_ctx* ctx, hipStream_t stream);
+int32_t profile_end(smart_ctx* ctx, hipStream_t stream);
+
 // Entry points of the two attention implementations (validated params).
 int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
 int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
 bool tva_mfma_supported(const tva_params& p);
 // Workspace the matrix-core path needs for a problem of this size.
-void tva_mfma_workspace(int32_t batch, int32_t total_nodes, int32_t num_q_heads,
-                        int32_t num_kv_heads, int32_t workers, size_t* ws_bytes, size_t* plan_bytes);
+void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,
+                        int32_t num_kv_heads, size_t* ws_bytes, size_t* plan_bytes);
 int32_t tva_mfma_default_workers(const smart_ctx* ctx);
 
 }  // namespace smart

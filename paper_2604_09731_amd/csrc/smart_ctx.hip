@@ -30,6 +30,31 @@ int32_t ensure_workspace(smart_ctx* ctx, hipStream_t stream, size_t ws_bytes, si
   }
   return SMART_OK;
 }
+
+static void profile_free(smart_ctx* ctx) {
+  for (int i = 0; i < ctx->prof_cap; ++i) {
+    (void)hipEventDestroy(ctx->prof_start[i]);
+    (void)hipEventDestroy(ctx->prof_stop[i]);
+  }
+  delete[] ctx->prof_start;
+  delete[] ctx->prof_stop;
+  ctx->prof_start = ctx->prof_stop = nullptr;
+  ctx->prof_cap = 0;
+  ctx->prof_recorded = 0;
+}
+
+int32_t profile_begin(smart_ctx* ctx, hipStream_t stream) {
+  if (ctx->prof_cap <= 0) return SMART_OK;
+  SMART_HIP_CHECK(hipEventRecord(ctx->prof_start[ctx->prof_recorded % ctx->prof_cap], stream));
+  return SMART_OK;
+}
+
+int32_t profile_end(smart_ctx* ctx, hipStream_t stream) {
+  if (ctx->prof_cap <= 0) return SMART_OK;
+  SMART_HIP_CHECK(hipEventRecord(ctx->prof_stop[ctx->prof_recorded % ctx->prof_cap], stream));
+  ctx->prof_recorded += 1;
+  return SMART_OK;
+}
 }  // namespace smart
 
 extern "C" const char* smart_strerror(int32_t code) {
@@ -65,12 +90,13 @@ extern "C" int32_t smart_create(smart_ctx** out_ctx, int32_t device_id) {
 extern "C" int32_t smart_destroy(smart_ctx* ctx) {
   if (!ctx) return SMART_EINVAL;
   int32_t rc = SMART_OK;
-  if (ctx->ws || ctx->plan) {
+  if (ctx->ws || ctx->plan || ctx->prof_cap) {
     int prev = 0;
     if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(ctx->device) == hipSuccess) {
       (void)hipDeviceSynchronize();
       if (ctx->ws && hipFree(ctx->ws) != hipSuccess) rc = SMART_EHIP;
       if (ctx->plan && hipFree(ctx->plan) != hipSuccess) rc = SMART_EHIP;
+      smart::profile_free(ctx);
       (void)hipSetDevice(prev);
     } else {
       rc = SMART_EHIP;
@@ -91,9 +117,59 @@ extern "C" int32_t smart_set_option(smart_ctx* ctx, int32_t key, int64_t value) 
       if (value != 0 && value != 1) return SMART_EINVAL;
       ctx->opt_force_general = value;
       return SMART_OK;
+    case SMART_OPT_TVA_PROFILE: {
+      if (value < 0 || value > 65536) return SMART_EINVAL;
+      int prev = 0;
+      SMART_HIP_CHECK(hipGetDevice(&prev));
+      SMART_HIP_CHECK(hipSetDevice(ctx->device));
+      smart::profile_free(ctx);
+      const int n = (int)value;
+      if (n > 0) {
+        ctx->prof_start = new (std::nothrow) hipEvent_t[n];
+        ctx->prof_stop = new (std::nothrow) hipEvent_t[n];
+        if (!ctx->prof_start || !ctx->prof_stop) {
+          delete[] ctx->prof_start;
+          delete[] ctx->prof_stop;
+          ctx->prof_start = ctx->prof_stop = nullptr;
+          (void)hipSetDevice(prev);
+          return SMART_ENOMEM;
+        }
+        for (int i = 0; i < n; ++i) {
+          hipError_t e1 = hipEventCreate(&ctx->prof_start[i]);
+          hipError_t e2 = e1 == hipSuccess ? hipEventCreate(&ctx->prof_stop[i]) : e1;
+          if (e2 != hipSuccess) {
+            if (e1 == hipSuccess) (void)hipEventDestroy(ctx->prof_start[i]);
+            ctx->prof_cap = i;
+            smart::profile_free(ctx);
+            smart::set_last_hip_error(e2);
+            (void)hipSetDevice(prev);
+            return SMART_EHIP;
+          }
+        }
+        ctx->prof_cap = n;
+      }
+      (void)hipSetDevice(prev);
+      return SMART_OK;
+    }
     default:
       return SMART_EINVAL;
   }
+}
+
+extern "C" int32_t smart_tva_profile_read(smart_ctx* ctx, float* h_ms, int32_t cap, int32_t* h_count) {
+  if (!ctx || !h_count || cap < 0 || (cap > 0 && !h_ms)) return SMART_EINVAL;
+  *h_count = 0;
+  if (ctx->prof_cap <= 0) return SMART_OK;
+  const int64_t have = ctx->prof_recorded < ctx->prof_cap ? ctx->prof_recorded : ctx->prof_cap;
+  const int64_t first = ctx->prof_recorded - have;
+  int32_t n = 0;
+  for (int64_t i = first; i < ctx->prof_recorded && n < cap; ++i, ++n) {
+    const int slot = (int)(i % ctx->prof_cap);
+    SMART_HIP_CHECK(hipEventElapsedTime(&h_ms[n], ctx->prof_start[slot], ctx->prof_stop[slot]));
+  }
+  *h_count = n;
+  ctx->prof_recorded = 0;
+  return SMART_OK;
 }
 
 extern "C" int32_t smart_reserve(smart_ctx* ctx, int32_t max_batch, int32_t max_total_nodes,
@@ -104,10 +180,8 @@ extern "C" int32_t smart_reserve(smart_ctx* ctx, int32_t max_batch, int32_t max_
   int prev = 0;
   SMART_HIP_CHECK(hipGetDevice(&prev));
   SMART_HIP_CHECK(hipSetDevice(ctx->device));
-  const int32_t workers = ctx->opt_workers > 0 ? (int32_t)ctx->opt_workers
-                                               : smart::tva_mfma_default_workers(ctx);
   size_t ws = 0, plan = 0;
-  smart::tva_mfma_workspace(max_batch, max_total_nodes, max_q_heads, max_kv_heads, workers, &ws, &plan);
+  smart::tva_mfma_workspace(ctx, max_batch, max_total_nodes, max_q_heads, max_kv_heads, &ws, &plan);
   int32_t rc = smart::ensure_workspace(ctx, nullptr, ws, plan);
   (void)hipSetDevice(prev);
   return rc;

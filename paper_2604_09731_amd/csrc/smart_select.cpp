@@ -12,9 +12,12 @@
 // bit-identical on every host.
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <cmath>
+#include <condition_variable>
 #include <cstdint>
-#include <queue>
+#include <functional>
+#include <mutex>
 #include <thread>
 #include <vector>
 
@@ -27,6 +30,11 @@ struct SeqResult {
   std::vector<double> pathprob;
   double L = 0.0, R = 0.0;
   int32_t err = SMART_OK;
+  void clear() {
+    parent.clear(); token.clear(); cand.clear(); pathprob.clear();
+    L = R = 0.0;
+    err = SMART_OK;
+  }
 };
 
 struct Args {
@@ -40,6 +48,13 @@ struct Args {
   int32_t max_depth, budget, schedule, dilution;
 };
 
+// Per-thread scratch reused across sequences and calls (no allocation in steady state).
+struct Scratch {
+  std::vector<int32_t> first_child, child, fill, node_of, depth, heap, active, survivors;
+  std::vector<double> P, path_sum;
+  std::vector<int32_t> n_children;
+};
+
 // Expected acceptance length of the current tree and its number of root-to-leaf
 // paths.  `sum_L` is the running sum of path probabilities (dilution NONE).
 // For PATH_MEAN the per-node running sums along the path from the root are kept
@@ -47,23 +62,29 @@ struct Args {
 // the same addition sequence as summing each path from the root down; leaves
 // are then added in increasing node id.
 struct TreeState {
-  std::vector<int32_t>& parent;
-  std::vector<double>& P;
-  std::vector<double> path_sum;
-  std::vector<int32_t> n_children;
+  const std::vector<int32_t>& parent;
+  const std::vector<double>& P;
+  std::vector<double>& path_sum;
+  std::vector<int32_t>& n_children;
   double sum_L = 1.0;
   int dilution;
 
-  TreeState(std::vector<int32_t>& par, std::vector<double>& p, int dil)
-      : parent(par), P(p), dilution(dil) {}
+  TreeState(const std::vector<int32_t>& par, const std::vector<double>& p, Scratch& sc, int dil)
+      : parent(par), P(p), path_sum(sc.path_sum), n_children(sc.n_children), dilution(dil) {
+    path_sum.clear();
+    n_children.clear();
+  }
 
   void on_append(int node) {
+    if (dilution == SMART_DILUTION_NONE) {
+      if (node != 0) sum_L = sum_L + P[node];
+      return;
+    }
     if (node == 0) {
       path_sum.push_back(0.0 + P[0]);
       n_children.push_back(0);
       return;
     }
-    sum_L = sum_L + P[node];
     path_sum.push_back(path_sum[parent[node]] + P[node]);
     n_children.push_back(0);
     n_children[parent[node]] += 1;
@@ -95,37 +116,59 @@ inline bool keep(double alpha, double benefit, double dC, double L, double cost_
   return lhs > rhs;
 }
 
-void select_one(const Args& a, int b, SeqResult* out) {
+void select_one(const Args& a, int b, SeqResult* out, Scratch& sc) {
   const int lo = a.cand_cu[b], hi = a.cand_cu[b + 1];
   const int C = hi - lo;
   const int32_t* cpar = a.cand_parent + lo;
   const double* cprob = a.cand_prob + lo;
   const int32_t* ctok = a.cand_token + lo;
+  out->clear();
 
   if (C < 1 || cpar[0] != -1) { out->err = SMART_ETREE; return; }
-  std::vector<double> P(C);
-  std::vector<int32_t> depth(C), first_child(C + 1, 0);
-  P[0] = 1.0;
-  depth[0] = 0;
+  // Validation + children index.  Parents that never decrease (breadth-first or
+  // layered candidate orders) make every node's children one contiguous range.
+  bool bad = false, sorted = true;
   for (int u = 1; u < C; ++u) {
     const int p = cpar[u];
     const double pr = cprob[u];
-    if (p < 0 || p >= u || !(pr >= 0.0 && pr <= 1.0)) { out->err = SMART_ETREE; return; }
-    P[u] = P[p] * pr;
-    depth[u] = depth[p] + 1;
-    first_child[p + 1] += 1;
+    bad |= (p < 0) | (p >= u) | !(pr >= 0.0 && pr <= 1.0);
+    sorted &= (u == 1) | (p >= cpar[u - 1]);
   }
-  // children of each candidate, ascending index (CSR by counting)
-  for (int u = 0; u < C; ++u) first_child[u + 1] += first_child[u];
-  std::vector<int32_t> child(C > 1 ? C - 1 : 0), fill(first_child.begin(), first_child.end() - 1);
-  for (int u = 1; u < C; ++u) child[fill[cpar[u]]++] = u;
+  if (bad) { out->err = SMART_ETREE; return; }
+  sc.first_child.assign(C + 1, 0);
+  if (sorted) {
+    // first_child[p] = first u with parent >= p  (children of p are [first_child[p], first_child[p+1]))
+    int u = 1;
+    for (int p = 0; p <= C; ++p) {
+      while (u < C && cpar[u] < p) ++u;
+      sc.first_child[p] = u;
+    }
+  } else {
+    for (int u = 1; u < C; ++u) sc.first_child[cpar[u] + 1] += 1;
+    sc.first_child[0] = 0;
+    for (int u = 0; u < C; ++u) sc.first_child[u + 1] += sc.first_child[u];
+    sc.child.assign(C > 1 ? C - 1 : 0, 0);
+    sc.fill.assign(sc.first_child.begin(), sc.first_child.end() - 1);
+    for (int u = 1; u < C; ++u) sc.child[sc.fill[cpar[u]]++] = u;
+  }
+  auto child_at = [&](int c) { return sorted ? c : sc.child[c]; };
+  auto child_end = [&](int u) { return sc.first_child[u + 1]; };
 
-  std::vector<int32_t> node_of(C, -1);
-  TreeState st(out->parent, out->pathprob, a.dilution);
+  // Path probabilities are computed only for candidates that reach the frontier
+  // (each one P(parent) * p(u), the parent's value being final by then).
+  sc.P.resize(C);
+  sc.depth.resize(C);
+  sc.node_of.resize(C);
+  std::vector<double>& P = sc.P;
+  std::vector<int32_t>& depth = sc.depth;
+  P[0] = 1.0;
+  depth[0] = 0;
+
+  TreeState st(out->parent, out->pathprob, sc, a.dilution);
   auto append = [&](int u) {
     const int node = (int)out->parent.size();
-    node_of[u] = node;
-    out->parent.push_back(u == 0 ? -1 : node_of[cpar[u]]);
+    sc.node_of[u] = node;
+    out->parent.push_back(u == 0 ? -1 : sc.node_of[cpar[u]]);
     out->token.push_back(ctok[u]);
     out->cand.push_back(u);
     out->pathprob.push_back(P[u]);
@@ -135,27 +178,37 @@ void select_one(const Args& a, int b, SeqResult* out) {
   append(0);
 
   if (a.schedule == SMART_BEST_FIRST) {
+    // binary max-heap of candidate indices ordered by (P desc, index asc)
+    std::vector<int32_t>& heap = sc.heap;
+    heap.clear();
     auto worse = [&](int x, int y) { return P[x] < P[y] || (P[x] == P[y] && x > y); };
-    std::priority_queue<int, std::vector<int>, decltype(worse)> frontier(worse);
     auto push_children = [&](int u) {
       if (depth[u] >= a.max_depth) return;
-      for (int c = first_child[u]; c < first_child[u + 1]; ++c) frontier.push(child[c]);
+      for (int c = sc.first_child[u]; c < child_end(u); ++c) {
+        const int v = child_at(c);
+        P[v] = P[u] * cprob[v];
+        depth[v] = depth[u] + 1;
+        heap.push_back(v);
+        std::push_heap(heap.begin(), heap.end(), worse);
+      }
     };
     push_children(0);
-    while (!frontier.empty()) {
+    while (!heap.empty()) {
       const int n = (int)out->parent.size();
       if (n >= a.budget) break;
-      const int u = frontier.top();
+      const int u = heap.front();
       double L, paths;
       st.current(&L, &paths);
       const double benefit = a.dilution == SMART_DILUTION_NONE ? P[u] : P[u] / paths;
       if (!keep(a.alpha, benefit, dC_of(n), L, a.cost[n])) break;
-      frontier.pop();
+      std::pop_heap(heap.begin(), heap.end(), worse);
+      heap.pop_back();
       append(u);
       push_children(u);
     }
   } else {  // SMART_LAYERWISE
-    std::vector<int> active{0}, survivors;
+    std::vector<int32_t>&active = sc.active, &survivors = sc.survivors;
+    active.assign(1, 0);
     for (int layer = 1; layer <= a.max_depth; ++layer) {
       const int n = (int)out->parent.size();
       if (n >= a.budget) break;
@@ -164,8 +217,10 @@ void select_one(const Args& a, int b, SeqResult* out) {
       const double dC = dC_of(n), cost_n = a.cost[n];
       survivors.clear();
       for (int p : active)
-        for (int c = first_child[p]; c < first_child[p + 1]; ++c) {
-          const int u = child[c];
+        for (int c = sc.first_child[p]; c < child_end(p); ++c) {
+          const int u = child_at(c);
+          P[u] = P[p] * cprob[u];
+          depth[u] = depth[p] + 1;
           const double benefit = a.dilution == SMART_DILUTION_NONE ? P[u] : P[u] / paths;
           if (keep(a.alpha, benefit, dC, L, cost_n)) survivors.push_back(u);
         }
@@ -186,6 +241,85 @@ void select_one(const Args& a, int b, SeqResult* out) {
   out->L = L;
   out->R = L / a.cost[out->parent.size()];
 }
+
+// A small persistent pool: workers spin briefly between jobs (calls arrive every
+// ~100 us in a decoding loop), then sleep on a condition variable.
+class Pool {
+ public:
+  static Pool& get() {
+    static Pool p;
+    return p;
+  }
+  int size() const { return (int)threads_.size() + 1; }
+
+  // Runs fn(item, scratch) for item in [0, n) on the pool and the calling thread.
+  void run(int n, const std::function<void(int, Scratch&)>& fn) {
+    std::lock_guard<std::mutex> serial(run_mutex_);  // one job at a time
+    fn_ = &fn;
+    n_ = n;
+    next_.store(0, std::memory_order_relaxed);
+    done_.store(0, std::memory_order_relaxed);
+    {
+      std::lock_guard<std::mutex> lk(m_);
+      generation_.fetch_add(1, std::memory_order_release);
+    }
+    cv_.notify_all();
+    work(scratch_[0]);
+    const int workers = (int)threads_.size();
+    while (done_.load(std::memory_order_acquire) < workers) std::this_thread::yield();
+    fn_ = nullptr;
+  }
+
+ private:
+  Pool() {
+    unsigned hw = std::thread::hardware_concurrency();
+    int n = (int)std::min<unsigned>(hw ? hw : 1u, 8u);
+    scratch_.resize(n);
+    for (int t = 1; t < n; ++t) threads_.emplace_back([this, t] { loop(t); });
+  }
+  ~Pool() {
+    {
+      std::lock_guard<std::mutex> lk(m_);
+      stop_ = true;
+      generation_.fetch_add(1, std::memory_order_release);
+    }
+    cv_.notify_all();
+    for (auto& th : threads_) th.join();
+  }
+  void work(Scratch& sc) {
+    for (int i = next_.fetch_add(1, std::memory_order_relaxed); i < n_;
+         i = next_.fetch_add(1, std::memory_order_relaxed))
+      (*fn_)(i, sc);
+  }
+  void loop(int t) {
+    uint64_t seen = 0;
+    for (;;) {
+      // spin for a short while, then block
+      const auto spin_until = std::chrono::steady_clock::now() + std::chrono::microseconds(200);
+      while (generation_.load(std::memory_order_acquire) == seen &&
+             std::chrono::steady_clock::now() < spin_until) {
+      }
+      if (generation_.load(std::memory_order_acquire) == seen) {
+        std::unique_lock<std::mutex> lk(m_);
+        cv_.wait(lk, [&] { return generation_.load(std::memory_order_acquire) != seen; });
+      }
+      seen = generation_.load(std::memory_order_acquire);
+      if (stop_) return;
+      work(scratch_[t]);
+      done_.fetch_add(1, std::memory_order_release);
+    }
+  }
+
+  std::vector<std::thread> threads_;
+  std::vector<Scratch> scratch_;
+  std::mutex m_, run_mutex_;
+  std::condition_variable cv_;
+  std::atomic<uint64_t> generation_{0};
+  std::atomic<int> next_{0}, done_{0};
+  const std::function<void(int, Scratch&)>* fn_ = nullptr;
+  int n_ = 0;
+  bool stop_ = false;
+};
 
 }  // namespace
 
@@ -212,19 +346,14 @@ extern "C" int32_t smart_select_tree(
 
   const Args a{h_cand_cu, h_cand_parent, h_cand_prob, h_cand_token, h_cost, h_dcost,
                alpha, max_depth, budget, schedule, dilution};
-  std::vector<SeqResult> res(batch);
-  int n_threads = (int)std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u);
-  n_threads = std::min(n_threads, batch / 4);
-  if (n_threads <= 1) {
-    for (int b = 0; b < batch; ++b) select_one(a, b, &res[b]);
+  static thread_local std::vector<SeqResult> res;
+  if ((int)res.size() < batch) res.resize(batch);
+  if (batch < 8) {
+    static thread_local Scratch sc;
+    for (int b = 0; b < batch; ++b) select_one(a, b, &res[b], sc);
   } else {
-    std::atomic<int> next{0};
-    std::vector<std::thread> pool;
-    for (int t = 0; t < n_threads; ++t)
-      pool.emplace_back([&] {
-        for (int b = next.fetch_add(1); b < batch; b = next.fetch_add(1)) select_one(a, b, &res[b]);
-      });
-    for (auto& th : pool) th.join();
+    SeqResult* r = res.data();
+    Pool::get().run(batch, [&a, r](int b, Scratch& sc) { select_one(a, b, &r[b], sc); });
   }
   int64_t total = 0;
   for (int b = 0; b < batch; ++b) {

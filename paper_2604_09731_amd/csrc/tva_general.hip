@@ -78,6 +78,12 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
   int len = prefix_len[b];
   const int cap = max_blocks * lay.block_size;
   len = len < 0 ? 0 : (len > cap ? cap : len);
+  if (node - base >= n_b) {  // a node no sequence owns (inconsistent offsets): defined output
+    T* o = out + ((size_t)node * Hq + h) * D;
+    for (int d = lane; d < D; d += kWave) from_float(0.f, &o[d]);
+    if (lse && lane == 0) lse[(size_t)node * Hq + h] = -INFINITY;
+    return;
+  }
   const uint64_t mask_lo = anc_mask[2 * (size_t)node], mask_hi = anc_mask[2 * (size_t)node + 1];
 
   for (int d = lane; d < D; d += kWave) s_q[d] = to_float(q[((size_t)node * Hq + h) * D + d]);
@@ -155,12 +161,13 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
 namespace smart {
 
 int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p) {
-  (void)ctx;
   const int64_t rows = (int64_t)p.total_nodes * p.num_q_heads;
   if (rows == 0) return SMART_OK;
   if (rows > 0x7FFFFFFF) return SMART_EINVAL;
   Layout lay{p.kv_layout, p.block_size, p.head_dim, p.cache_block_stride, p.cache_head_stride,
              p.cache_token_stride};
+  int32_t rc = profile_begin(ctx, stream);
+  if (rc != SMART_OK) return rc;
   if (p.dtype == SMART_F32)
     hipLaunchKernelGGL(tva_general_kernel<float>, dim3((unsigned)rows), dim3(kWave), 0, stream,
                        p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, p.head_dim,
@@ -177,7 +184,7 @@ int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params&
                        (const uint16_t*)p.d_v_cache, p.d_block_table, p.d_prefix_len, p.d_cu_nodes,
                        p.d_anc_mask, (uint16_t*)p.d_out, p.d_lse);
   SMART_HIP_CHECK(hipGetLastError());
-  return SMART_OK;
+  return profile_end(ctx, stream);
 }
 
 }  // namespace smart

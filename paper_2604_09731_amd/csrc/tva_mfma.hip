@@ -42,63 +42,85 @@ constexpr int kWave = 64;
 constexpr int kD = 128;
 constexpr int kBlock = 16;            // tokens per cache block
 constexpr int kTile = 32;             // keys per tile = two cache blocks
-constexpr int kRowsPerGroup = 64;     // query rows one worker carries (two 32-row MFMA tiles)
-constexpr int kSlotFloats = kRowsPerGroup * kD + 2 * kRowsPerGroup;  // O, then max, then sum
+constexpr int kSmallRows = 32;        // class 1: all rows of a (sequence, kv head) fit one MFMA tile
+constexpr int kLargeRows = 64;        // class 2: rows per row group (two MFMA tiles)
+constexpr int kSmallSlot = kSmallRows * kD + 2 * kSmallRows;  // floats: O, then max, then sum
+constexpr int kLargeSlot = kLargeRows * kD + 2 * kLargeRows;
 constexpr int kCombineRows = 8;       // rows per combine wavefront (8 lanes per row)
-constexpr int kMinTilesPerWorker = 8;
+constexpr int kMinTilesPerWorker[2] = {16, 8};  // class 1 workers are 8-wave workgroups
+constexpr int kChunkTiles = 64;       // tiles whose block ids one pair of registers holds
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------
 // launch plan (device memory, written by tva_plan_kernel)
+//
+// A "unit" is one 32-key tile of one (sequence, kv head, row group) segment.
+// Sequences fall in two classes with separate unit spaces and kernels:
+//   class 1  n * G <= 32 rows: one row group, the bandwidth-bound kernel
+//   class 2  more rows: row groups of 64 rows
 // ---------------------------------------------------------------------------
 struct SeqInfo {
   int32_t len;    // prefix length, clamped
   int32_t n;      // tree nodes, clamped to [0, SMART_MAX_NODES]
   int32_t tiles;  // ceil(len / 32)
-  int32_t rg;     // row groups = ceil(n * G / 64)
+  int32_t rg;     // row groups (1 for class 1)
 };
 
 struct PlanView {
-  int64_t* header;        // [0] total units U, [1] workers W
-  int64_t* cum_units;     // [B+1] units before sequence b (unit = one tile of one (kv head, row group))
-  int32_t* cum_segs;      // [B+1] segments before sequence b (segment = (kv head, row group))
+  int64_t* header;        // [0] U1, [1] W1, [2] U2, [3] W2
+  int64_t* cum_units[2];  // [B+1] per class: units before sequence b
+  int32_t* cum_segs[2];   // [B+1] per class: segments before sequence b
   int32_t* cum_chunks;    // [B+1] combine row chunks before sequence b
   SeqInfo* info;          // [B]
 };
 
 __host__ __device__ inline size_t plan_bytes_for(int batch) {
-  return sizeof(int64_t) * (8 + (size_t)batch + 1) + sizeof(int32_t) * 2 * ((size_t)batch + 2) +
-         sizeof(SeqInfo) * (size_t)batch + 64;
+  const size_t n = (size_t)batch + 2;
+  return sizeof(int64_t) * (8 + 2 * n) + sizeof(SeqInfo) * (size_t)batch + sizeof(int32_t) * 3 * n + 64;
 }
 
 __host__ __device__ inline PlanView plan_view(void* base, int batch) {
   PlanView v;
+  const size_t n = (size_t)batch + 2;
   char* p = (char*)base;
   v.header = (int64_t*)p;
   p += sizeof(int64_t) * 8;
-  v.cum_units = (int64_t*)p;
-  p += sizeof(int64_t) * ((size_t)batch + 1);
+  v.cum_units[0] = (int64_t*)p;
+  p += sizeof(int64_t) * n;
+  v.cum_units[1] = (int64_t*)p;
+  p += sizeof(int64_t) * n;
   v.info = (SeqInfo*)p;
   p += sizeof(SeqInfo) * (size_t)batch;
-  v.cum_segs = (int32_t*)p;
-  p += sizeof(int32_t) * ((size_t)batch + 2);
+  v.cum_segs[0] = (int32_t*)p;
+  p += sizeof(int32_t) * n;
+  v.cum_segs[1] = (int32_t*)p;
+  p += sizeof(int32_t) * n;
   v.cum_chunks = (int32_t*)p;
   return v;
 }
 
-// One workgroup.  Thread t owns a contiguous range of sequences; a serial scan
-// over the per-thread sums (256 entries) ties the ranges together.
-__global__ __launch_bounds__(256) void tva_plan_kernel(
-    void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int max_workers,
-    const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ cu_nodes) {
-  __shared__ int64_t s_units[256];
-  __shared__ int32_t s_segs[256], s_chunks[256];
+__host__ __device__ inline int seq_class(int rows) { return rows <= kSmallRows ? 0 : 1; }
+
+// One wavefront.  Lane t owns a contiguous range of sequences; an exclusive
+// shuffle scan over the per-lane sums ties the ranges together.
+__device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
+  int64_t incl = v;
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int64_t up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  *total = __shfl(incl, kWave - 1);
+  return incl - v;
+}
+
+__global__ __launch_bounds__(kWave) void tva_plan_kernel(
+    void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int max_workers1,
+    int max_workers2, const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ cu_nodes) {
   PlanView pv = plan_view(plan_base, batch);
   const int t = threadIdx.x;
-  const int per = (batch + 255) / 256;
-  const int b0 = t * per, b1 = min(batch, b0 + per);
-  int64_t units = 0;
-  int32_t segs = 0, chunks = 0;
+  const int per = (batch + kWave - 1) / kWave;
+  const int b0 = min(batch, t * per), b1 = min(batch, b0 + per);
+  int64_t units[2] = {0, 0}, segs[2] = {0, 0}, chunks = 0;
   for (int b = b0; b < b1; ++b) {
     int len = prefix_len[b];
     const int cap = max_blocks * kBlock;
@@ -107,54 +129,53 @@ __global__ __launch_bounds__(256) void tva_plan_kernel(
     int n = cu_nodes[b + 1] - base;
     if (base < 0 || n < 0 || base + n > total_nodes) n = 0;
     n = n > SMART_MAX_NODES ? SMART_MAX_NODES : n;
+    const int rows = n * G;
     SeqInfo si;
     si.len = len;
     si.n = n;
     si.tiles = (len + kTile - 1) / kTile;
-    si.rg = (n * G + kRowsPerGroup - 1) / kRowsPerGroup;
+    si.rg = rows == 0 ? 0 : (seq_class(rows) == 0 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
     pv.info[b] = si;
-    units += (int64_t)si.tiles * Hkv * si.rg;
-    segs += Hkv * si.rg;
-    chunks += Hkv * ((n * G + kCombineRows - 1) / kCombineRows);
+    const int c = seq_class(rows);
+    units[c] += (int64_t)si.tiles * Hkv * si.rg;
+    segs[c] += Hkv * si.rg;
+    chunks += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
   }
-  s_units[t] = units;
-  s_segs[t] = segs;
-  s_chunks[t] = chunks;
-  __syncthreads();
+  int64_t tot_u[2], tot_s[2], tot_c, u[2], s[2];
+  for (int c = 0; c < 2; ++c) {
+    u[c] = wave_excl_scan(units[c], t, &tot_u[c]);
+    s[c] = wave_excl_scan(segs[c], t, &tot_s[c]);
+  }
+  int64_t ch = wave_excl_scan(chunks, t, &tot_c);
   if (t == 0) {
-    int64_t u = 0;
-    int32_t s = 0, c = 0;
-    for (int i = 0; i < 256; ++i) {
-      const int64_t uu = s_units[i];
-      const int32_t ss = s_segs[i], cc = s_chunks[i];
-      s_units[i] = u; s_segs[i] = s; s_chunks[i] = c;
-      u += uu; s += ss; c += cc;
+    for (int c = 0; c < 2; ++c) {
+      pv.cum_units[c][batch] = tot_u[c];
+      pv.cum_segs[c][batch] = (int32_t)tot_s[c];
+      int64_t w = tot_u[c] / kMinTilesPerWorker[c];
+      const int64_t mw = c == 0 ? max_workers1 : max_workers2;
+      w = w < 1 ? 1 : (w > mw ? mw : w);
+      pv.header[2 * c] = tot_u[c];
+      pv.header[2 * c + 1] = w;
     }
-    pv.cum_units[batch] = u;
-    pv.cum_segs[batch] = s;
-    pv.cum_chunks[batch] = c;
-    int64_t w = u / kMinTilesPerWorker;
-    w = w < 1 ? 1 : (w > max_workers ? max_workers : w);
-    pv.header[0] = u;
-    pv.header[1] = w;
+    pv.cum_chunks[batch] = (int32_t)tot_c;
   }
-  __syncthreads();
-  units = s_units[t];
-  segs = s_segs[t];
-  chunks = s_chunks[t];
   for (int b = b0; b < b1; ++b) {
     const SeqInfo si = pv.info[b];
-    pv.cum_units[b] = units;
-    pv.cum_segs[b] = segs;
-    pv.cum_chunks[b] = chunks;
-    units += (int64_t)si.tiles * Hkv * si.rg;
-    segs += Hkv * si.rg;
-    chunks += Hkv * ((si.n * G + kCombineRows - 1) / kCombineRows);
+    const int rows = si.n * G;
+    const int c = seq_class(rows);
+    pv.cum_units[0][b] = u[0];
+    pv.cum_units[1][b] = u[1];
+    pv.cum_segs[0][b] = (int32_t)s[0];
+    pv.cum_segs[1][b] = (int32_t)s[1];
+    pv.cum_chunks[b] = (int32_t)ch;
+    u[c] += (int64_t)si.tiles * Hkv * si.rg;
+    s[c] += Hkv * si.rg;
+    ch += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
   }
 }
 
 // ---------------------------------------------------------------------------
-// prefix kernel
+// prefix kernels
 // ---------------------------------------------------------------------------
 struct MainArgs {
   const __bf16* q;
@@ -163,11 +184,28 @@ struct MainArgs {
   const int32_t* block_table;
   const int32_t* cu_nodes;
   void* plan;
-  float* ws;
+  float* ws;  // partial slots of this kernel's class
   int64_t block_stride, head_stride;
   int32_t batch, Hq, Hkv, G, max_blocks, num_blocks;
   float scale_log2e;
 };
+
+// Wave-uniform data (block table, plan) is read through the constant address
+// space so that the loads are scalar and stay off the vector-memory queue the
+// K/V stream uses.  Nothing read this way is written by the same kernel.
+typedef const __attribute__((address_space(4))) int32_t* const_i32;
+typedef const __attribute__((address_space(4))) int64_t* const_i64;
+__device__ inline int32_t sload(const int32_t* p) { return *(const_i32)(uintptr_t)p; }
+__device__ inline int64_t sload(const int64_t* p) { return *(const_i64)(uintptr_t)p; }
+__device__ inline SeqInfo sload(const SeqInfo* p) {
+  SeqInfo si;
+  const int32_t* q = (const int32_t*)p;
+  si.len = sload(q);
+  si.n = sload(q + 1);
+  si.tiles = sload(q + 2);
+  si.rg = sload(q + 3);
+  return si;
+}
 
 // Row m of a 16-row half of the score tile holds cache slot sigma(m): swapping
 // bits 2 and 3 makes the 8 accumulator registers a lane ends up with (rows
@@ -175,199 +213,473 @@ struct MainArgs {
 // one V vector of the interleaved layout.
 __device__ inline int sigma(int m) { return (m & 3) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
-struct KVTile {
-  bf16x8 k[8];     // A operand of scores: [k step]
-  bf16x8 v[2][4];  // A operand of the output product: [cache block of the tile][32-wide d tile]
+// Maximum over the two half-wavefronts (lanes j and j + 32) without touching LDS.
+__device__ inline float max_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float sum_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Addresses of the two cache pages (one per 16-token block) of a 32-key tile.
+struct TilePages {
+  int64_t page0, page1;  // element offsets of (block, kv head) pages
 };
 
-__device__ inline void load_tile(KVTile& T, const MainArgs& a, const int32_t* bt_row, int tile,
-                                 int n_blocks, int g, int lane) {
-  const int h = lane >> 5, j = lane & 31;
+__device__ inline int64_t clamp_block(int64_t blk, int num_blocks) {
+  return blk < 0 ? 0 : (blk >= num_blocks ? num_blocks - 1 : blk);
+}
+
+__device__ inline TilePages tile_pages(const MainArgs& a, const int32_t* bt_row, int tile,
+                                       int n_blocks, int g) {
   const int i0 = 2 * tile;
   const int i1 = min(2 * tile + 1, n_blocks - 1);  // a missing second block is fully masked later
-  int64_t blk0 = bt_row[i0], blk1 = bt_row[i1];
-  blk0 = blk0 < 0 ? 0 : (blk0 >= a.num_blocks ? a.num_blocks - 1 : blk0);
-  blk1 = blk1 < 0 ? 0 : (blk1 >= a.num_blocks ? a.num_blocks - 1 : blk1);
-  const int64_t page0 = blk0 * a.block_stride + (int64_t)g * a.head_stride;
-  const int64_t page1 = blk1 * a.block_stride + (int64_t)g * a.head_stride;
-  const __bf16* kp = a.k_cache + ((j >> 4) ? page1 : page0) + (h * 16 + sigma(j & 15)) * 8;
+  TilePages tp;
+  tp.page0 = clamp_block(sload(bt_row + i0), a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
+  tp.page1 = clamp_block(sload(bt_row + i1), a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
+  return tp;
+}
+
+// K tile as the A operand of the score product: lane (h, j) holds key row j,
+// head dims 16 ks + 8 h .. + 7 for k step ks.
+__device__ inline void load_k(bf16x8 (&k)[8], const MainArgs& a, const TilePages& tp, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  // rows 0..15 come from the tile's first cache block, rows 16..31 from its second
+  // (branch-free select: mask is all ones for the second block)
+  const int64_t mask = -(int64_t)(j >> 4);
+  const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
+  const __bf16* kp = a.k_cache + page + (h * 16 + sigma(j & 15)) * 8;
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) T.k[ks] = *(const bf16x8*)(kp + ks * 256);
-  const __bf16* vp0 = a.v_cache + page0 + (h * kD + j) * 8;
-  const __bf16* vp1 = a.v_cache + page1 + (h * kD + j) * 8;
+  for (int ks = 0; ks < 8; ++ks) k[ks] = *(const bf16x8*)(kp + ks * 256);
+}
+
+// V tile as the A operand of the output product: lane (h, j) holds head dim
+// 32 jt + j, tokens 8 h .. 8 h + 7 of cache block kk.
+__device__ inline void load_v(bf16x8 (&v)[2][4], const MainArgs& a, const TilePages& tp, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  const __bf16* vp0 = a.v_cache + tp.page0 + (h * kD + j) * 8;
+  const __bf16* vp1 = a.v_cache + tp.page1 + (h * kD + j) * 8;
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt) {
-    T.v[0][jt] = *(const bf16x8*)(vp0 + jt * 256);
-    T.v[1][jt] = *(const bf16x8*)(vp1 + jt * 256);
+    v[0][jt] = *(const bf16x8*)(vp0 + jt * 256);
+    v[1][jt] = *(const bf16x8*)(vp1 + jt * 256);
   }
 }
 
-template <int QT>
-struct RowState {
-  bf16x8 q[QT][8];     // B operand of scores
-  floatx16 o[QT][4];   // output accumulators, transposed: [d tile], lane = query row
-  float m[QT], l[QT];  // running max (raw score units) and this lane's share of the sum
+// Masks the ragged end of a prefix: scores of tokens >= n_valid become -inf and
+// their V entries zero (unused cache slots may hold anything, NaN included).
+__device__ inline void mask_tail(floatx16& s, bf16x8 (&v)[2][4], int n_valid, int h) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int i = 8 * (r >> 2) + 4 * h + (r & 3);  // score-tile row of this register
+    const int tok = (i & 16) + sigma(i & 15);      // token of the tile it holds
+    if (tok >= n_valid) s[r] = -INFINITY;
+  }
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (kk * 16 + h * 8 + e >= n_valid) {
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) v[kk][jt][e] = (__bf16)0.f;
+      }
+}
+
+// Online-softmax update of one 32-row tile: scores s (keys x rows, transposed)
+// -> bf16 probabilities in the operand layout of the output product.
+__device__ inline void softmax_tile(const floatx16& s, float& m, float& l, floatx16 (&o)[4],
+                                    bf16x8& pb0, bf16x8& pb1, float c) {
+  float mx = s[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+  mx = max_across_halves(mx);
+  const float m_new = fmaxf(m, mx);
+  if (__any(m_new > m)) {  // rescale only when some row's maximum moved
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+    l *= alpha;
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) o[jt] *= alpha;
+    m = m_new;
+  }
+  const float mc = m * c;
+  floatx8 p0, p1;
+  float sum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    p0[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c, -mc));
+    p1[r] = __builtin_amdgcn_exp2f(fmaf(s[r + 8], c, -mc));
+    sum += p0[r] + p1[r];
+  }
+  l += sum;
+  pb0 = __builtin_convertvector(p0, bf16x8);
+  pb1 = __builtin_convertvector(p1, bf16x8);
+}
+
+// Writes one 32-row tile of a partial: O as [d / 4][row][4] so that lanes
+// write contiguous 16-byte pieces; then the row maxima and sums.
+__device__ inline void store_partial(float* slot, int rows_in_slot, int qt, const floatx16 (&o)[4],
+                                     float m, float l, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  const float lsum = sum_across_halves(l);
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int chunk = jt * 8 + 2 * r4 + h;
+      floatx4 x;
+      x[0] = o[jt][4 * r4 + 0];
+      x[1] = o[jt][4 * r4 + 1];
+      x[2] = o[jt][4 * r4 + 2];
+      x[3] = o[jt][4 * r4 + 3];
+      *(floatx4*)(slot + ((size_t)(qt * 32 + chunk) * 32 + j) * 4) = x;
+    }
+  if (h == 0) {
+    slot[rows_in_slot * kD + qt * 32 + j] = m;
+    slot[rows_in_slot * kD + rows_in_slot + qt * 32 + j] = lsum;
+  }
+}
+
+// Locates the sequence that holds unit u0 in one class's unit space.
+__device__ inline int find_sequence(const int64_t* cum_units, int batch, int64_t u0) {
+  int lo = 0, hi = batch;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (sload(cum_units + mid) <= u0) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// ---- class 1: bandwidth-bound kernel, rows <= 32 -----------------------------------------
+//
+// K and V each have one register buffer.  The loop body is straight-line:
+// scores -> request next K -> softmax -> output product -> request next V, so
+// each request is in flight during the other half of the iteration and during
+// the co-resident wavefront's work (two wavefronts per SIMD).  Requests past
+// the end of the range are clamped to its last tile (an L2 hit) rather than
+// predicated, which keeps the hardware wait counters exact.
+struct SmallState {
+  floatx16 o[4];
+  float m, l;
 };
 
-template <int QT>
-__device__ inline void compute_tile(RowState<QT>& R, KVTile& T, int n_valid, float c, int lane) {
-  const int h = lane >> 5;
-  floatx16 s[QT];
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    s[qt] = (floatx16)(0.f);
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T.k[ks], R.q[qt][ks], s[qt], 0, 0, 0);
-  }
-  if (n_valid < kTile) {  // ragged end of the prefix (wave-uniform)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int i = 8 * (r >> 2) + 4 * h + (r & 3);     // score-tile row of this register
-      const int tok = (i & 16) + sigma(i & 15);         // token of the tile it holds
-      if (tok >= n_valid) {
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) s[qt][r] = -INFINITY;
-      }
-    }
-    // unused cache slots may hold anything, NaN included: zero them in V
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (kk * 16 + h * 8 + e >= n_valid) {
-#pragma unroll
-          for (int jt = 0; jt < 4; ++jt) T.v[kk][jt][e] = (__bf16)0.f;
-        }
-  }
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    float mx = s[qt][0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[qt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(R.m[qt], mx);
-    if (__any(m_new > R.m[qt])) {  // rescale only when some row's maximum moved
-      const float alpha = __builtin_amdgcn_exp2f((R.m[qt] - m_new) * c);
-      R.l[qt] *= alpha;
-#pragma unroll
-      for (int jt = 0; jt < 4; ++jt) R.o[qt][jt] *= alpha;
-      R.m[qt] = m_new;
-    }
-    const float mc = R.m[qt] * c;
-    floatx8 p0, p1;
-    float sum = 0.f;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      p0[r] = __builtin_amdgcn_exp2f(fmaf(s[qt][r], c, -mc));
-      p1[r] = __builtin_amdgcn_exp2f(fmaf(s[qt][r + 8], c, -mc));
-      sum += p0[r] + p1[r];
-    }
-    R.l[qt] += sum;
-    const bf16x8 pb0 = __builtin_convertvector(p0, bf16x8);
-    const bf16x8 pb1 = __builtin_convertvector(p1, bf16x8);
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt) {
-      R.o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T.v[0][jt], pb0, R.o[qt][jt], 0, 0, 0);
-      R.o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T.v[1][jt], pb1, R.o[qt][jt], 0, 0, 0);
-    }
-  }
+// Block ids of tiles [tc, tc + 64) of a sequence live in two registers (lane i
+// of reg r holds entry 2 tc + 64 r + i); a tile's two ids come out by readlane.
+struct BlockIds {
+  int32_t lo, hi;
+};
+
+__device__ inline TilePages pages_from_ids(const MainArgs& a, const BlockIds& ids, int rel_tile, int g) {
+  const int r = 2 * rel_tile;  // even, so both entries sit in the same register
+  const int32_t src = r < kWave ? ids.lo : ids.hi;
+  const int64_t blk0 = clamp_block(__builtin_amdgcn_readlane(src, r & (kWave - 1)), a.num_blocks);
+  const int64_t blk1 = clamp_block(__builtin_amdgcn_readlane(src, (r + 1) & (kWave - 1)), a.num_blocks);
+  TilePages tp;
+  tp.page0 = blk0 * a.block_stride + (int64_t)g * a.head_stride;
+  tp.page1 = blk1 * a.block_stride + (int64_t)g * a.head_stride;
+  return tp;
 }
 
-// Streams tiles [t0, t1) of (sequence b, kv head g) against row group `rgi`
-// and writes the unnormalised partial to `slot`.
-template <int QT>
-__device__ inline void process_segment(const MainArgs& a, int b, int g, int rgi, int t0, int t1,
-                                       const SeqInfo si, float* slot, int lane) {
+template <bool kMasked>
+__device__ inline void small_tile(SmallState& S, bf16x8 (&k)[8], bf16x8 (&v)[2][4], const bf16x8 (&q)[8],
+                                  int lane, float c, int n_valid, const MainArgs& a,
+                                  const TilePages& next) {
+  floatx16 s = (floatx16)(0.f);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[ks], q[ks], s, 0, 0, 0);
+  load_k(k, a, next, lane);
+  if (kMasked) mask_tail(s, v, n_valid, lane >> 5);
+  bf16x8 pb0, pb1;
+  softmax_tile(s, S.m, S.l, S.o, pb0, pb1, c);
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[0][jt], pb0, S.o[jt], 0, 0, 0);
+    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[1][jt], pb1, S.o[jt], 0, 0, 0);
+  }
+  load_v(v, a, next, lane);
+}
+
+__device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, int g, int base, int t0,
+                                     int t1, const SeqInfo si, int lane) {
   const int h = lane >> 5, j = lane & 31;
   const int M = si.n * a.G;
-  const int base = a.cu_nodes[b];
-  RowState<QT> R;
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    int rho = rgi * kRowsPerGroup + qt * 32 + j;
-    rho = rho < M ? rho : M - 1;  // padding rows repeat the last real row; never read back
+  for (int jt = 0; jt < 4; ++jt) S.o[jt] = (floatx16)(0.f);
+  S.m = -INFINITY;
+  S.l = 0.f;
+  if (t0 >= t1) return;  // this wavefront has no tile of the piece
+  bf16x8 q[8];  // B operand of the score product: query row j, head dims 16 ks + 8 h ..
+  {
+    const int rho = j < M ? j : M - 1;  // padding rows repeat the last real row; never read back
     const int node = base + rho / a.G, head = g * a.G + rho % a.G;
     const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) R.q[qt][ks] = *(const bf16x8*)(qp + ks * 16);
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt) R.o[qt][jt] = (floatx16)(0.f);
-    R.m[qt] = -INFINITY;
-    R.l[qt] = 0.f;
+    for (int ks = 0; ks < 8; ++ks) q[ks] = *(const bf16x8*)(qp + ks * 16);
   }
   const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
   const int n_blocks = (si.len + kBlock - 1) / kBlock;
   const float c = a.scale_log2e;
 
-  KVTile A, B;
-  load_tile(A, a, bt_row, t0, n_blocks, g, lane);
-  int t = t0;
-  while (t + 1 < t1) {
-    load_tile(B, a, bt_row, t + 1, n_blocks, g, lane);
-    compute_tile<QT>(R, A, min(kTile, si.len - t * kTile), c, lane);
-    if (t + 2 < t1) load_tile(A, a, bt_row, t + 2, n_blocks, g, lane);
-    compute_tile<QT>(R, B, min(kTile, si.len - (t + 1) * kTile), c, lane);
-    t += 2;
-  }
-  if (t < t1) compute_tile<QT>(R, A, min(kTile, si.len - t * kTile), c, lane);
-
-  // partial: O as [row tile][d / 4][row][4] so that lanes write contiguous 16-byte pieces
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    const float l = R.l[qt] + __shfl_xor(R.l[qt], 32);
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int chunk = jt * 8 + 2 * r4 + h;
-        floatx4 v;
-        v[0] = R.o[qt][jt][4 * r4 + 0];
-        v[1] = R.o[qt][jt][4 * r4 + 1];
-        v[2] = R.o[qt][jt][4 * r4 + 2];
-        v[3] = R.o[qt][jt][4 * r4 + 3];
-        *(floatx4*)(slot + ((size_t)(qt * 32 + chunk) * 32 + j) * 4) = v;
-      }
-    if (h == 0) {
-      slot[kRowsPerGroup * kD + qt * 32 + j] = R.m[qt];
-      slot[kRowsPerGroup * kD + kRowsPerGroup + qt * 32 + j] = l;
+  for (int tc = t0; tc < t1; tc += kChunkTiles) {
+    const int te = min(t1, tc + kChunkTiles);
+    BlockIds ids;
+    ids.lo = bt_row[min(2 * tc + lane, n_blocks - 1)];
+    ids.hi = bt_row[min(2 * tc + kWave + lane, n_blocks - 1)];
+    // Both id registers must have landed before the tile stream starts: inside the loop
+    // nothing may wait on them, or the wait would also drain the K/V requests in flight.
+    asm volatile("" ::"v"(ids.lo), "v"(ids.hi));
+    // complete tiles (32 valid keys) end here; at most the sequence's last tile is ragged
+    const int full_end = min(te, si.len / kTile);
+    bf16x8 k[8], v[2][4];
+    {
+      const TilePages first = pages_from_ids(a, ids, 0, g);
+      load_k(k, a, first, lane);
+      load_v(v, a, first, lane);
+    }
+    int t = tc;
+    for (; t < full_end; ++t) {
+      const TilePages next = pages_from_ids(a, ids, min(t + 1, te - 1) - tc, g);
+      small_tile<false>(S, k, v, q, lane, c, kTile, a, next);
+    }
+    if (t < te) {  // the ragged last tile of the sequence
+      const TilePages next = pages_from_ids(a, ids, te - 1 - tc, g);
+      small_tile<true>(S, k, v, q, lane, c, si.len - t * kTile, a, next);
     }
   }
 }
 
-// One wavefront per worker.  Worker w owns units [w U / W, (w+1) U / W) of the
-// batch-wide sequence of (sequence, kv head, row group, tile) units.
-__global__ __launch_bounds__(kWave) void tva_prefix_kernel(MainArgs a) {
+// Folds another wavefront's running softmax state (read from LDS, where the
+// partner wrote it register by register, lane by lane) into this one's.
+constexpr int kStateFloats = (64 + 2) * kWave;  // 64 accumulator registers + max + sum, per lane
+
+__device__ inline void state_to_lds(const SmallState& S, float* region, int lane) {
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) region[(jt * 16 + r) * kWave + lane] = S.o[jt][r];
+  region[64 * kWave + lane] = S.m;
+  region[65 * kWave + lane] = S.l;
+}
+
+__device__ inline void merge_from_lds(SmallState& S, const float* region, int lane, float c) {
+  const float mb = region[64 * kWave + lane], lb = region[65 * kWave + lane];
+  const float m_new = fmaxf(S.m, mb);
+  // an empty state has max -inf and contributes nothing; two empty states stay empty
+  const float sa = S.m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((S.m - m_new) * c);
+  const float sb = mb == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mb - m_new) * c);
+  S.l = S.l * sa + lb * sb;
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) S.o[jt][r] = S.o[jt][r] * sa + region[(jt * 16 + r) * kWave + lane] * sb;
+  S.m = m_new;
+}
+
+// The plan entries of 64 consecutive sequences, one per lane, fetched with one
+// round trip; a worker's range rarely leaves the window it starts in.
+struct PlanWindow {
+  int first;          // sequence held by lane 0
+  int64_t cum_units;  // lane i: units before sequence first + i (entry `batch` included)
+  int32_t cum_segs;
+  int32_t cu_nodes;
+  int32_t len, n, tiles, rg;
+};
+
+__device__ inline int64_t readlane64(int64_t v, int lane) {
+  const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, lane);
+  const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)v >> 32), lane);
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ inline void load_window(PlanWindow& w, const PlanView& pv, const int32_t* cu_nodes,
+                                   int cls, int batch, int first, int lane) {
+  w.first = first;
+  const int e = min(first + lane, batch);      // entries 0 .. batch exist
+  const int b = min(first + lane, batch - 1);  // per-sequence info exists for 0 .. batch - 1
+  w.cum_units = pv.cum_units[cls][e];
+  w.cum_segs = pv.cum_segs[cls][e];
+  w.cu_nodes = cu_nodes[e];
+  const SeqInfo si = pv.info[b];
+  w.len = si.len;
+  w.n = si.n;
+  w.tiles = si.tiles;
+  w.rg = si.rg;
+}
+
+__device__ inline SeqInfo window_info(const PlanWindow& w, int b) {
+  const int i = b - w.first;
+  SeqInfo si;
+  si.len = __builtin_amdgcn_readlane(w.len, i);
+  si.n = __builtin_amdgcn_readlane(w.n, i);
+  si.tiles = __builtin_amdgcn_readlane(w.tiles, i);
+  si.rg = __builtin_amdgcn_readlane(w.rg, i);
+  return si;
+}
+
+// Sequence that holds unit u0 of class `cls`, with its plan window loaded.
+__device__ inline int locate(PlanWindow& w, const PlanView& pv, const int32_t* cu_nodes, int cls,
+                             int batch, int64_t u0, int lane) {
+  if (batch <= kWave) {
+    load_window(w, pv, cu_nodes, cls, batch, 0, lane);
+    // cum_units is non-decreasing: the lanes with cum <= u0 are a prefix, its last lane is b
+    const uint64_t below = __ballot(lane < batch && w.cum_units <= u0);
+    return __popcll(below) - 1;
+  }
+  const int b = find_sequence(pv.cum_units[cls], batch, u0);
+  load_window(w, pv, cu_nodes, cls, batch, b, lane);
+  return b;
+}
+
+// One workgroup of eight wavefronts per worker (two per SIMD).  Worker w owns
+// units [w U / W, (w+1) U / W) of class 1; every piece of that range (its
+// intersection with one (sequence, kv head) segment) is cut into eight
+// contiguous sub-ranges, one per wavefront, and the eight running states are
+// folded together through LDS in three rounds, so that a piece leaves ONE
+// partial in memory however many wavefronts streamed it.
+constexpr int kSmallWaves = 8;
+
+__global__ __launch_bounds__(kSmallWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void tva_prefix_small_kernel(MainArgs a) {
+  __shared__ float merge_lds[(kSmallWaves / 2) * kStateFloats];  // 66 KB
   const PlanView pv = plan_view(a.plan, a.batch);
-  const int64_t U = pv.header[0], W = pv.header[1];
+  const int64_t U = sload(pv.header), W = sload(pv.header + 1);
+  const int64_t w = blockIdx.x;
+  if (w >= W || U <= 0) return;
+  int64_t u0 = (w * U) / W;
+  const int64_t u1 = ((w + 1) * U) / W;
+  if (u0 >= u1) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  PlanWindow win;
+  int b = locate(win, pv, a.cu_nodes, 0, a.batch, u0, lane);
+  while (u0 < u1 && b < a.batch) {
+    if (b - win.first >= kWave - 1) load_window(win, pv, a.cu_nodes, 0, a.batch, b, lane);
+    const int64_t seq_begin = readlane64(win.cum_units, b - win.first);
+    const int64_t seq_end = readlane64(win.cum_units, b + 1 - win.first);
+    if (u0 >= seq_end) { ++b; continue; }  // also skips sequences without units in this class
+    const SeqInfo si = window_info(win, b);
+    const int64_t local = u0 - seq_begin;
+    const int g = (int)(local / si.tiles);
+    const int t0 = (int)(local % si.tiles);
+    const int64_t left = u1 - u0;
+    const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
+    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + g;
+    const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
+    // this wavefront's share of the piece
+    const int s0 = t0 + (int)(((int64_t)nt * wv) / kSmallWaves);
+    const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kSmallWaves);
+    SmallState S;
+    small_segment(S, a, b, g, base, s0, s1, si, lane);
+    // fold: waves [half, 2 half) hand their state to waves [0, half)
+#pragma unroll
+    for (int half = kSmallWaves / 2; half >= 1; half >>= 1) {
+      if (wv >= half && wv < 2 * half) state_to_lds(S, merge_lds + (wv - half) * kStateFloats, lane);
+      __syncthreads();
+      if (wv < half) merge_from_lds(S, merge_lds + wv * kStateFloats, lane, a.scale_log2e);
+      __syncthreads();
+    }
+    if (wv == 0) store_partial(a.ws + (size_t)(w + seg) * kSmallSlot, kSmallRows, 0, S.o, S.m, S.l, lane);
+    u0 += nt;
+  }
+}
+
+// ---- class 2: row groups of 64 rows (two MFMA tiles per wavefront) -----------------------
+//
+// K and V each have one register buffer; the next tile's K is requested as
+// soon as the scores are done and its V as soon as the output product is done.
+template <int QT>
+__device__ inline void large_segment(const MainArgs& a, int b, int g, int rgi, int t0, int t1,
+                                     const SeqInfo si, float* slot, int lane, bf16x8* q_lds) {
+  const int h = lane >> 5, j = lane & 31;
+  const int M = si.n * a.G;
+  const int base = sload(a.cu_nodes + b);
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    int rho = rgi * kLargeRows + qt * 32 + j;
+    rho = rho < M ? rho : M - 1;
+    const int node = base + rho / a.G, head = g * a.G + rho % a.G;
+    const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) q_lds[(qt * 8 + ks) * kWave + lane] = *(const bf16x8*)(qp + ks * 16);
+  }
+  floatx16 o[QT][4];
+  float m[QT], l[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) o[qt][jt] = (floatx16)(0.f);
+    m[qt] = -INFINITY;
+    l[qt] = 0.f;
+  }
+  const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
+  const int n_blocks = (si.len + kBlock - 1) / kBlock;
+  const float c = a.scale_log2e;
+
+  bf16x8 k[8], v[2][4];
+  TilePages tp = tile_pages(a, bt_row, t0, n_blocks, g);
+  load_k(k, a, tp, lane);
+  load_v(v, a, tp, lane);
+  for (int t = t0; t < t1; ++t) {
+    // past the end the last tile is requested again (an L2 hit) instead of predicating the loads
+    tp = tile_pages(a, bt_row, min(t + 1, t1 - 1), n_blocks, g);
+    const int n_valid = min(kTile, si.len - t * kTile);
+    floatx16 s[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      s[qt] = (floatx16)(0.f);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[ks], q_lds[(qt * 8 + ks) * kWave + lane],
+                                                        s[qt], 0, 0, 0);
+    }
+    load_k(k, a, tp, lane);
+    if (n_valid < kTile) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) mask_tail(s[qt], v, n_valid, h);
+    }
+    bf16x8 pb[QT][2];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) softmax_tile(s[qt], m[qt], l[qt], o[qt], pb[qt][0], pb[qt][1], c);
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+      for (int jt = 0; jt < 4; ++jt) {
+        o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[0][jt], pb[qt][0], o[qt][jt], 0, 0, 0);
+        o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[1][jt], pb[qt][1], o[qt][jt], 0, 0, 0);
+      }
+    load_v(v, a, tp, lane);
+  }
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) store_partial(slot, kLargeRows, qt, o[qt], m[qt], l[qt], lane);
+}
+
+__global__ __launch_bounds__(kWave) void tva_prefix_large_kernel(MainArgs a) {
+  __shared__ bf16x8 q_lds[2 * 8 * kWave];  // 16 KB: two 32-row tiles of query operands
+  const PlanView pv = plan_view(a.plan, a.batch);
+  const int64_t U = sload(pv.header + 2), W = sload(pv.header + 3);
   const int64_t w = blockIdx.x;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
   if (u0 >= u1) return;
   const int lane = threadIdx.x;
-  // sequence that holds unit u0: last b with cum_units[b] <= u0
-  int lo = 0, hi = a.batch;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (pv.cum_units[mid] <= u0) lo = mid; else hi = mid;
-  }
-  int b = lo;
+  int b = find_sequence(pv.cum_units[1], a.batch, u0);
   while (u0 < u1 && b < a.batch) {
-    const SeqInfo si = pv.info[b];
-    const int64_t seq_begin = pv.cum_units[b], seq_end = pv.cum_units[b + 1];
-    if (u0 >= seq_end) { ++b; continue; }  // also skips sequences without units
+    const int64_t seq_begin = sload(pv.cum_units[1] + b), seq_end = sload(pv.cum_units[1] + b + 1);
+    if (u0 >= seq_end) { ++b; continue; }
+    const SeqInfo si = sload(pv.info + b);
     const int64_t local = u0 - seq_begin;
     const int seg_local = (int)(local / si.tiles);
     const int t0 = (int)(local % si.tiles);
     const int g = seg_local / si.rg, rgi = seg_local % si.rg;
     const int64_t left = u1 - u0;
     const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
-    const int64_t seg = (int64_t)pv.cum_segs[b] + seg_local;
-    float* slot = a.ws + (size_t)(w + seg) * kSlotFloats;
-    const int rows = si.n * a.G - rgi * kRowsPerGroup;
-    if (rows > 32) process_segment<2>(a, b, g, rgi, t0, t0 + nt, si, slot, lane);
-    else process_segment<1>(a, b, g, rgi, t0, t0 + nt, si, slot, lane);
+    const int64_t seg = (int64_t)sload(pv.cum_segs[1] + b) + seg_local;
+    float* slot = a.ws + (size_t)(w + seg) * kLargeSlot;
+    const int rows = si.n * a.G - rgi * kLargeRows;
+    if (rows > 32) large_segment<2>(a, b, g, rgi, t0, t0 + nt, si, slot, lane, q_lds);
+    else large_segment<1>(a, b, g, rgi, t0, t0 + nt, si, slot, lane, q_lds);
     u0 += nt;
   }
 }
@@ -382,7 +694,8 @@ struct CombineArgs {
   const int32_t* cu_nodes;
   const uint64_t* anc_mask;
   void* plan;
-  const float* ws;
+  const float* ws_small;
+  const float* ws_large;
   uint16_t* out;
   float* lse;
   int32_t batch, Hq, Hkv, G;
@@ -398,30 +711,53 @@ __device__ inline uint16_t f32_to_bf16(float v) {
 }
 
 // 8 lanes per query row; lane e of a row owns d = 4c .. 4c+3 for c = e, e+8, e+16, e+24.
+// Memory round trips are the cost here, so independent loads are issued in
+// batches: the plan entries together, four tree keys (K and V rows) at a time,
+// and all of a partial's pieces at once.
+constexpr int kKeyBatch = 4;
+
 __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int wc = blockIdx.x;
-  if (wc >= pv.cum_chunks[a.batch]) return;
-  int lo = 0, hi = a.batch;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (pv.cum_chunks[mid] <= wc) lo = mid; else hi = mid;
-  }
-  const int b = lo;
-  const SeqInfo si = pv.info[b];
-  const int M = si.n * a.G;
-  const int per_g = (M + kCombineRows - 1) / kCombineRows;
-  const int local = wc - pv.cum_chunks[b];
-  const int g = local / per_g, chunk = local % per_g;
   const int lane = threadIdx.x;
+  int b;
+  if (a.batch <= kWave) {
+    // cum_chunks is non-decreasing: lanes with cum <= wc are a prefix whose last lane is b
+    const int32_t cum = pv.cum_chunks[min(lane, a.batch - 1)];
+    const int32_t total = sload(pv.cum_chunks + a.batch);
+    if (wc >= total) return;
+    const uint64_t below = __ballot(lane < a.batch && cum <= wc);
+    b = __popcll(below) - 1;
+  } else {
+    if (wc >= sload(pv.cum_chunks + a.batch)) return;
+    int lo = 0, hi = a.batch;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (sload(pv.cum_chunks + mid) <= wc) lo = mid; else hi = mid;
+    }
+    b = lo;
+  }
+  const SeqInfo si = sload(pv.info + b);
+  const int M = si.n * a.G;
+  const int cls = seq_class(M);
+  const int chunk_base = sload(pv.cum_chunks + b);
+  const int base = sload(a.cu_nodes + b);
+  const int64_t U = sload(pv.header + 2 * cls), W = sload(pv.header + 2 * cls + 1);
+  const int64_t seg_base = sload(pv.cum_segs[cls] + b);
+  const int64_t unit_base = sload(pv.cum_units[cls] + b);
+  const int per_g = (M + kCombineRows - 1) / kCombineRows;
+  const int local = wc - chunk_base;
+  const int g = local / per_g, chunk = local % per_g;
   const int e = lane & 7;
   const int rho_raw = chunk * kCombineRows + (lane >> 3);
   const bool active = rho_raw < M;
   const int rho = active ? rho_raw : M - 1;
-  const int base = a.cu_nodes[b];
   const int node = base + rho / a.G, head = g * a.G + rho % a.G;
   const float c = a.scale_log2e;
 
+  // tree keys: the set bits of this row's ancestor mask, lowest first
+  uint64_t mlo = active ? a.anc_mask[2 * (size_t)node] : 0ull;
+  uint64_t mhi = active ? a.anc_mask[2 * (size_t)node + 1] : 0ull;
   float qv[16];
   {
     const uint16_t* qp = a.q + ((int64_t)node * a.Hq + head) * kD;
@@ -432,73 +768,88 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
       for (int i = 0; i < 4; ++i) qv[4 * k + i] = bf16_to_f32(x[i]);
     }
   }
+  if (si.n < 64) mlo &= (1ull << si.n) - 1ull, mhi = 0ull;           // never index past the tree
+  else if (si.n < 128) mhi &= (1ull << (si.n - 64)) - 1ull;
+
   float m = -INFINITY, l = 0.f, acc[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 
-  // tree keys: the set bits of this row's ancestor mask, lowest first
-  uint64_t mlo = active ? a.anc_mask[2 * (size_t)node] : 0ull;
-  uint64_t mhi = active ? a.anc_mask[2 * (size_t)node + 1] : 0ull;
-  if (si.n < 64) mlo &= (1ull << si.n) - 1ull, mhi = 0ull;           // never index past the tree
-  else if (si.n < 128) mhi &= (1ull << (si.n - 64)) - 1ull;
   while (__any((mlo | mhi) != 0ull)) {
-    const bool have = (mlo | mhi) != 0ull;
-    int jn = 0;
-    if (mlo) { jn = __ffsll((unsigned long long)mlo) - 1; mlo &= mlo - 1; }
-    else if (mhi) { jn = 64 + __ffsll((unsigned long long)mhi) - 1; mhi &= mhi - 1; }
-    const uint16_t* kp = a.k_tree + ((int64_t)(base + jn) * a.Hkv + g) * kD;
-    const uint16_t* vp = a.v_tree + ((int64_t)(base + jn) * a.Hkv + g) * kD;
-    float dot = 0.f;
+    int jn[kKeyBatch];
+    bool have[kKeyBatch];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const ushortx4 x = *(const ushortx4*)(kp + 4 * (e + 8 * k));
-#pragma unroll
-      for (int i = 0; i < 4; ++i) dot = fmaf(qv[4 * k + i], bf16_to_f32(x[i]), dot);
+    for (int u = 0; u < kKeyBatch; ++u) {
+      have[u] = (mlo | mhi) != 0ull;
+      jn[u] = 0;
+      if (mlo) { jn[u] = __ffsll((unsigned long long)mlo) - 1; mlo &= mlo - 1; }
+      else if (mhi) { jn[u] = 64 + __ffsll((unsigned long long)mhi) - 1; mhi &= mhi - 1; }
     }
-    dot += __shfl_xor(dot, 1);
-    dot += __shfl_xor(dot, 2);
-    dot += __shfl_xor(dot, 4);
-    if (have) {
-      const float m_new = fmaxf(m, dot);
-      const float al = __builtin_amdgcn_exp2f((m - m_new) * c);
-      const float p = __builtin_amdgcn_exp2f((dot - m_new) * c);
-      l = l * al + p;
+    ushortx4 kx[kKeyBatch][4], vx[kKeyBatch][4];
+#pragma unroll
+    for (int u = 0; u < kKeyBatch; ++u) {
+      const uint16_t* kp = a.k_tree + ((int64_t)(base + jn[u]) * a.Hkv + g) * kD;
+      const uint16_t* vp = a.v_tree + ((int64_t)(base + jn[u]) * a.Hkv + g) * kD;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        const ushortx4 x = *(const ushortx4*)(vp + 4 * (e + 8 * k));
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[4 * k + i] = acc[4 * k + i] * al + p * bf16_to_f32(x[i]);
+        kx[u][k] = *(const ushortx4*)(kp + 4 * (e + 8 * k));
+        vx[u][k] = *(const ushortx4*)(vp + 4 * (e + 8 * k));
       }
-      m = m_new;
+    }
+#pragma unroll
+    for (int u = 0; u < kKeyBatch; ++u) {
+      float dot = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dot = fmaf(qv[4 * k + i], bf16_to_f32(kx[u][k][i]), dot);
+      dot += __shfl_xor(dot, 1);
+      dot += __shfl_xor(dot, 2);
+      dot += __shfl_xor(dot, 4);
+      if (have[u]) {
+        const float m_new = fmaxf(m, dot);
+        const float al = __builtin_amdgcn_exp2f((m - m_new) * c);
+        const float p = __builtin_amdgcn_exp2f((dot - m_new) * c);
+        l = l * al + p;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[4 * k + i] = acc[4 * k + i] * al + p * bf16_to_f32(vx[u][k][i]);
+        m = m_new;
+      }
     }
   }
 
-  // prefix partials of this row's segment: workers w_first .. w_last
+  // prefix partials of this row's segment: workers w_first .. w_last of its class
   if (si.tiles > 0 && active) {
-    const int64_t U = pv.header[0], W = pv.header[1];
-    const int rgi = rho / kRowsPerGroup;
+    const int rows_per_group = cls == 0 ? kSmallRows : kLargeRows;
+    const int slot_floats = cls == 0 ? kSmallSlot : kLargeSlot;
+    const float* ws = cls == 0 ? a.ws_small : a.ws_large;
+    const int rgi = rho / rows_per_group;
     const int seg_local = g * si.rg + rgi;
-    const int64_t seg = (int64_t)pv.cum_segs[b] + seg_local;
-    const int64_t ub = pv.cum_units[b] + (int64_t)seg_local * si.tiles;
+    const int64_t seg = seg_base + seg_local;
+    const int64_t ub = unit_base + (int64_t)seg_local * si.tiles;
     const int64_t ue = ub + si.tiles - 1;
     const int64_t w_first = ((ub + 1) * W - 1) / U;
     const int64_t w_last = ((ue + 1) * W - 1) / U;
-    const int row = rho % kRowsPerGroup;  // = qt * 32 + j
+    const int row = rho % rows_per_group;  // = qt * 32 + j
     const int qt = row >> 5, j = row & 31;
     for (int64_t w = w_first; w <= w_last; ++w) {
-      const float* slot = a.ws + (size_t)(w + seg) * kSlotFloats;
-      const float mc = slot[kRowsPerGroup * kD + row];
-      const float lc = slot[kRowsPerGroup * kD + kRowsPerGroup + row];
+      const float* slot = ws + (size_t)(w + seg) * slot_floats;
+      const float mc = slot[rows_per_group * kD + row];
+      const float lc = slot[rows_per_group * kD + rows_per_group + row];
+      floatx4 x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        x[k] = *(const floatx4*)(slot + ((size_t)(qt * 32 + e + 8 * k) * 32 + j) * 4);
       const float m_new = fmaxf(m, mc);
       const float al = __builtin_amdgcn_exp2f((m - m_new) * c);
       const float wt = __builtin_amdgcn_exp2f((mc - m_new) * c);
       l = l * al + lc * wt;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const floatx4 x = *(const floatx4*)(slot + ((size_t)(qt * 32 + e + 8 * k) * 32 + j) * 4);
+      for (int k = 0; k < 4; ++k)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[4 * k + i] = acc[4 * k + i] * al + wt * x[i];
-      }
+        for (int i = 0; i < 4; ++i) acc[4 * k + i] = acc[4 * k + i] * al + wt * x[k][i];
       m = m_new;
     }
   }
@@ -520,18 +871,30 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
 
 namespace smart {
 
-int32_t tva_mfma_default_workers(const smart_ctx* ctx) {
-  // one wavefront per SIMD: 4 per compute unit
-  return (ctx->num_cus > 0 ? ctx->num_cus : 256) * 4;
+// class 1: one 8-wave workgroup per compute unit (two wavefronts per SIMD); class 2: one
+// single-wave workgroup per SIMD.
+static int32_t workers_small(const smart_ctx* ctx) {
+  return ctx->opt_workers > 0 ? (int32_t)ctx->opt_workers : (ctx->num_cus > 0 ? ctx->num_cus : 256);
+}
+static int32_t workers_large(const smart_ctx* ctx) {
+  return ctx->opt_workers > 0 ? (int32_t)ctx->opt_workers : (ctx->num_cus > 0 ? ctx->num_cus : 256) * 4;
+}
+int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return workers_small(ctx); }
+
+static size_t small_slots(const smart_ctx* ctx, int32_t batch, int32_t num_kv_heads) {
+  return (size_t)workers_small(ctx) + (size_t)num_kv_heads * batch + 1;
+}
+static size_t large_slots(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,
+                          int32_t num_kv_heads) {
+  const int64_t G = num_q_heads / num_kv_heads;
+  const int64_t segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
+  return (size_t)workers_large(ctx) + (size_t)segs + 1;
 }
 
-void tva_mfma_workspace(int32_t batch, int32_t total_nodes, int32_t num_q_heads,
-                        int32_t num_kv_heads, int32_t workers, size_t* ws_bytes,
-                        size_t* plan_bytes) {
-  const int64_t G = num_q_heads / num_kv_heads;
-  const int64_t segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kRowsPerGroup - 1) / kRowsPerGroup + batch);
-  const int64_t slots = (int64_t)workers + segs + 1;
-  *ws_bytes = (size_t)slots * kSlotFloats * sizeof(float);
+void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,
+                        int32_t num_kv_heads, size_t* ws_bytes, size_t* plan_bytes) {
+  *ws_bytes = (small_slots(ctx, batch, num_kv_heads) * kSmallSlot +
+               large_slots(ctx, batch, total_nodes, num_q_heads, num_kv_heads) * kLargeSlot) * sizeof(float);
   *plan_bytes = plan_bytes_for(batch);
 }
 
@@ -546,15 +909,17 @@ bool tva_mfma_supported(const tva_params& p) {
 int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p) {
   if (p.batch == 0 || p.total_nodes == 0) return SMART_OK;
   const int G = p.num_q_heads / p.num_kv_heads;
-  const int32_t workers = ctx->opt_workers > 0 ? (int32_t)ctx->opt_workers : tva_mfma_default_workers(ctx);
+  const int32_t w1 = workers_small(ctx), w2 = workers_large(ctx);
   size_t ws_bytes = 0, plan_bytes = 0;
-  tva_mfma_workspace(p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, workers, &ws_bytes, &plan_bytes);
+  tva_mfma_workspace(ctx, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, &ws_bytes, &plan_bytes);
   int32_t rc = ensure_workspace(ctx, stream, ws_bytes, plan_bytes);
   if (rc != SMART_OK) return rc;
+  float* ws_small = (float*)ctx->ws;
+  float* ws_large = ws_small + small_slots(ctx, p.batch, p.num_kv_heads) * kSmallSlot;
 
-  hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(256), 0, stream, (void*)ctx->plan, p.batch,
-                     p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workers,
-                     p.d_prefix_len, p.d_cu_nodes);
+  hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
+                     p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, w1, w2, p.d_prefix_len,
+                     p.d_cu_nodes);
   SMART_HIP_CHECK(hipGetLastError());
 
   MainArgs ma;
@@ -564,7 +929,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.block_table = p.d_block_table;
   ma.cu_nodes = p.d_cu_nodes;
   ma.plan = ctx->plan;
-  ma.ws = (float*)ctx->ws;
+  ma.ws = ws_small;
   ma.block_stride = p.cache_block_stride;
   ma.head_stride = p.cache_head_stride;
   ma.batch = p.batch;
@@ -574,8 +939,30 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.max_blocks = p.max_blocks_per_seq;
   ma.num_blocks = p.num_blocks;
   ma.scale_log2e = p.softmax_scale * kLog2e;
-  hipLaunchKernelGGL(tva_prefix_kernel, dim3(workers), dim3(kWave), 0, stream, ma);
-  SMART_HIP_CHECK(hipGetLastError());
+  // Which of the two classes occur?  Known exactly with a host copy of the tree offsets,
+  // otherwise both kernels are launched (a kernel without units returns at once).
+  bool need_small = true, need_large = (int64_t)p.total_nodes * G > kSmallRows;
+  if (p.h_cu_nodes) {
+    need_small = need_large = false;
+    for (int b = 0; b < p.batch; ++b) {
+      const int64_t rows = (int64_t)(p.h_cu_nodes[b + 1] - p.h_cu_nodes[b]) * G;
+      if (rows > kSmallRows) need_large = true;
+      else if (rows > 0) need_small = true;
+    }
+  }
+  rc = profile_begin(ctx, stream);
+  if (rc != SMART_OK) return rc;
+  if (need_small) {
+    hipLaunchKernelGGL(tva_prefix_small_kernel, dim3(w1), dim3(kSmallWaves * kWave), 0, stream, ma);
+    SMART_HIP_CHECK(hipGetLastError());
+  }
+  if (need_large) {
+    ma.ws = ws_large;
+    hipLaunchKernelGGL(tva_prefix_large_kernel, dim3(w2), dim3(kWave), 0, stream, ma);
+    SMART_HIP_CHECK(hipGetLastError());
+  }
+  rc = profile_end(ctx, stream);
+  if (rc != SMART_OK) return rc;
 
   CombineArgs ca;
   ca.q = (const uint16_t*)p.d_q;
@@ -584,7 +971,8 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ca.cu_nodes = p.d_cu_nodes;
   ca.anc_mask = p.d_anc_mask;
   ca.plan = ctx->plan;
-  ca.ws = (const float*)ctx->ws;
+  ca.ws_small = ws_small;
+  ca.ws_large = ws_large;
   ca.out = (uint16_t*)p.d_out;
   ca.lse = p.d_lse;
   ca.batch = p.batch;
