@@ -42,12 +42,17 @@ constexpr int kWave = 64;
 constexpr int kD = 128;
 constexpr int kBlock = 16;            // tokens per cache block
 constexpr int kTile = 32;             // keys per tile = two cache blocks
-constexpr int kSmallRows = 32;        // class 1: all rows of a (sequence, kv head) fit one MFMA tile
-constexpr int kLargeRows = 64;        // class 2: rows per row group (two MFMA tiles)
+constexpr int kClasses = 3;           // sequences are classed by rows = nodes x group heads per kv head
+constexpr int kSmallRows = 32;        // class 0: all rows fit one 32-row MFMA tile
+constexpr int kMediumRows = 64;       // class 1: all rows fit two MFMA tiles of one wavefront
+constexpr int kLargeRows = 256;       // class 2: row groups of 256 = one workgroup of eight wavefronts x 32 rows
 constexpr int kSmallSlot = kSmallRows * kD + 2 * kSmallRows;  // floats: O, then max, then sum
+constexpr int kMediumSlot = kMediumRows * kD + 2 * kMediumRows;
 constexpr int kLargeSlot = kLargeRows * kD + 2 * kLargeRows;
+__host__ __device__ inline int class_rows(int cls) { return cls == 0 ? kSmallRows : (cls == 1 ? kMediumRows : kLargeRows); }
+__host__ __device__ inline int class_slot(int cls) { return cls == 0 ? kSmallSlot : (cls == 1 ? kMediumSlot : kLargeSlot); }
 constexpr int kCombineRows = 8;       // rows per combine wavefront (8 lanes per row)
-constexpr int kMinTilesPerWorker[2] = {16, 8};  // class 1 workers are 8-wave workgroups
+constexpr int kMinTilesPerWorker[kClasses] = {16, 8, 8};  // class 0 workers are 8-wave workgroups
 constexpr int kChunkTiles = 64;       // tiles whose block ids one pair of registers holds
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -55,9 +60,10 @@ constexpr float kLog2e = 1.4426950408889634f;
 // launch plan (device memory, written by tva_plan_kernel)
 //
 // A "unit" is one 32-key tile of one (sequence, kv head, row group) segment.
-// Sequences fall in two classes with separate unit spaces and kernels:
-//   class 1  n * G <= 32 rows: one row group, the bandwidth-bound kernel
-//   class 2  more rows: row groups of 64 rows
+// Sequences fall in three classes with separate unit spaces and kernels:
+//   class 0  n * G <= 32 rows: one row group, eight wavefronts share a worker's tiles
+//   class 1  33 .. 64 rows: one row group, one wavefront per worker, two MFMA row tiles
+//   class 2  more rows: row groups of 256 rows, four wavefronts x 64 rows per worker
 // ---------------------------------------------------------------------------
 struct SeqInfo {
   int32_t len;    // prefix length, clamped
@@ -67,16 +73,17 @@ struct SeqInfo {
 };
 
 struct PlanView {
-  int64_t* header;        // [0] U1, [1] W1, [2] U2, [3] W2
-  int64_t* cum_units[2];  // [B+1] per class: units before sequence b
-  int32_t* cum_segs[2];   // [B+1] per class: segments before sequence b
+  int64_t* header;               // [2c] units U_c, [2c+1] workers W_c of class c
+  int64_t* cum_units[kClasses];  // [B+1] per class: units before sequence b
+  int32_t* cum_segs[kClasses];   // [B+1] per class: segments before sequence b
   int32_t* cum_chunks;    // [B+1] combine row chunks before sequence b
   SeqInfo* info;          // [B]
 };
 
 __host__ __device__ inline size_t plan_bytes_for(int batch) {
   const size_t n = (size_t)batch + 2;
-  return sizeof(int64_t) * (8 + 2 * n) + sizeof(SeqInfo) * (size_t)batch + sizeof(int32_t) * 3 * n + 64;
+  return sizeof(int64_t) * (8 + kClasses * n) + sizeof(SeqInfo) * (size_t)batch +
+         sizeof(int32_t) * (kClasses + 1) * n + 64;
 }
 
 __host__ __device__ inline PlanView plan_view(void* base, int batch) {
@@ -85,21 +92,21 @@ __host__ __device__ inline PlanView plan_view(void* base, int batch) {
   char* p = (char*)base;
   v.header = (int64_t*)p;
   p += sizeof(int64_t) * 8;
-  v.cum_units[0] = (int64_t*)p;
-  p += sizeof(int64_t) * n;
-  v.cum_units[1] = (int64_t*)p;
-  p += sizeof(int64_t) * n;
+  for (int c = 0; c < kClasses; ++c) {
+    v.cum_units[c] = (int64_t*)p;
+    p += sizeof(int64_t) * n;
+  }
   v.info = (SeqInfo*)p;
   p += sizeof(SeqInfo) * (size_t)batch;
-  v.cum_segs[0] = (int32_t*)p;
-  p += sizeof(int32_t) * n;
-  v.cum_segs[1] = (int32_t*)p;
-  p += sizeof(int32_t) * n;
+  for (int c = 0; c < kClasses; ++c) {
+    v.cum_segs[c] = (int32_t*)p;
+    p += sizeof(int32_t) * n;
+  }
   v.cum_chunks = (int32_t*)p;
   return v;
 }
 
-__host__ __device__ inline int seq_class(int rows) { return rows <= kSmallRows ? 0 : 1; }
+__host__ __device__ inline int seq_class(int rows) { return rows <= kSmallRows ? 0 : (rows <= kMediumRows ? 1 : 2); }
 
 // One wavefront.  Lane t owns a contiguous range of sequences; an exclusive
 // shuffle scan over the per-lane sums ties the ranges together.
@@ -114,13 +121,14 @@ __device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
 }
 
 __global__ __launch_bounds__(kWave) void tva_plan_kernel(
-    void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int max_workers1,
-    int max_workers2, const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ cu_nodes) {
+    void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int max_workers0,
+    int max_workers1, int max_workers2, const int32_t* __restrict__ prefix_len,
+    const int32_t* __restrict__ cu_nodes) {
   PlanView pv = plan_view(plan_base, batch);
   const int t = threadIdx.x;
   const int per = (batch + kWave - 1) / kWave;
   const int b0 = min(batch, t * per), b1 = min(batch, b0 + per);
-  int64_t units[2] = {0, 0}, segs[2] = {0, 0}, chunks = 0;
+  int64_t units[kClasses] = {0, 0, 0}, segs[kClasses] = {0, 0, 0}, chunks = 0;
   for (int b = b0; b < b1; ++b) {
     int len = prefix_len[b];
     const int cap = max_blocks * kBlock;
@@ -134,25 +142,25 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     si.len = len;
     si.n = n;
     si.tiles = (len + kTile - 1) / kTile;
-    si.rg = rows == 0 ? 0 : (seq_class(rows) == 0 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
+    si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
     pv.info[b] = si;
     const int c = seq_class(rows);
     units[c] += (int64_t)si.tiles * Hkv * si.rg;
     segs[c] += Hkv * si.rg;
     chunks += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
   }
-  int64_t tot_u[2], tot_s[2], tot_c, u[2], s[2];
-  for (int c = 0; c < 2; ++c) {
+  int64_t tot_u[kClasses], tot_s[kClasses], tot_c, u[kClasses], s[kClasses];
+  for (int c = 0; c < kClasses; ++c) {
     u[c] = wave_excl_scan(units[c], t, &tot_u[c]);
     s[c] = wave_excl_scan(segs[c], t, &tot_s[c]);
   }
   int64_t ch = wave_excl_scan(chunks, t, &tot_c);
   if (t == 0) {
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < kClasses; ++c) {
       pv.cum_units[c][batch] = tot_u[c];
       pv.cum_segs[c][batch] = (int32_t)tot_s[c];
       int64_t w = tot_u[c] / kMinTilesPerWorker[c];
-      const int64_t mw = c == 0 ? max_workers1 : max_workers2;
+      const int64_t mw = c == 0 ? max_workers0 : (c == 1 ? max_workers1 : max_workers2);
       w = w < 1 ? 1 : (w > mw ? mw : w);
       pv.header[2 * c] = tot_u[c];
       pv.header[2 * c + 1] = w;
@@ -163,10 +171,10 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     const SeqInfo si = pv.info[b];
     const int rows = si.n * G;
     const int c = seq_class(rows);
-    pv.cum_units[0][b] = u[0];
-    pv.cum_units[1][b] = u[1];
-    pv.cum_segs[0][b] = (int32_t)s[0];
-    pv.cum_segs[1][b] = (int32_t)s[1];
+    for (int k = 0; k < kClasses; ++k) {
+      pv.cum_units[k][b] = u[k];
+      pv.cum_segs[k][b] = (int32_t)s[k];
+    }
     pv.cum_chunks[b] = (int32_t)ch;
     u[c] += (int64_t)si.tiles * Hkv * si.rg;
     s[c] += Hkv * si.rg;
@@ -584,20 +592,65 @@ void tva_prefix_small_kernel(MainArgs a) {
   }
 }
 
-// ---- class 2: row groups of 64 rows (two MFMA tiles per wavefront) -----------------------
+// ---- class 2: more than 32 rows per (sequence, kv head) -----------------------------------
 //
-// K and V each have one register buffer; the next tile's K is requested as
-// soon as the scores are done and its V as soon as the output product is done.
-template <int QT>
-__device__ inline void large_segment(const MainArgs& a, int b, int g, int rgi, int t0, int t1,
-                                     const SeqInfo si, float* slot, int lane, bf16x8* q_lds) {
-  const int h = lane >> 5, j = lane & 31;
-  const int M = si.n * a.G;
-  const int base = sload(a.cu_nodes + b);
+// A workgroup of four wavefronts (one per SIMD) is the worker; it streams the
+// tiles of its share once for a row group of up to 256 query rows, wavefront w
+// carrying rows 64 w .. 64 w + 63 of the group as two 32-row MFMA tiles.  The
+// four wavefronts read the same K/V tiles at about the same time, so the
+// second to fourth read of a tile is an L1 / L2 hit and HBM sees it once.
+// Wavefronts write disjoint row slices of the worker's partial: no barriers.
+// Query operands live in LDS (64 registers otherwise) and are re-read per tile.
+template <int QT, bool kMasked>
+__device__ inline void large_tile(floatx16 (&o)[QT][4], float (&m)[QT], float (&l)[QT], bf16x8 (&k)[8],
+                                  bf16x8 (&v)[2][4], const bf16x8* q_lds, int lane, float c, int n_valid,
+                                  const MainArgs& a, const TilePages& next) {
+  int q_off = lane;
+  asm volatile("" : "+v"(q_off));  // keeps the query reads inside the loop (they would cost 32 QT registers)
+  // one 32-row tile after the other, so that only one score tile is live at a time; K is
+  // released after the last score product, V after the last output product
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    int rho = rgi * kLargeRows + qt * 32 + j;
-    rho = rho < M ? rho : M - 1;
+    floatx16 s = (floatx16)(0.f);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {  // query operands four at a time: 16 registers in flight
+      bf16x8 qop[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) qop[i] = q_lds[(qt * 8 + half * 4 + i) * kWave + q_off];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[half * 4 + i], qop[i], s, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (qt == QT - 1) load_k(k, a, next, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kMasked) mask_tail(s, v, n_valid, lane >> 5);
+    bf16x8 pb0, pb1;
+    softmax_tile(s, m[qt], l[qt], o[qt], pb0, pb1, c);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) {
+      o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[0][jt], pb0, o[qt][jt], 0, 0, 0);
+      o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[1][jt], pb1, o[qt][jt], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  load_v(v, a, next, lane);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// Streams tiles [t0, t1) of (sequence b, kv head g) against rows row0 .. row0 + 32 QT - 1 and
+// writes this wavefront's row slice of the partial.
+template <int QT>
+__device__ inline void large_segment(const MainArgs& a, int b, int g, int base, int row0, int t0, int t1,
+                                     const SeqInfo si, float* slot, int rows_in_slot, int qt0, int lane,
+                                     bf16x8* q_lds) {
+  const int h = lane >> 5, j = lane & 31;
+  const int M = si.n * a.G;
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    int rho = row0 + qt * 32 + j;
+    rho = rho < M ? rho : M - 1;  // padding rows repeat the last real row; never read back
     const int node = base + rho / a.G, head = g * a.G + rho % a.G;
     const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
 #pragma unroll
@@ -616,46 +669,237 @@ __device__ inline void large_segment(const MainArgs& a, int b, int g, int rgi, i
   const int n_blocks = (si.len + kBlock - 1) / kBlock;
   const float c = a.scale_log2e;
 
-  bf16x8 k[8], v[2][4];
-  TilePages tp = tile_pages(a, bt_row, t0, n_blocks, g);
-  load_k(k, a, tp, lane);
-  load_v(v, a, tp, lane);
-  for (int t = t0; t < t1; ++t) {
-    // past the end the last tile is requested again (an L2 hit) instead of predicating the loads
-    tp = tile_pages(a, bt_row, min(t + 1, t1 - 1), n_blocks, g);
-    const int n_valid = min(kTile, si.len - t * kTile);
-    floatx16 s[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      s[qt] = (floatx16)(0.f);
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[ks], q_lds[(qt * 8 + ks) * kWave + lane],
-                                                        s[qt], 0, 0, 0);
+  for (int tc = t0; tc < t1; tc += kChunkTiles) {
+    const int te = min(t1, tc + kChunkTiles);
+    BlockIds ids;
+    ids.lo = bt_row[min(2 * tc + lane, n_blocks - 1)];
+    ids.hi = bt_row[min(2 * tc + kWave + lane, n_blocks - 1)];
+    asm volatile("" ::"v"(ids.lo), "v"(ids.hi));  // landed before the stream starts (see class 1)
+    const int full_end = min(te, si.len / kTile);
+    bf16x8 k[8], v[2][4];
+    {
+      const TilePages first = pages_from_ids(a, ids, 0, g);
+      load_k(k, a, first, lane);
+      load_v(v, a, first, lane);
     }
-    load_k(k, a, tp, lane);
-    if (n_valid < kTile) {
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) mask_tail(s[qt], v, n_valid, h);
+    int t = tc;
+    for (; t < full_end; ++t) {
+      const TilePages next = pages_from_ids(a, ids, min(t + 1, te - 1) - tc, g);
+      large_tile<QT, false>(o, m, l, k, v, q_lds, lane, c, kTile, a, next);
     }
-    bf16x8 pb[QT][2];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) softmax_tile(s[qt], m[qt], l[qt], o[qt], pb[qt][0], pb[qt][1], c);
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-      for (int jt = 0; jt < 4; ++jt) {
-        o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[0][jt], pb[qt][0], o[qt][jt], 0, 0, 0);
-        o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[1][jt], pb[qt][1], o[qt][jt], 0, 0, 0);
-      }
-    load_v(v, a, tp, lane);
+    if (t < te) {  // the ragged last tile of the sequence
+      const TilePages next = pages_from_ids(a, ids, te - 1 - tc, g);
+      large_tile<QT, true>(o, m, l, k, v, q_lds, lane, c, si.len - t * kTile, a, next);
+    }
   }
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) store_partial(slot, kLargeRows, qt, o[qt], m[qt], l[qt], lane);
+  for (int qt = 0; qt < QT; ++qt) store_partial(slot, rows_in_slot, qt0 + qt, o[qt], m[qt], l[qt], lane);
 }
 
-__global__ __launch_bounds__(kWave) void tva_prefix_large_kernel(MainArgs a) {
-  __shared__ bf16x8 q_lds[2 * 8 * kWave];  // 16 KB: two 32-row tiles of query operands
+// ---- class 2: K/V tiles staged in LDS, shared by the eight wavefronts of a workgroup --------
+//
+// A workgroup of eight wavefronts (two per SIMD) is the worker; it streams the
+// tiles of its share once for a row group of up to 256 query rows, wavefront w
+// carrying rows 32 w .. 32 w + 31 (one MFMA row tile).  A tile (16 KB: 8 K + 8 V
+// operand vectors per lane) is fetched from HBM once per workgroup: each
+// wavefront requests an eighth of it (two vectors per lane), FOUR tiles ahead,
+// into a ring of registers, so a compute unit keeps about 48 KB in flight.  The
+// tile is written to LDS in operand order -- the vector a lane will feed to the
+// MFMA sits at [instruction][lane], so reads are 16 bytes per lane at
+// consecutive addresses, free of bank conflicts -- into one of two buffers:
+// tile t+1 is written while tile t is being multiplied, one barrier per tile.
+constexpr int kLargeWaves = 8;
+constexpr int kRing = 4;
+
+struct Eighth {
+  bf16x8 part[2];  // this wavefront's share of a tile: instructions 2 wv, 2 wv + 1
+};
+
+__device__ inline void request_eighth(Eighth& e, const MainArgs& a, const TilePages& tp, int wv, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  if (wv < 4) {  // K vectors of k steps 2 wv, 2 wv + 1
+    const int64_t mask = -(int64_t)(j >> 4);
+    const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
+    const __bf16* kp = a.k_cache + page + (h * 16 + sigma(j & 15)) * 8 + wv * 2 * 256;
+    e.part[0] = *(const bf16x8*)(kp);
+    e.part[1] = *(const bf16x8*)(kp + 256);
+  } else {  // V vectors of cache block (wv - 4) / 2, d tiles 2 ((wv - 4) % 2) + {0, 1}
+    const int kk = (wv - 4) >> 1, jt0 = 2 * ((wv - 4) & 1);
+    const __bf16* vp = a.v_cache + (kk == 0 ? tp.page0 : tp.page1) + (h * kD + j) * 8 + jt0 * 256;
+    e.part[0] = *(const bf16x8*)(vp);
+    e.part[1] = *(const bf16x8*)(vp + 256);
+  }
+}
+
+// Zeroes the V entries of tokens >= n_valid (ragged end of a prefix; unowned slots may hold NaN).
+__device__ inline void zero_invalid_v(Eighth& e, int wv, int lane, int n_valid) {
+  if (wv < 4) return;
+  const int h = lane >> 5, kk = (wv - 4) >> 1;
+#pragma unroll
+  for (int x = 0; x < 8; ++x)
+    if (kk * 16 + h * 8 + x >= n_valid) {
+      e.part[0][x] = (__bf16)0.f;
+      e.part[1][x] = (__bf16)0.f;
+    }
+}
+
+__device__ inline void mask_scores(floatx16& s, int n_valid, int h) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int i = 8 * (r >> 2) + 4 * h + (r & 3);
+    const int tok = (i & 16) + sigma(i & 15);
+    if (tok >= n_valid) s[r] = -INFINITY;
+  }
+}
+
+// One tile from LDS against this wavefront's 32 query rows.
+__device__ inline void staged_tile(floatx16 (&o)[4], float& m, float& l, const bf16x8* kv, const bf16x8* q_lds,
+                                   int lane, float c, int n_valid) {
+  int off = lane;
+  asm volatile("" : "+v"(off));  // keeps the LDS reads inside the loop
+  floatx16 s = (floatx16)(0.f);
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    bf16x8 kop[4], qop[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      kop[i] = kv[(half * 4 + i) * kWave + off];
+      qop[i] = q_lds[(half * 4 + i) * kWave + off];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[i], qop[i], s, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (n_valid < kTile) mask_scores(s, n_valid, lane >> 5);
+  bf16x8 pb0, pb1;
+  softmax_tile(s, m, l, o, pb0, pb1, c);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    bf16x8 vop[4];
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) vop[jt] = kv[(8 + kk * 4 + jt) * kWave + off];
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+      o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[jt], kk == 0 ? pb0 : pb1, o[jt], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// All eight wavefronts of the workgroup run this together (it contains barriers);
+// kRows = false marks a wavefront without rows in this row group: it only helps to fetch.
+template <bool kRows>
+__device__ inline void staged_segment(const MainArgs& a, int b, int g, int base, int row0, int t0, int t1,
+                                      const SeqInfo si, float* slot, int wv, int lane, bf16x8* q_lds,
+                                      bf16x8* kv_lds) {
+  const int h = lane >> 5, j = lane & 31;
+  const int M = si.n * a.G;
+  floatx16 o[4];
+  float m = -INFINITY, l = 0.f;
+  if (kRows) {
+    int rho = row0 + j;
+    rho = rho < M ? rho : M - 1;  // padding rows repeat the last real row; never read back
+    const int node = base + rho / a.G, head = g * a.G + rho % a.G;
+    const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) q_lds[ks * kWave + lane] = *(const bf16x8*)(qp + ks * 16);
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) o[jt] = (floatx16)(0.f);
+  }
+  const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
+  const int n_blocks = (si.len + kBlock - 1) / kBlock;
+  const float c = a.scale_log2e;
+
+  for (int tc = t0; tc < t1; tc += kChunkTiles) {
+    const int te = min(t1, tc + kChunkTiles);
+    BlockIds ids;
+    ids.lo = bt_row[min(2 * tc + lane, n_blocks - 1)];
+    ids.hi = bt_row[min(2 * tc + kWave + lane, n_blocks - 1)];
+    asm volatile("" ::"v"(ids.lo), "v"(ids.hi));
+    // ring of four tiles: tile tc + i in slot i; requests past the end repeat the last tile (an L2 hit)
+    Eighth ring[kRing];
+#pragma unroll
+    for (int i = 0; i < kRing; ++i)
+      request_eighth(ring[i], a, pages_from_ids(a, ids, min(i, te - 1 - tc), g), wv, lane);
+    auto publish = [&](Eighth& e, int t) {  // tile t -> LDS buffer t & 1
+      const int n_valid = si.len - t * kTile;
+      if (n_valid < kTile) zero_invalid_v(e, wv, lane, n_valid);
+      bf16x8* dst = kv_lds + (t & 1) * 16 * kWave + (2 * wv) * kWave + lane;
+      dst[0] = e.part[0];
+      dst[kWave] = e.part[1];
+    };
+    __syncthreads();  // the previous chunk / piece is done with both buffers
+    publish(ring[0], tc);
+    __syncthreads();
+    // iteration t: publish tile t + 1 (other buffer), request tile t + 4 into the slot tile t came
+    // from, multiply tile t, meet
+    auto iter = [&](int t, Eighth& next_tile, Eighth& free_slot) {
+      if (t + 1 < te) publish(next_tile, t + 1);
+      request_eighth(free_slot, a, pages_from_ids(a, ids, min(t + kRing, te - 1) - tc, g), wv, lane);
+      if (kRows) staged_tile(o, m, l, kv_lds + (t & 1) * 16 * kWave, q_lds, lane, c, min(kTile, si.len - t * kTile));
+      __syncthreads();
+    };
+    int t = tc;
+    for (; t + kRing <= te; t += kRing) {
+      iter(t, ring[1], ring[0]);
+      iter(t + 1, ring[2], ring[1]);
+      iter(t + 2, ring[3], ring[2]);
+      iter(t + 3, ring[0], ring[3]);
+    }
+    if (t < te) {
+      iter(t, ring[1], ring[0]);
+      if (t + 1 < te) {
+        iter(t + 1, ring[2], ring[1]);
+        if (t + 2 < te) iter(t + 2, ring[3], ring[2]);
+      }
+    }
+  }
+  if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane);
+}
+
+__global__ __launch_bounds__(kLargeWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void tva_prefix_large_kernel(MainArgs a) {
+  __shared__ bf16x8 q_lds_all[kLargeWaves * 8 * kWave];  // 64 KB: one 32-row query tile per wavefront
+  __shared__ bf16x8 kv_lds[2 * 16 * kWave];              // 32 KB: two K/V tiles in operand order
+  const PlanView pv = plan_view(a.plan, a.batch);
+  const int64_t U = sload(pv.header + 4), W = sload(pv.header + 5);
+  const int64_t w = blockIdx.x;
+  if (w >= W || U <= 0) return;
+  int64_t u0 = (w * U) / W;
+  const int64_t u1 = ((w + 1) * U) / W;
+  if (u0 >= u1) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  bf16x8* q_lds = q_lds_all + wv * (8 * kWave);
+  PlanWindow win;
+  int b = locate(win, pv, a.cu_nodes, 2, a.batch, u0, lane);
+  while (u0 < u1 && b < a.batch) {
+    if (b - win.first >= kWave - 1) load_window(win, pv, a.cu_nodes, 2, a.batch, b, lane);
+    const int64_t seq_begin = readlane64(win.cum_units, b - win.first);
+    const int64_t seq_end = readlane64(win.cum_units, b + 1 - win.first);
+    if (u0 >= seq_end) { ++b; continue; }
+    const SeqInfo si = window_info(win, b);
+    const int64_t local = u0 - seq_begin;
+    const int seg_local = (int)(local / si.tiles);
+    const int t0 = (int)(local % si.tiles);
+    const int g = seg_local / si.rg, rgi = seg_local % si.rg;
+    const int64_t left = u1 - u0;
+    const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
+    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
+    const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
+    float* slot = a.ws + (size_t)(w + seg) * kLargeSlot;
+    // rows of the group are dealt to the eight wavefronts in 32-row tiles
+    const int row0 = rgi * kLargeRows + wv * 32;
+    if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, q_lds, kv_lds);
+    else staged_segment<false>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, q_lds, kv_lds);
+    u0 += nt;
+  }
+}
+
+// ---- class 1: 33 .. 64 rows: one wavefront per worker, two MFMA row tiles -----------------
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void tva_prefix_medium_kernel(MainArgs a) {
+  __shared__ bf16x8 q_lds[2 * 8 * kWave];  // 16 KB: two 32-row query tiles
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = sload(pv.header + 2), W = sload(pv.header + 3);
   const int64_t w = blockIdx.x;
@@ -664,22 +908,23 @@ __global__ __launch_bounds__(kWave) void tva_prefix_large_kernel(MainArgs a) {
   const int64_t u1 = ((w + 1) * U) / W;
   if (u0 >= u1) return;
   const int lane = threadIdx.x;
-  int b = find_sequence(pv.cum_units[1], a.batch, u0);
+  PlanWindow win;
+  int b = locate(win, pv, a.cu_nodes, 1, a.batch, u0, lane);
   while (u0 < u1 && b < a.batch) {
-    const int64_t seq_begin = sload(pv.cum_units[1] + b), seq_end = sload(pv.cum_units[1] + b + 1);
+    if (b - win.first >= kWave - 1) load_window(win, pv, a.cu_nodes, 1, a.batch, b, lane);
+    const int64_t seq_begin = readlane64(win.cum_units, b - win.first);
+    const int64_t seq_end = readlane64(win.cum_units, b + 1 - win.first);
     if (u0 >= seq_end) { ++b; continue; }
-    const SeqInfo si = sload(pv.info + b);
+    const SeqInfo si = window_info(win, b);
     const int64_t local = u0 - seq_begin;
-    const int seg_local = (int)(local / si.tiles);
+    const int g = (int)(local / si.tiles);
     const int t0 = (int)(local % si.tiles);
-    const int g = seg_local / si.rg, rgi = seg_local % si.rg;
     const int64_t left = u1 - u0;
     const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
-    const int64_t seg = (int64_t)sload(pv.cum_segs[1] + b) + seg_local;
-    float* slot = a.ws + (size_t)(w + seg) * kLargeSlot;
-    const int rows = si.n * a.G - rgi * kLargeRows;
-    if (rows > 32) large_segment<2>(a, b, g, rgi, t0, t0 + nt, si, slot, lane, q_lds);
-    else large_segment<1>(a, b, g, rgi, t0, t0 + nt, si, slot, lane, q_lds);
+    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + g;
+    const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
+    large_segment<2>(a, b, g, base, 0, t0, t0 + nt, si, a.ws + (size_t)(w + seg) * kMediumSlot, kMediumRows, 0,
+                     lane, q_lds);
     u0 += nt;
   }
 }
@@ -694,8 +939,7 @@ struct CombineArgs {
   const int32_t* cu_nodes;
   const uint64_t* anc_mask;
   void* plan;
-  const float* ws_small;
-  const float* ws_large;
+  const float* ws[kClasses];
   uint16_t* out;
   float* lse;
   int32_t batch, Hq, Hkv, G;
@@ -822,9 +1066,9 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
 
   // prefix partials of this row's segment: workers w_first .. w_last of its class
   if (si.tiles > 0 && active) {
-    const int rows_per_group = cls == 0 ? kSmallRows : kLargeRows;
-    const int slot_floats = cls == 0 ? kSmallSlot : kLargeSlot;
-    const float* ws = cls == 0 ? a.ws_small : a.ws_large;
+    const int rows_per_group = class_rows(cls);
+    const int slot_floats = class_slot(cls);
+    const float* ws = cls == 0 ? a.ws[0] : (cls == 1 ? a.ws[1] : a.ws[2]);
     const int rgi = rho / rows_per_group;
     const int seg_local = g * si.rg + rgi;
     const int64_t seg = seg_base + seg_local;
@@ -871,30 +1115,30 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
 
 namespace smart {
 
-// class 1: one 8-wave workgroup per compute unit (two wavefronts per SIMD); class 2: one
-// single-wave workgroup per SIMD.
-static int32_t workers_small(const smart_ctx* ctx) {
-  return ctx->opt_workers > 0 ? (int32_t)ctx->opt_workers : (ctx->num_cus > 0 ? ctx->num_cus : 256);
+// Workers per class: class 0 one 8-wave workgroup per compute unit (two wavefronts per SIMD);
+// class 1 one single-wave workgroup per wavefront slot (two per SIMD); class 2 one 8-wave
+// workgroup per compute unit.
+static int32_t class_workers(const smart_ctx* ctx, int cls) {
+  if (ctx->opt_workers > 0) return (int32_t)ctx->opt_workers;
+  const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+  return cls == 0 ? cus : (cls == 1 ? cus * 8 : cus);
 }
-static int32_t workers_large(const smart_ctx* ctx) {
-  return ctx->opt_workers > 0 ? (int32_t)ctx->opt_workers : (ctx->num_cus > 0 ? ctx->num_cus : 256) * 4;
-}
-int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return workers_small(ctx); }
+int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return class_workers(ctx, 0); }
 
-static size_t small_slots(const smart_ctx* ctx, int32_t batch, int32_t num_kv_heads) {
-  return (size_t)workers_small(ctx) + (size_t)num_kv_heads * batch + 1;
-}
-static size_t large_slots(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,
-                          int32_t num_kv_heads) {
+static size_t class_slots(const smart_ctx* ctx, int cls, int32_t batch, int32_t total_nodes,
+                          int32_t num_q_heads, int32_t num_kv_heads) {
   const int64_t G = num_q_heads / num_kv_heads;
-  const int64_t segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
-  return (size_t)workers_large(ctx) + (size_t)segs + 1;
+  int64_t segs = (int64_t)num_kv_heads * batch;  // one row group per sequence in classes 0 and 1
+  if (cls == 2) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
+  return (size_t)class_workers(ctx, cls) + (size_t)segs + 1;
 }
 
 void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,
                         int32_t num_kv_heads, size_t* ws_bytes, size_t* plan_bytes) {
-  *ws_bytes = (small_slots(ctx, batch, num_kv_heads) * kSmallSlot +
-               large_slots(ctx, batch, total_nodes, num_q_heads, num_kv_heads) * kLargeSlot) * sizeof(float);
+  size_t floats = 0;
+  for (int c = 0; c < kClasses; ++c)
+    floats += class_slots(ctx, c, batch, total_nodes, num_q_heads, num_kv_heads) * class_slot(c);
+  *ws_bytes = floats * sizeof(float);
   *plan_bytes = plan_bytes_for(batch);
 }
 
@@ -909,16 +1153,18 @@ bool tva_mfma_supported(const tva_params& p) {
 int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p) {
   if (p.batch == 0 || p.total_nodes == 0) return SMART_OK;
   const int G = p.num_q_heads / p.num_kv_heads;
-  const int32_t w1 = workers_small(ctx), w2 = workers_large(ctx);
+  const int32_t w0 = class_workers(ctx, 0), w1 = class_workers(ctx, 1), w2 = class_workers(ctx, 2);
   size_t ws_bytes = 0, plan_bytes = 0;
   tva_mfma_workspace(ctx, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, &ws_bytes, &plan_bytes);
   int32_t rc = ensure_workspace(ctx, stream, ws_bytes, plan_bytes);
   if (rc != SMART_OK) return rc;
-  float* ws_small = (float*)ctx->ws;
-  float* ws_large = ws_small + small_slots(ctx, p.batch, p.num_kv_heads) * kSmallSlot;
+  float* ws[kClasses];
+  ws[0] = (float*)ctx->ws;
+  for (int c = 1; c < kClasses; ++c)
+    ws[c] = ws[c - 1] + class_slots(ctx, c - 1, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads) * class_slot(c - 1);
 
   hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
-                     p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, w1, w2, p.d_prefix_len,
+                     p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, w0, w1, w2, p.d_prefix_len,
                      p.d_cu_nodes);
   SMART_HIP_CHECK(hipGetLastError());
 
@@ -929,7 +1175,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.block_table = p.d_block_table;
   ma.cu_nodes = p.d_cu_nodes;
   ma.plan = ctx->plan;
-  ma.ws = ws_small;
+  ma.ws = ws[0];
   ma.block_stride = p.cache_block_stride;
   ma.head_stride = p.cache_head_stride;
   ma.batch = p.batch;
@@ -939,26 +1185,30 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.max_blocks = p.max_blocks_per_seq;
   ma.num_blocks = p.num_blocks;
   ma.scale_log2e = p.softmax_scale * kLog2e;
-  // Which of the two classes occur?  Known exactly with a host copy of the tree offsets,
-  // otherwise both kernels are launched (a kernel without units returns at once).
-  bool need_small = true, need_large = (int64_t)p.total_nodes * G > kSmallRows;
+  // Which classes occur?  Known exactly with a host copy of the tree offsets, otherwise every
+  // kernel is launched (a kernel without units returns at once).
+  bool need[kClasses] = {true, (int64_t)p.total_nodes * G > kSmallRows, (int64_t)p.total_nodes * G > kMediumRows};
   if (p.h_cu_nodes) {
-    need_small = need_large = false;
+    need[0] = need[1] = need[2] = false;
     for (int b = 0; b < p.batch; ++b) {
       const int64_t rows = (int64_t)(p.h_cu_nodes[b + 1] - p.h_cu_nodes[b]) * G;
-      if (rows > kSmallRows) need_large = true;
-      else if (rows > 0) need_small = true;
+      if (rows > 0) need[seq_class((int)(rows > 0x7FFFFFFF ? 0x7FFFFFFF : rows))] = true;
     }
   }
   rc = profile_begin(ctx, stream);
   if (rc != SMART_OK) return rc;
-  if (need_small) {
-    hipLaunchKernelGGL(tva_prefix_small_kernel, dim3(w1), dim3(kSmallWaves * kWave), 0, stream, ma);
+  if (need[0]) {
+    hipLaunchKernelGGL(tva_prefix_small_kernel, dim3(w0), dim3(kSmallWaves * kWave), 0, stream, ma);
     SMART_HIP_CHECK(hipGetLastError());
   }
-  if (need_large) {
-    ma.ws = ws_large;
-    hipLaunchKernelGGL(tva_prefix_large_kernel, dim3(w2), dim3(kWave), 0, stream, ma);
+  if (need[1]) {
+    ma.ws = ws[1];
+    hipLaunchKernelGGL(tva_prefix_medium_kernel, dim3(w1), dim3(kWave), 0, stream, ma);
+    SMART_HIP_CHECK(hipGetLastError());
+  }
+  if (need[2]) {
+    ma.ws = ws[2];
+    hipLaunchKernelGGL(tva_prefix_large_kernel, dim3(w2), dim3(kLargeWaves * kWave), 0, stream, ma);
     SMART_HIP_CHECK(hipGetLastError());
   }
   rc = profile_end(ctx, stream);
@@ -971,8 +1221,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ca.cu_nodes = p.d_cu_nodes;
   ca.anc_mask = p.d_anc_mask;
   ca.plan = ctx->plan;
-  ca.ws_small = ws_small;
-  ca.ws_large = ws_large;
+  for (int c = 0; c < kClasses; ++c) ca.ws[c] = ws[c];
   ca.out = (uint16_t*)p.d_out;
   ca.lse = p.d_lse;
   ca.batch = p.batch;
