@@ -46,6 +46,7 @@ constexpr int kClasses = 3;           // sequences are classed by rows = nodes x
 constexpr int kSmallRows = 32;        // class 0: all rows fit one 32-row MFMA tile
 constexpr int kMediumRows = 64;       // class 1: all rows fit two MFMA tiles of one wavefront
 constexpr int kLargeRows = 256;       // class 2: row groups of 256 = one workgroup of eight wavefronts x 32 rows
+constexpr int kWgWaves = 8;           // wavefronts per workgroup of the prefix kernel (two per SIMD)
 constexpr int kSmallSlot = kSmallRows * kD + 2 * kSmallRows;  // floats: O, then max, then sum
 constexpr int kMediumSlot = kMediumRows * kD + 2 * kMediumRows;
 constexpr int kLargeSlot = kLargeRows * kD + 2 * kLargeRows;
@@ -73,7 +74,7 @@ struct SeqInfo {
 };
 
 struct PlanView {
-  int64_t* header;               // [2c] units U_c, [2c+1] workers W_c of class c
+  int64_t* header;               // [2c] units U_c, [2c+1] workers W_c, [6+c] first workgroup of class c
   int64_t* cum_units[kClasses];  // [B+1] per class: units before sequence b
   int32_t* cum_segs[kClasses];   // [B+1] per class: segments before sequence b
   int32_t* cum_chunks;    // [B+1] combine row chunks before sequence b
@@ -82,7 +83,7 @@ struct PlanView {
 
 __host__ __device__ inline size_t plan_bytes_for(int batch) {
   const size_t n = (size_t)batch + 2;
-  return sizeof(int64_t) * (8 + kClasses * n) + sizeof(SeqInfo) * (size_t)batch +
+  return sizeof(int64_t) * (16 + kClasses * n) + sizeof(SeqInfo) * (size_t)batch +
          sizeof(int32_t) * (kClasses + 1) * n + 64;
 }
 
@@ -91,7 +92,7 @@ __host__ __device__ inline PlanView plan_view(void* base, int batch) {
   const size_t n = (size_t)batch + 2;
   char* p = (char*)base;
   v.header = (int64_t*)p;
-  p += sizeof(int64_t) * 8;
+  p += sizeof(int64_t) * 16;
   for (int c = 0; c < kClasses; ++c) {
     v.cum_units[c] = (int64_t*)p;
     p += sizeof(int64_t) * n;
@@ -121,9 +122,8 @@ __device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
 }
 
 __global__ __launch_bounds__(kWave) void tva_plan_kernel(
-    void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int max_workers0,
-    int max_workers1, int max_workers2, const int32_t* __restrict__ prefix_len,
-    const int32_t* __restrict__ cu_nodes) {
+    void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int workgroups,
+    const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ cu_nodes) {
   PlanView pv = plan_view(plan_base, batch);
   const int t = threadIdx.x;
   const int per = (batch + kWave - 1) / kWave;
@@ -156,15 +156,36 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   }
   int64_t ch = wave_excl_scan(chunks, t, &tot_c);
   if (t == 0) {
+    // The prefix kernel is ONE launch of `workgroups` (+ slack) workgroups; the classes share
+    // them in proportion to their work, so that all of them finish together.  A class-2 tile
+    // costs more than its bytes (it is multiplied against up to 256 rows).
+    const int64_t weight[kClasses] = {2, 2, 3};
+    int64_t cost[kClasses], total = 0;
+    for (int c = 0; c < kClasses; ++c) {
+      cost[c] = tot_u[c] * weight[c];
+      total += cost[c];
+    }
+    int64_t wg[kClasses], used = 0;
+    for (int c = 0; c < kClasses; ++c) {
+      wg[c] = tot_u[c] > 0 ? (cost[c] * workgroups + total / 2) / total : 0;
+      if (tot_u[c] > 0 && wg[c] < 1) wg[c] = 1;
+      used += wg[c];
+    }
+    // rounding may overshoot by at most one per class; the launch carries that much slack
+    int64_t first = 0;
     for (int c = 0; c < kClasses; ++c) {
       pv.cum_units[c][batch] = tot_u[c];
       pv.cum_segs[c][batch] = (int32_t)tot_s[c];
-      int64_t w = tot_u[c] / kMinTilesPerWorker[c];
-      const int64_t mw = c == 0 ? max_workers0 : (c == 1 ? max_workers1 : max_workers2);
-      w = w < 1 ? 1 : (w > mw ? mw : w);
+      int64_t w = wg[c] * (c == 1 ? kWgWaves : 1);  // class 1 workers are single wavefronts
+      const int64_t cap = tot_u[c] / kMinTilesPerWorker[c];
+      if (w > cap) w = cap;
+      if (tot_u[c] > 0 && w < 1) w = 1;
       pv.header[2 * c] = tot_u[c];
       pv.header[2 * c + 1] = w;
+      pv.header[6 + c] = first;
+      first += c == 1 ? (w + kWgWaves - 1) / kWgWaves : w;
     }
+    pv.header[6 + kClasses] = first;
     pv.cum_chunks[batch] = (int32_t)tot_c;
   }
   for (int b = b0; b < b1; ++b) {
@@ -192,7 +213,7 @@ struct MainArgs {
   const int32_t* block_table;
   const int32_t* cu_nodes;
   void* plan;
-  float* ws;  // partial slots of this kernel's class
+  float* ws[3];  // partial slots per class
   int64_t block_stride, head_stride;
   int32_t batch, Hq, Hkv, G, max_blocks, num_blocks;
   float scale_log2e;
@@ -545,14 +566,11 @@ __device__ inline int locate(PlanWindow& w, const PlanView& pv, const int32_t* c
 // contiguous sub-ranges, one per wavefront, and the eight running states are
 // folded together through LDS in three rounds, so that a piece leaves ONE
 // partial in memory however many wavefronts streamed it.
-constexpr int kSmallWaves = 8;
+constexpr int kSmallWaves = kWgWaves;
 
-__global__ __launch_bounds__(kSmallWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void tva_prefix_small_kernel(MainArgs a) {
-  __shared__ float merge_lds[(kSmallWaves / 2) * kStateFloats];  // 66 KB
+__device__ inline void small_worker(const MainArgs& a, int64_t w, float* merge_lds /* 66 KB */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = sload(pv.header), W = sload(pv.header + 1);
-  const int64_t w = blockIdx.x;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
@@ -587,7 +605,7 @@ void tva_prefix_small_kernel(MainArgs a) {
       if (wv < half) merge_from_lds(S, merge_lds + wv * kStateFloats, lane, a.scale_log2e);
       __syncthreads();
     }
-    if (wv == 0) store_partial(a.ws + (size_t)(w + seg) * kSmallSlot, kSmallRows, 0, S.o, S.m, S.l, lane);
+    if (wv == 0) store_partial(a.ws[0] + (size_t)(w + seg) * kSmallSlot, kSmallRows, 0, S.o, S.m, S.l, lane);
     u0 += nt;
   }
 }
@@ -708,7 +726,7 @@ __device__ inline void large_segment(const MainArgs& a, int b, int g, int base, 
 // MFMA sits at [instruction][lane], so reads are 16 bytes per lane at
 // consecutive addresses, free of bank conflicts -- into one of two buffers:
 // tile t+1 is written while tile t is being multiplied, one barrier per tile.
-constexpr int kLargeWaves = 8;
+constexpr int kLargeWaves = kWgWaves;
 constexpr int kRing = 4;
 
 struct Eighth {
@@ -857,13 +875,11 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
   if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane);
 }
 
-__global__ __launch_bounds__(kLargeWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void tva_prefix_large_kernel(MainArgs a) {
-  __shared__ bf16x8 q_lds_all[kLargeWaves * 8 * kWave];  // 64 KB: one 32-row query tile per wavefront
-  __shared__ bf16x8 kv_lds[2 * 16 * kWave];              // 32 KB: two K/V tiles in operand order
+__device__ inline void large_worker(const MainArgs& a, int64_t w, bf16x8* lds /* 96 KB */) {
+  bf16x8* q_lds_all = lds;                              // 64 KB: one 32-row query tile per wavefront
+  bf16x8* kv_lds = lds + kLargeWaves * 8 * kWave;       // 32 KB: two K/V tiles in operand order
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = sload(pv.header + 4), W = sload(pv.header + 5);
-  const int64_t w = blockIdx.x;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
@@ -887,7 +903,7 @@ void tva_prefix_large_kernel(MainArgs a) {
     const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
     const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
     const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
-    float* slot = a.ws + (size_t)(w + seg) * kLargeSlot;
+    float* slot = a.ws[2] + (size_t)(w + seg) * kLargeSlot;
     // rows of the group are dealt to the eight wavefronts in 32-row tiles
     const int row0 = rgi * kLargeRows + wv * 32;
     if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, q_lds, kv_lds);
@@ -897,17 +913,14 @@ void tva_prefix_large_kernel(MainArgs a) {
 }
 
 // ---- class 1: 33 .. 64 rows: one wavefront per worker, two MFMA row tiles -----------------
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void tva_prefix_medium_kernel(MainArgs a) {
-  __shared__ bf16x8 q_lds[2 * 8 * kWave];  // 16 KB: two 32-row query tiles
+__device__ inline void medium_worker(const MainArgs& a, int64_t w, bf16x8* q_lds /* 16 KB of this wavefront */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = sload(pv.header + 2), W = sload(pv.header + 3);
-  const int64_t w = blockIdx.x;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
   if (u0 >= u1) return;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & (kWave - 1);
   PlanWindow win;
   int b = locate(win, pv, a.cu_nodes, 1, a.batch, u0, lane);
   while (u0 < u1 && b < a.batch) {
@@ -923,9 +936,27 @@ void tva_prefix_medium_kernel(MainArgs a) {
     const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
     const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + g;
     const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
-    large_segment<2>(a, b, g, base, 0, t0, t0 + nt, si, a.ws + (size_t)(w + seg) * kMediumSlot, kMediumRows, 0,
+    large_segment<2>(a, b, g, base, 0, t0, t0 + nt, si, a.ws[1] + (size_t)(w + seg) * kMediumSlot, kMediumRows, 0,
                      lane, q_lds);
     u0 += nt;
+  }
+}
+
+// ---- the prefix kernel: one launch, workgroups apportioned to the classes by the plan ------
+__global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void tva_prefix_kernel(MainArgs a) {
+  __shared__ float4 lds_raw[8192];  // 128 KB, carved up per class
+  const PlanView pv = plan_view(a.plan, a.batch);
+  const int64_t wg = blockIdx.x;
+  const int64_t first1 = sload(pv.header + 7), first2 = sload(pv.header + 8), end = sload(pv.header + 9);
+  if (wg >= end) return;
+  if (wg < first1) {
+    small_worker(a, wg, (float*)lds_raw);
+  } else if (wg < first2) {
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    medium_worker(a, (wg - first1) * kWgWaves + wv, (bf16x8*)lds_raw + wv * (2 * 8 * kWave));
+  } else {
+    large_worker(a, wg - first2, (bf16x8*)lds_raw);
   }
 }
 
@@ -1115,15 +1146,17 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
 
 namespace smart {
 
-// Workers per class: class 0 one 8-wave workgroup per compute unit (two wavefronts per SIMD);
-// class 1 one single-wave workgroup per wavefront slot (two per SIMD); class 2 one 8-wave
-// workgroup per compute unit.
-static int32_t class_workers(const smart_ctx* ctx, int cls) {
+// Workgroups of the prefix kernel: one per compute unit (eight wavefronts, two per SIMD).  The
+// plan deals them to the classes; a class never gets more workers than this bound.
+static int32_t prefix_workgroups(const smart_ctx* ctx) {
   if (ctx->opt_workers > 0) return (int32_t)ctx->opt_workers;
-  const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
-  return cls == 0 ? cus : (cls == 1 ? cus * 8 : cus);
+  return ctx->num_cus > 0 ? ctx->num_cus : 256;
 }
-int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return class_workers(ctx, 0); }
+static int32_t class_workers(const smart_ctx* ctx, int cls) {
+  const int32_t wg = prefix_workgroups(ctx) + 1;
+  return cls == 1 ? wg * kWgWaves : wg;
+}
+int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return prefix_workgroups(ctx); }
 
 static size_t class_slots(const smart_ctx* ctx, int cls, int32_t batch, int32_t total_nodes,
                           int32_t num_q_heads, int32_t num_kv_heads) {
@@ -1153,7 +1186,7 @@ bool tva_mfma_supported(const tva_params& p) {
 int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p) {
   if (p.batch == 0 || p.total_nodes == 0) return SMART_OK;
   const int G = p.num_q_heads / p.num_kv_heads;
-  const int32_t w0 = class_workers(ctx, 0), w1 = class_workers(ctx, 1), w2 = class_workers(ctx, 2);
+  const int32_t workgroups = prefix_workgroups(ctx);
   size_t ws_bytes = 0, plan_bytes = 0;
   tva_mfma_workspace(ctx, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, &ws_bytes, &plan_bytes);
   int32_t rc = ensure_workspace(ctx, stream, ws_bytes, plan_bytes);
@@ -1164,7 +1197,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
     ws[c] = ws[c - 1] + class_slots(ctx, c - 1, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads) * class_slot(c - 1);
 
   hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
-                     p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, w0, w1, w2, p.d_prefix_len,
+                     p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
                      p.d_cu_nodes);
   SMART_HIP_CHECK(hipGetLastError());
 
@@ -1175,7 +1208,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.block_table = p.d_block_table;
   ma.cu_nodes = p.d_cu_nodes;
   ma.plan = ctx->plan;
-  ma.ws = ws[0];
+  for (int c = 0; c < kClasses; ++c) ma.ws[c] = ws[c];
   ma.block_stride = p.cache_block_stride;
   ma.head_stride = p.cache_head_stride;
   ma.batch = p.batch;
@@ -1185,32 +1218,11 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.max_blocks = p.max_blocks_per_seq;
   ma.num_blocks = p.num_blocks;
   ma.scale_log2e = p.softmax_scale * kLog2e;
-  // Which classes occur?  Known exactly with a host copy of the tree offsets, otherwise every
-  // kernel is launched (a kernel without units returns at once).
-  bool need[kClasses] = {true, (int64_t)p.total_nodes * G > kSmallRows, (int64_t)p.total_nodes * G > kMediumRows};
-  if (p.h_cu_nodes) {
-    need[0] = need[1] = need[2] = false;
-    for (int b = 0; b < p.batch; ++b) {
-      const int64_t rows = (int64_t)(p.h_cu_nodes[b + 1] - p.h_cu_nodes[b]) * G;
-      if (rows > 0) need[seq_class((int)(rows > 0x7FFFFFFF ? 0x7FFFFFFF : rows))] = true;
-    }
-  }
   rc = profile_begin(ctx, stream);
   if (rc != SMART_OK) return rc;
-  if (need[0]) {
-    hipLaunchKernelGGL(tva_prefix_small_kernel, dim3(w0), dim3(kSmallWaves * kWave), 0, stream, ma);
-    SMART_HIP_CHECK(hipGetLastError());
-  }
-  if (need[1]) {
-    ma.ws = ws[1];
-    hipLaunchKernelGGL(tva_prefix_medium_kernel, dim3(w1), dim3(kWave), 0, stream, ma);
-    SMART_HIP_CHECK(hipGetLastError());
-  }
-  if (need[2]) {
-    ma.ws = ws[2];
-    hipLaunchKernelGGL(tva_prefix_large_kernel, dim3(w2), dim3(kLargeWaves * kWave), 0, stream, ma);
-    SMART_HIP_CHECK(hipGetLastError());
-  }
+  // the plan may round every class up by one workgroup
+  hipLaunchKernelGGL(tva_prefix_kernel, dim3(workgroups + kClasses), dim3(kWgWaves * kWave), 0, stream, ma);
+  SMART_HIP_CHECK(hipGetLastError());
   rc = profile_end(ctx, stream);
   if (rc != SMART_OK) return rc;
 
