@@ -1018,8 +1018,11 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   const int chunk_base = sload(pv.cum_chunks + b);
   const int base = sload(a.cu_nodes + b);
   const int64_t U = sload(pv.header + 2 * cls), W = sload(pv.header + 2 * cls + 1);
-  const int64_t seg_base = sload(pv.cum_segs[cls] + b);
-  const int64_t unit_base = sload(pv.cum_units[cls] + b);
+  // (selected with compares: indexing the pointer arrays with a run-time class would push the plan view to scratch)
+  const int32_t* segs_c = cls == 0 ? pv.cum_segs[0] : (cls == 1 ? pv.cum_segs[1] : pv.cum_segs[2]);
+  const int64_t* units_c = cls == 0 ? pv.cum_units[0] : (cls == 1 ? pv.cum_units[1] : pv.cum_units[2]);
+  const int64_t seg_base = sload(segs_c + b);
+  const int64_t unit_base = sload(units_c + b);
   const int per_g = (M + kCombineRows - 1) / kCombineRows;
   const int local = wc - chunk_base;
   const int g = local / per_g, chunk = local % per_g;

@@ -123,6 +123,29 @@ def test_bf16_group_sizes_and_big_trees(lib, oracle_attention, G, Hkv):
     check_full(lib, oracle_attention, case)
 
 
+def test_many_sequences_all_classes_and_window_reload(lib, oracle_attention):
+    """More than 64 sequences (the plan lookup leaves its 64-sequence window), all three row
+    classes in one batch, empty prefixes and one-node trees in between."""
+    rng = np.random.default_rng(77)
+    B_ = 150
+    sizes = rng.choice([1, 2, 5, 8, 9, 14, 16, 17, 30, 64, 65, 100], size=B_)
+    trees = [W.random_tree(int(n), rng) for n in sizes]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    lens = rng.integers(0, 200, size=B_).astype(np.int32)
+    lens[::7] = 0
+    lens[3] = 1500                      # one long prefix: pieces longer than the block-id window
+    w = W.Workload("many", "bf16", B_, 8, 2, 128, 0, 0, seed=55)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=lens,
+                     trees=(cu, np.concatenate(trees).astype(np.int32)))
+    check_full(lib, oracle_attention, case)
+    for workers in (3, 1000):
+        lib.set_option(B.SMART_OPT_TVA_WORKERS, workers)
+        try:
+            check_full(lib, oracle_attention, case)
+        finally:
+            lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
+
+
 # ----- the bf16 configurations ------------------------------------------------------------
 def test_cfg2_full(lib, oracle_attention):
     check_full(lib, oracle_attention, make_case(W.WORKLOADS["cfg2"], B.SMART_KV_INTERLEAVED))
