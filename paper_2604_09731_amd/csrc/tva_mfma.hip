@@ -729,36 +729,90 @@ __device__ inline void large_segment(const MainArgs& a, int b, int g, int base, 
 constexpr int kLargeWaves = kWgWaves;
 constexpr int kRing = 4;
 
-struct Eighth {
-  bf16x8 part[2];  // this wavefront's share of a tile: instructions 2 wv, 2 wv + 1
+// K/V tiles travel HBM -> LDS without passing through registers (global_load_lds, 16 bytes a
+// lane).  A stage holds one 32-key tile in operand order: eight K vectors (k steps) then
+// eight V vectors (cache block kk, d tile jt at 4 kk + jt), 64 lanes x 16 bytes each;
+// wavefront w fetches vectors 2 w and 2 w + 1 of every tile.  kStages tiles are in flight.
+constexpr int kStages = 8;
+constexpr int kStageVecs = 16 * kWave;
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_void;
+
+__device__ inline uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lds_void*)p; }
+
+// What a lane fetches of every tile: fixed offset inside a page, and which of the tile's two
+// pages (mask all ones: the second).
+struct FetchLane {
+  const __bf16* base;
+  int64_t second_page;
 };
 
-__device__ inline void request_eighth(Eighth& e, const MainArgs& a, const TilePages& tp, int wv, int lane) {
+__device__ inline FetchLane fetch_lane(const MainArgs& a, int wv, int lane) {
   const int h = lane >> 5, j = lane & 31;
-  if (wv < 4) {  // K vectors of k steps 2 wv, 2 wv + 1
-    const int64_t mask = -(int64_t)(j >> 4);
-    const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
-    const __bf16* kp = a.k_cache + page + (h * 16 + sigma(j & 15)) * 8 + wv * 2 * 256;
-    e.part[0] = *(const bf16x8*)(kp);
-    e.part[1] = *(const bf16x8*)(kp + 256);
+  FetchLane f;
+  if (wv < 4) {  // K vectors of k steps 2 wv, 2 wv + 1: key row j, head dims 16 ks + 8 h ..
+    f.base = a.k_cache + (h * 16 + sigma(j & 15)) * 8 + wv * 2 * 256;
+    f.second_page = -(int64_t)(j >> 4);
   } else {  // V vectors of cache block (wv - 4) / 2, d tiles 2 ((wv - 4) % 2) + {0, 1}
-    const int kk = (wv - 4) >> 1, jt0 = 2 * ((wv - 4) & 1);
-    const __bf16* vp = a.v_cache + (kk == 0 ? tp.page0 : tp.page1) + (h * kD + j) * 8 + jt0 * 256;
-    e.part[0] = *(const bf16x8*)(vp);
-    e.part[1] = *(const bf16x8*)(vp + 256);
+    f.base = a.v_cache + (h * kD + j) * 8 + 2 * ((wv - 4) & 1) * 256;
+    f.second_page = -(int64_t)((wv - 4) >> 1);
+  }
+  return f;
+}
+
+__device__ inline void request_tile(const MainArgs& a, const FetchLane& f, int32_t blk0, int32_t blk1, int g,
+                                    bf16x8* stage, int wv) {
+  const int64_t page0 = clamp_block(blk0, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
+  const int64_t page1 = clamp_block(blk1, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
+  const __bf16* src = f.base + (page0 ^ ((page0 ^ page1) & f.second_page));
+  bf16x8* dst = stage + 2 * wv * kWave;
+  __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst, 16, 0, 0);
+  __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(dst + kWave), 16, 0, 0);
+}
+
+// LDS reads of the staged tiles are written as assembly: the compiler would otherwise wait
+// for every outstanding global_load_lds before each read it can see.  The counter waits
+// below carry the registers they release as operands, so that no use can move above them.
+#define SMART_LDS_READ(dst, addr, OFFSET) \
+  asm volatile("ds_read_b128 %0, %1 offset:" #OFFSET : "=v"(dst) : "v"(addr) : "memory")
+#define SMART_LDS_WAIT(reg, N) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(reg) : : "memory")
+
+__device__ inline void lds_read_half(bf16x8 (&r)[8], uint32_t addr, int half) {
+  if (half == 0) {
+    SMART_LDS_READ(r[0], addr, 0);
+    SMART_LDS_READ(r[1], addr, 1024);
+    SMART_LDS_READ(r[2], addr, 2048);
+    SMART_LDS_READ(r[3], addr, 3072);
+  } else {
+    SMART_LDS_READ(r[4], addr, 4096);
+    SMART_LDS_READ(r[5], addr, 5120);
+    SMART_LDS_READ(r[6], addr, 6144);
+    SMART_LDS_READ(r[7], addr, 7168);
   }
 }
 
-// Zeroes the V entries of tokens >= n_valid (ragged end of a prefix; unowned slots may hold NaN).
-__device__ inline void zero_invalid_v(Eighth& e, int wv, int lane, int n_valid) {
+// The V fetchers clear the entries of tokens >= n_valid in their two vectors of a landed
+// stage (ragged end of a prefix; unowned slots may hold NaN).
+__device__ inline void zero_invalid_v_lds(bf16x8* stage, int wv, int lane, int n_valid) {
   if (wv < 4) return;
   const int h = lane >> 5, kk = (wv - 4) >> 1;
+  const uint32_t addr = lds_address(stage + 2 * wv * kWave + lane);
+  bf16x8 v0, v1;
+  SMART_LDS_READ(v0, addr, 0);
+  SMART_LDS_READ(v1, addr, 1024);
+  SMART_LDS_WAIT(v0, 0);
+  SMART_LDS_WAIT(v1, 0);
 #pragma unroll
   for (int x = 0; x < 8; ++x)
     if (kk * 16 + h * 8 + x >= n_valid) {
-      e.part[0][x] = (__bf16)0.f;
-      e.part[1][x] = (__bf16)0.f;
+      v0[x] = (__bf16)0.f;
+      v1[x] = (__bf16)0.f;
     }
+  asm volatile("ds_write_b128 %0, %1\n\tds_write_b128 %0, %2 offset:1024\n\ts_waitcnt lgkmcnt(0)"
+               :
+               : "v"(addr), "v"(v0), "v"(v1)
+               : "memory");
 }
 
 __device__ inline void mask_scores(floatx16& s, int n_valid, int h) {
@@ -770,49 +824,107 @@ __device__ inline void mask_scores(floatx16& s, int n_valid, int h) {
   }
 }
 
-// One tile from LDS against this wavefront's 32 query rows.
-__device__ inline void staged_tile(floatx16 (&o)[4], float& m, float& l, const bf16x8* kv, const bf16x8* q_lds,
-                                   int lane, float c, int n_valid) {
-  int off = lane;
-  asm volatile("" : "+v"(off));  // keeps the LDS reads inside the loop
-  floatx16 s = (floatx16)(0.f);
+// Scores of one staged tile (used for the first tile of a segment only).
+__device__ inline void score_tile(floatx16& s, uint32_t k_addr, const bf16x8 (&q)[8]) {
+  bf16x8 kop[8];
+  lds_read_half(kop, k_addr, 0);
+  lds_read_half(kop, k_addr, 1);
+  SMART_LDS_WAIT(kop[0], 0);
+  s = (floatx16)(0.f);
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    bf16x8 kop[4], qop[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      kop[i] = kv[(half * 4 + i) * kWave + off];
-      qop[i] = q_lds[(half * 4 + i) * kWave + off];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[i], qop[i], s, 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+  for (int ks = 0; ks < 8; ++ks) {
+    if (ks > 0) SMART_LDS_WAIT(kop[ks], 0);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks], q[ks], s, 0, 0, 0);
   }
-  if (n_valid < kTile) mask_scores(s, n_valid, lane >> 5);
-  bf16x8 pb0, pb1;
-  softmax_tile(s, m, l, o, pb0, pb1, c);
+}
+
+// One iteration of a wavefront with rows: softmax and output product of tile t (scores
+// s_in, V at v_addr) with the score product of tile t + 1 (K at k_addr, result s_out) woven
+// in, so that the matrix cores run in the shadow of the exponentials:
+//   8 x { score MFMA k step i | exp of first-half probability i }
+//   4 x { output MFMA (first cache block, d tile jt) | exp of second-half probabilities 2 jt, 2 jt + 1 }
+//   4 x   output MFMA (second cache block)
+// The scheduling barriers keep that order.  `between` runs after the first LDS reads are
+// issued (the caller's fetch requests go there, in the shadow of the LDS latency).  The
+// counts of the LDS waits follow the order in which the 16 reads are issued: K 0..7 and
+// V 0..3 up front, V 4..7 after the fourth score step.
+template <typename Between>
+__device__ inline void woven_tile(const floatx16& s, floatx16& s_next, floatx16 (&o)[4], float& m, float& l,
+                                  const bf16x8 (&q)[8], uint32_t k_addr, uint32_t v_addr, float c,
+                                  Between between) {
+  bf16x8 kop[8], vop[8];
+  lds_read_half(kop, k_addr, 0);
+  lds_read_half(kop, k_addr, 1);
+  lds_read_half(vop, v_addr, 0);
+  between();
+  float mx = s[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+  mx = max_across_halves(mx);
+  const float m_new = fmaxf(m, mx);
+  if (__any(m_new > m)) {  // rescale only when some row's maximum moved
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+    l *= alpha;
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) o[jt] *= alpha;
+    m = m_new;
+  }
+  const float mc = m * c;
+  s_next = (floatx16)(0.f);
+  floatx8 p0, p1;
+  float sum = 0.f;
   __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int kk = 0; kk < 2; ++kk) {
-    bf16x8 vop[4];
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt) vop[jt] = kv[(8 + kk * 4 + jt) * kWave + off];
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-      o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[jt], kk == 0 ? pb0 : pb1, o[jt], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+#define SMART_SCORE_STEP(I, N)                                                        \
+  SMART_LDS_WAIT(kop[I], N);                                                          \
+  s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[I], q[I], s_next, 0, 0, 0);    \
+  p0[I] = __builtin_amdgcn_exp2f(fmaf(s[I], c, -mc));                                 \
+  sum += p0[I];                                                                       \
+  __builtin_amdgcn_sched_barrier(0);
+  SMART_SCORE_STEP(0, 11)
+  SMART_SCORE_STEP(1, 10)
+  SMART_SCORE_STEP(2, 9)
+  SMART_SCORE_STEP(3, 8)
+  lds_read_half(vop, v_addr, 1);  // outstanding: K 4..7, V 0..7
+  SMART_SCORE_STEP(4, 11)
+  SMART_SCORE_STEP(5, 10)
+  SMART_SCORE_STEP(6, 9)
+  SMART_SCORE_STEP(7, 8)
+#undef SMART_SCORE_STEP
+  const bf16x8 pb0 = __builtin_convertvector(p0, bf16x8);
+  __builtin_amdgcn_sched_barrier(0);
+#define SMART_OUTPUT_STEP(JT, N)                                                      \
+  SMART_LDS_WAIT(vop[JT], N);                                                         \
+  o[JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[JT], pb0, o[JT], 0, 0, 0);      \
+  p1[2 * JT] = __builtin_amdgcn_exp2f(fmaf(s[8 + 2 * JT], c, -mc));                   \
+  p1[2 * JT + 1] = __builtin_amdgcn_exp2f(fmaf(s[9 + 2 * JT], c, -mc));               \
+  sum += p1[2 * JT] + p1[2 * JT + 1];                                                 \
+  __builtin_amdgcn_sched_barrier(0);
+  SMART_OUTPUT_STEP(0, 7)
+  SMART_OUTPUT_STEP(1, 6)
+  SMART_OUTPUT_STEP(2, 5)
+  SMART_OUTPUT_STEP(3, 4)
+#undef SMART_OUTPUT_STEP
+  l += sum;
+  const bf16x8 pb1 = __builtin_convertvector(p1, bf16x8);
+  SMART_LDS_WAIT(vop[4], 3);
+  o[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[4], pb1, o[0], 0, 0, 0);
+  SMART_LDS_WAIT(vop[5], 2);
+  o[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[5], pb1, o[1], 0, 0, 0);
+  SMART_LDS_WAIT(vop[6], 1);
+  o[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[6], pb1, o[2], 0, 0, 0);
+  SMART_LDS_WAIT(vop[7], 0);
+  o[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[7], pb1, o[3], 0, 0, 0);
 }
 
 // All eight wavefronts of the workgroup run this together (it contains barriers);
 // kRows = false marks a wavefront without rows in this row group: it only helps to fetch.
 template <bool kRows>
 __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base, int row0, int t0, int t1,
-                                      const SeqInfo si, float* slot, int wv, int lane, bf16x8* q_lds,
-                                      bf16x8* kv_lds) {
+                                      const SeqInfo si, float* slot, int wv, int lane, bf16x8* lds) {
   const int h = lane >> 5, j = lane & 31;
   const int M = si.n * a.G;
   floatx16 o[4];
+  bf16x8 q[8];
   float m = -INFINITY, l = 0.f;
   if (kRows) {
     int rho = row0 + j;
@@ -820,64 +932,73 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
     const int node = base + rho / a.G, head = g * a.G + rho % a.G;
     const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) q_lds[ks * kWave + lane] = *(const bf16x8*)(qp + ks * 16);
+    for (int ks = 0; ks < 8; ++ks) q[ks] = *(const bf16x8*)(qp + ks * 16);
 #pragma unroll
     for (int jt = 0; jt < 4; ++jt) o[jt] = (floatx16)(0.f);
+    asm volatile("" ::"v"(q[0]), "v"(q[7]));  // landed: the counted waits below see tile fetches only
   }
   const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
   const int n_blocks = (si.len + kBlock - 1) / kBlock;
   const float c = a.scale_log2e;
+  const FetchLane f = fetch_lane(a, wv, lane);
+  const uint32_t rd = lds_address(lds + lane);  // this lane's slice of vector 0 of stage 0
+  const int last = t1 - 1;
+  auto stage_of = [&](int t) { return lds + (t & (kStages - 1)) * kStageVecs; };
+  auto block_id = [&](int t, int which) { return sload(bt_row + min(2 * min(t, last) + which, n_blocks - 1)); };
+  auto land = [&](int t) {  // after this wavefront's share of tile t arrived: mend a ragged tile
+    const int n_valid = si.len - t * kTile;
+    if (t <= last && n_valid < kTile) zero_invalid_v_lds(stage_of(t), wv, lane, n_valid);
+  };
 
-  for (int tc = t0; tc < t1; tc += kChunkTiles) {
-    const int te = min(t1, tc + kChunkTiles);
-    BlockIds ids;
-    ids.lo = bt_row[min(2 * tc + lane, n_blocks - 1)];
-    ids.hi = bt_row[min(2 * tc + kWave + lane, n_blocks - 1)];
-    asm volatile("" ::"v"(ids.lo), "v"(ids.hi));
-    // ring of four tiles: tile tc + i in slot i; requests past the end repeat the last tile (an L2 hit)
-    Eighth ring[kRing];
+  __builtin_amdgcn_s_barrier();  // the previous segment is done with every stage
 #pragma unroll
-    for (int i = 0; i < kRing; ++i)
-      request_eighth(ring[i], a, pages_from_ids(a, ids, min(i, te - 1 - tc), g), wv, lane);
-    auto publish = [&](Eighth& e, int t) {  // tile t -> LDS buffer t & 1
-      const int n_valid = si.len - t * kTile;
-      if (n_valid < kTile) zero_invalid_v(e, wv, lane, n_valid);
-      bf16x8* dst = kv_lds + (t & 1) * 16 * kWave + (2 * wv) * kWave + lane;
-      dst[0] = e.part[0];
-      dst[kWave] = e.part[1];
-    };
-    __syncthreads();  // the previous chunk / piece is done with both buffers
-    publish(ring[0], tc);
-    __syncthreads();
-    // iteration t: publish tile t + 1 (other buffer), request tile t + 4 into the slot tile t came
-    // from, multiply tile t, meet
-    auto iter = [&](int t, Eighth& next_tile, Eighth& free_slot) {
-      if (t + 1 < te) publish(next_tile, t + 1);
-      request_eighth(free_slot, a, pages_from_ids(a, ids, min(t + kRing, te - 1) - tc, g), wv, lane);
-      if (kRows) staged_tile(o, m, l, kv_lds + (t & 1) * 16 * kWave, q_lds, lane, c, min(kTile, si.len - t * kTile));
-      __syncthreads();
-    };
-    int t = tc;
-    for (; t + kRing <= te; t += kRing) {
-      iter(t, ring[1], ring[0]);
-      iter(t + 1, ring[2], ring[1]);
-      iter(t + 2, ring[3], ring[2]);
-      iter(t + 3, ring[0], ring[3]);
-    }
-    if (t < te) {
-      iter(t, ring[1], ring[0]);
-      if (t + 1 < te) {
-        iter(t + 1, ring[2], ring[1]);
-        if (t + 2 < te) iter(t + 2, ring[3], ring[2]);
-      }
-    }
+  for (int i = 0; i < kStages - 1; ++i)  // tiles t0 .. t0 + kStages - 2; past the end: the last tile again (L2 hits)
+    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv);
+  int32_t nb0 = block_id(t0 + kStages - 1, 0), nb1 = block_id(t0 + kStages - 1, 1);
+  asm volatile("" ::"s"(nb0), "s"(nb1));
+  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // 2 (kStages - 2): tile t0 is in
+  land(t0);
+  __builtin_amdgcn_s_barrier();
+  floatx16 s;
+  if (kRows) {
+    score_tile(s, rd + (t0 & (kStages - 1)) * (kStageVecs * 16), q);
+    if (si.len - t0 * kTile < kTile) mask_scores(s, si.len - t0 * kTile, h);
   }
+  // iteration t: s_in holds the scores of tile t, s_out receives those of tile t + 1
+  auto iter = [&](int t, const floatx16& s_in, floatx16& s_out) {
+    asm volatile("s_waitcnt vmcnt(10)" ::: "memory");  // 2 (kStages - 3): tile t + 1 is in
+    land(t + 1);
+    // every share of tile t + 1 is visible, and everyone is done with tile t - 1
+    __builtin_amdgcn_s_barrier();
+    auto fetch = [&]() {
+      request_tile(a, f, nb0, nb1, g, stage_of(t + kStages - 1), wv);
+      nb0 = block_id(t + kStages, 0);
+      nb1 = block_id(t + kStages, 1);
+    };
+    if (kRows) {
+      const uint32_t k_addr = rd + ((t + 1) & (kStages - 1)) * (kStageVecs * 16);
+      const uint32_t v_addr = rd + (t & (kStages - 1)) * (kStageVecs * 16) + 8 * kWave * 16;
+      woven_tile(s_in, s_out, o, m, l, q, k_addr, v_addr, c, fetch);
+      const int nv_next = si.len - (t + 1) * kTile;
+      if (nv_next < kTile) mask_scores(s_out, nv_next, h);
+    } else {
+      fetch();
+    }
+    // the block ids are in before the next iteration issues its LDS reads (no wait among them)
+    asm volatile("" ::"s"(nb0), "s"(nb1));
+  };
+  floatx16 s2;
+  int t = t0;
+  for (; t + 2 <= t1; t += 2) {
+    iter(t, s, s2);
+    iter(t + 1, s2, s);
+  }
+  if (t < t1) iter(t, s, s2);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no fetch of this segment may land later
   if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane);
 }
 
-__device__ inline void large_worker(const MainArgs& a, int64_t w, bf16x8* lds /* 96 KB */) {
-  bf16x8* q_lds_all = lds;                              // 64 KB: one 32-row query tile per wavefront
-  bf16x8* kv_lds = lds + kLargeWaves * 8 * kWave;       // 32 KB: two K/V tiles in operand order
+__device__ inline void large_worker(const MainArgs& a, int64_t w, bf16x8* lds /* 128 KB: kStages tiles */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = sload(pv.header + 4), W = sload(pv.header + 5);
   if (w >= W || U <= 0) return;
@@ -886,7 +1007,6 @@ __device__ inline void large_worker(const MainArgs& a, int64_t w, bf16x8* lds /*
   if (u0 >= u1) return;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  bf16x8* q_lds = q_lds_all + wv * (8 * kWave);
   PlanWindow win;
   int b = locate(win, pv, a.cu_nodes, 2, a.batch, u0, lane);
   while (u0 < u1 && b < a.batch) {
@@ -906,8 +1026,8 @@ __device__ inline void large_worker(const MainArgs& a, int64_t w, bf16x8* lds /*
     float* slot = a.ws[2] + (size_t)(w + seg) * kLargeSlot;
     // rows of the group are dealt to the eight wavefronts in 32-row tiles
     const int row0 = rgi * kLargeRows + wv * 32;
-    if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, q_lds, kv_lds);
-    else staged_segment<false>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, q_lds, kv_lds);
+    if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
+    else staged_segment<false>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
     u0 += nt;
   }
 }
