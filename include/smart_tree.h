@@ -83,6 +83,8 @@ enum { SMART_DILUTION_NONE = 0, SMART_DILUTION_PATH_MEAN = 1 };
 enum {
   SMART_OPT_TVA_WORKERS = 1,      /* number of split-KV workers (waves); 0 = automatic   */
   SMART_OPT_TVA_FORCE_GENERAL = 2, /* 1 = always run the general (non matrix-core) kernel */
+  SMART_OPT_TVA_PROFILE_STRIDE = 4, /* record every value-th tree_verify_attention call only
+                                      (default 1); the event records cost a few us a call  */
   SMART_OPT_TVA_PROFILE = 3        /* n > 0: keep n pairs of HIP events and record one pair
                                       around the dominant attention kernel of every
                                       tree_verify_attention call (ring); 0 = off (default) */
@@ -158,6 +160,23 @@ int32_t smart_select_tree(
     int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
     int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
     double* h_out_L, double* h_out_R);
+
+/* ---------------------------------------------------------------------------
+ * tree_upload (pinned host -> device)
+ *
+ * smart_select_tree runs on the host (Sec. 3.2 builds the tree on the CPU side
+ * of the draft/verify loop), tree_pack and the calls after it on the device.
+ * This copies n_words 32-bit words of its output from PINNED host memory
+ * (hipHostMalloc, or a framework's pinned allocation: memory the device can
+ * address) to device memory with a copy kernel on `stream`, so the next kernel
+ * on the stream follows without a hand-off between the DMA engine's queue and
+ * the compute queue.  The host must leave h_pinned_src untouched until the
+ * copy has run (an event recorded after this call tells).
+ * Errors: SMART_EINVAL (null pointers, negative size, h_pinned_src not
+ * addressable by the device: pageable memory is refused, nothing is launched).
+ * ------------------------------------------------------------------------- */
+int32_t tree_upload(smart_ctx* ctx, void* stream, const void* h_pinned_src, void* d_dst,
+                    int64_t n_words);
 
 /* ---------------------------------------------------------------------------
  * tree_pack (device)

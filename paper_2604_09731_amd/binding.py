@@ -21,10 +21,12 @@ SMART_KV_PLAIN, SMART_KV_INTERLEAVED = 0, 1
 SMART_BEST_FIRST, SMART_LAYERWISE = 0, 1
 SMART_DILUTION_NONE, SMART_DILUTION_PATH_MEAN = 0, 1
 SMART_OPT_TVA_WORKERS, SMART_OPT_TVA_FORCE_GENERAL, SMART_OPT_TVA_PROFILE = 1, 2, 3
+SMART_OPT_TVA_PROFILE_STRIDE = 4
 SMART_MAX_NODES = 128
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
-           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "tree_pack",
+           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "tree_upload",
+           "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept"]
 
 
@@ -81,6 +83,8 @@ def _lib():
         lib.smart_select_tree.restype = i32
         lib.smart_select_tree.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, i32, i32,
                                           vp, vp, vp, vp, vp, i64, vp, vp]
+        lib.tree_upload.restype = i32
+        lib.tree_upload.argtypes = [vp, vp, vp, vp, i64]
         lib.tree_pack.restype = i32
         lib.tree_pack.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.kv_cache_write.restype = i32
@@ -216,6 +220,15 @@ class SmartTree:
         _check(_lib().smart_tva_profile_read(self._h, buf, cap, ctypes.byref(cnt)),
                "smart_tva_profile_read")
         return [buf[i] for i in range(cnt.value)]
+
+    # -- tree_upload -------------------------------------------------------
+    def tree_upload(self, pinned_src, dst):
+        """Copies a pinned host int32 tensor into a device int32 tensor of the same length."""
+        if pinned_src.numel() != dst.numel():
+            raise ValueError("tree_upload: sizes differ")
+        rc = _lib().tree_upload(self._h, _stream_ptr(), _ptr(pinned_src), _ptr(dst), pinned_src.numel())
+        _check(rc, "tree_upload")
+        return dst
 
     # -- tree_pack ---------------------------------------------------------
     def tree_pack(self, cu_nodes, parent, prefix_len):

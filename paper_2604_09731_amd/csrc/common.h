@@ -24,6 +24,9 @@ struct smart_ctx {
   hipEvent_t* prof_stop = nullptr;
   int32_t prof_cap = 0;
   int64_t prof_recorded = 0;  // calls recorded since the last read
+  int64_t prof_stride = 1;    // SMART_OPT_TVA_PROFILE_STRIDE
+  int64_t prof_calls = 0;     // calls seen since profiling was switched on
+  bool prof_open = false;     // the current call records
 };
 
 namespace smart {

@@ -41,16 +41,22 @@ static void profile_free(smart_ctx* ctx) {
   ctx->prof_start = ctx->prof_stop = nullptr;
   ctx->prof_cap = 0;
   ctx->prof_recorded = 0;
+  ctx->prof_calls = 0;
+  ctx->prof_open = false;
 }
 
 int32_t profile_begin(smart_ctx* ctx, hipStream_t stream) {
+  ctx->prof_open = false;
   if (ctx->prof_cap <= 0) return SMART_OK;
+  if (ctx->prof_calls++ % ctx->prof_stride != 0) return SMART_OK;
+  ctx->prof_open = true;
   SMART_HIP_CHECK(hipEventRecord(ctx->prof_start[ctx->prof_recorded % ctx->prof_cap], stream));
   return SMART_OK;
 }
 
 int32_t profile_end(smart_ctx* ctx, hipStream_t stream) {
-  if (ctx->prof_cap <= 0) return SMART_OK;
+  if (!ctx->prof_open) return SMART_OK;
+  ctx->prof_open = false;
   SMART_HIP_CHECK(hipEventRecord(ctx->prof_stop[ctx->prof_recorded % ctx->prof_cap], stream));
   ctx->prof_recorded += 1;
   return SMART_OK;
@@ -116,6 +122,10 @@ extern "C" int32_t smart_set_option(smart_ctx* ctx, int32_t key, int64_t value) 
     case SMART_OPT_TVA_FORCE_GENERAL:
       if (value != 0 && value != 1) return SMART_EINVAL;
       ctx->opt_force_general = value;
+      return SMART_OK;
+    case SMART_OPT_TVA_PROFILE_STRIDE:
+      if (value < 1 || value > 65536) return SMART_EINVAL;
+      ctx->prof_stride = value;
       return SMART_OK;
     case SMART_OPT_TVA_PROFILE: {
       if (value < 0 || value > 65536) return SMART_EINVAL;

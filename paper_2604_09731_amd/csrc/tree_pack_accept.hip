@@ -98,7 +98,45 @@ __global__ __launch_bounds__(kWave) void tree_accept_kernel(
   }
 }
 
+// 16 bytes a lane where both sides are aligned, the ragged rest word by word.
+__global__ __launch_bounds__(256) void tree_upload_kernel(const int32_t* __restrict__ src,
+                                                          int32_t* __restrict__ dst, int64_t n_words,
+                                                          int64_t n_vec) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n_vec) {
+    reinterpret_cast<int4*>(dst)[i] = reinterpret_cast<const int4*>(src)[i];
+  } else {
+    const int64_t w = 4 * n_vec + (i - n_vec);
+    if (w < n_words) dst[w] = src[w];
+  }
+}
+
 }  // namespace
+
+extern "C" int32_t tree_upload(smart_ctx* ctx, void* stream, const void* h_pinned_src, void* d_dst,
+                               int64_t n_words) {
+  if (!ctx || n_words < 0) return SMART_EINVAL;
+  if (n_words == 0) return SMART_OK;
+  if (!h_pinned_src || !d_dst) return SMART_EINVAL;
+  // a kernel that dereferences pageable host memory faults: refuse what the device cannot address
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, h_pinned_src) != hipSuccess) {
+    (void)hipGetLastError();
+    return SMART_EINVAL;
+  }
+  if (attr.type != hipMemoryTypeHost && attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
+    return SMART_EINVAL;
+  const bool aligned = (reinterpret_cast<uintptr_t>(h_pinned_src) % 16 == 0) &&
+                       (reinterpret_cast<uintptr_t>(d_dst) % 16 == 0);
+  const int64_t n_vec = aligned ? n_words / 4 : 0;
+  const int64_t threads = n_vec + (n_words - 4 * n_vec);
+  const int64_t blocks = (threads + 255) / 256;
+  if (blocks > 0x7fffffff) return SMART_EINVAL;
+  hipLaunchKernelGGL(tree_upload_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const int32_t*>(h_pinned_src), static_cast<int32_t*>(d_dst), n_words, n_vec);
+  SMART_HIP_CHECK(hipGetLastError());
+  return SMART_OK;
+}
 
 extern "C" int32_t tree_pack(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nodes,
                              const int32_t* d_cu_nodes, const int32_t* d_parent,

@@ -151,3 +151,31 @@ def test_kv_cache_write_layouts(lib, dtype, D):
                                            H.torch_elems(plain_v, dtype, "cuda"))
             assert np.array_equal(raw(ik).reshape(nb, Hkv, -1), raw(kc))
             assert np.array_equal(raw(iv).reshape(nb, Hkv, -1), raw(vc))
+
+
+@pytest.mark.parametrize("n_words,src_off,dst_off", [(1, 0, 0), (4, 0, 0), (4099, 0, 0), (1000, 1, 0), (1000, 0, 3),
+                                                     (70000, 4, 8)])
+def test_tree_upload_copies_pinned_host_words(lib, n_words, src_off, dst_off):
+    """The copy is bit-exact for aligned and unaligned ends and leaves the words around the
+    destination alone."""
+    import torch
+    rng = np.random.default_rng(n_words)
+    host = torch.empty(n_words + src_off + 5, dtype=torch.int32).pin_memory()
+    host.numpy()[:] = rng.integers(-2**31, 2**31 - 1, size=host.numel(), dtype=np.int64).astype(np.int32)
+    dev = torch.full((n_words + dst_off + 7,), -77, dtype=torch.int32, device="cuda")
+    lib.tree_upload(host[src_off:src_off + n_words], dev[dst_off:dst_off + n_words])
+    torch.cuda.synchronize()
+    got = dev.cpu().numpy()
+    assert (got[dst_off:dst_off + n_words] == host.numpy()[src_off:src_off + n_words]).all()
+    assert (got[:dst_off] == -77).all() and (got[dst_off + n_words:] == -77).all()
+
+
+def test_tree_upload_refuses_pageable_memory(lib):
+    import torch
+    host = torch.zeros(64, dtype=torch.int32)          # not pinned: the device cannot address it
+    dev = torch.full((64,), 5, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.SmartError) as e:
+        lib.tree_upload(host, dev)
+    assert e.value.code == B.SMART_EINVAL
+    torch.cuda.synchronize()
+    assert (dev.cpu().numpy() == 5).all()

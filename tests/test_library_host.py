@@ -133,6 +133,14 @@ def test_device_entry_points_validate_on_the_host_first():
     assert lib.kv_cache_write(ctx, None, 1, 1, 1, 8, 128, 12, 4, ptr, ptr, ptr, ptr, ptr, 16384, 2048, 128) == B.SMART_EINVAL
     assert lib.kv_cache_write(ctx, None, 1, 1, 1, 8, 128, 16, 4, ptr, ptr, ptr, ptr, ptr, 16384, 100, 128) == B.SMART_EINVAL
     assert lib.smart_set_option(None, 1, 0) == B.SMART_EINVAL
+    assert lib.smart_set_option(ctx, B.SMART_OPT_TVA_PROFILE_STRIDE, 0) == B.SMART_EINVAL
+    assert lib.tree_upload(None, None, ptr, ptr, 4) == B.SMART_EINVAL
+    assert lib.tree_upload(ctx, None, ptr, ptr, -1) == B.SMART_EINVAL
+    assert lib.tree_upload(ctx, None, None, ptr, 4) == B.SMART_EINVAL
+    assert lib.tree_upload(ctx, None, ptr, None, 4) == B.SMART_EINVAL
+    assert lib.tree_upload(ctx, None, None, None, 0) == B.SMART_OK
+    # pageable host memory is refused before anything is launched (here: no device at all)
+    assert lib.tree_upload(ctx, None, ptr, ptr, 4) == B.SMART_EINVAL
     assert lib.smart_create(None, 0) == B.SMART_EINVAL
     assert lib.smart_destroy(None) == B.SMART_EINVAL
 
