@@ -109,16 +109,104 @@ __host__ __device__ inline PlanView plan_view(void* base, int batch) {
 
 __host__ __device__ inline int seq_class(int rows) { return rows <= kSmallRows ? 0 : (rows <= kMediumRows ? 1 : 2); }
 
-// One wavefront.  Lane t owns a contiguous range of sequences; an exclusive
-// shuffle scan over the per-lane sums ties the ranges together.
+__device__ inline int64_t readlane64(int64_t v, int lane) {
+  const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, lane);
+  const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)v >> 32), lane);
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// A value every lane agrees on, moved to scalar registers.
+__device__ inline int64_t uniform64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Inclusive add scan over the 64 lanes with data-parallel-primitive moves (no LDS traffic):
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then lane 15 of rows 0 and 2 is added to
+// rows 1 and 3, then lane 31 to the upper half.  Lanes without a source add zero.
+template <int kCtrl, int kRowMask>
+__device__ inline int64_t dpp_add(int64_t v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, kCtrl, kRowMask, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((uint64_t)v >> 32), kCtrl, kRowMask, 0xf, false);
+  return v + (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// One wavefront: exclusive scan of v and (uniform) the total.
 __device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
   int64_t incl = v;
-  for (int o = 1; o < kWave; o <<= 1) {
-    const int64_t up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
-  *total = __shfl(incl, kWave - 1);
+  incl = dpp_add<0x111, 0xf>(incl);  // row_shr:1
+  incl = dpp_add<0x112, 0xf>(incl);  // row_shr:2
+  incl = dpp_add<0x114, 0xf>(incl);  // row_shr:4
+  incl = dpp_add<0x118, 0xf>(incl);  // row_shr:8
+  incl = dpp_add<0x142, 0xa>(incl);  // row_bcast:15 into rows 1 and 3
+  incl = dpp_add<0x143, 0xc>(incl);  // row_bcast:31 into rows 2 and 3
+  *total = readlane64(incl, kWave - 1);
   return incl - v;
+}
+
+// What the plan records of one sequence (inputs clamped so that nothing downstream can leave
+// its arrays whatever the offsets say).
+__device__ inline SeqInfo sequence_info(int len, int base, int next, int total_nodes, int G, int max_blocks) {
+  const int cap = max_blocks * kBlock;
+  len = len < 0 ? 0 : (len > cap ? cap : len);
+  int n = next - base;
+  if (base < 0 || n < 0 || base + n > total_nodes) n = 0;
+  n = n > SMART_MAX_NODES ? SMART_MAX_NODES : n;
+  const int rows = n * G;
+  SeqInfo si;
+  si.len = len;
+  si.n = n;
+  si.tiles = (len + kTile - 1) / kTile;
+  si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
+  return si;
+}
+
+// The prefix kernel is ONE launch of max(workgroups, kClasses) workgroups; the classes share
+// them in proportion to their work, so that all of them finish together.  A class-2 tile
+// costs more than its bytes (it is multiplied against up to 256 rows).  Every class with
+// work gets at least one workgroup, the shares are rounded down, and what is left over goes
+// to the class with the most work, so the classes never need more workgroups than were
+// launched.  Returns the workers per class and the first workgroup of each class (entry
+// kClasses: one past the last).
+__device__ inline void apportion(const int64_t (&tot_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
+                                 int64_t (&first_wg)[kClasses + 1]) {
+  const int64_t weight[kClasses] = {2, 2, 3};
+  const int64_t launched = workgroups > kClasses ? workgroups : kClasses;
+  int64_t cost[kClasses], total = 0;
+#pragma unroll
+  for (int c = 0; c < kClasses; ++c) {
+    cost[c] = tot_u[c] * weight[c];
+    total += cost[c];
+  }
+  int64_t wg[kClasses], used = 0;
+  int biggest = 0;
+#pragma unroll
+  for (int c = 0; c < kClasses; ++c) {
+    // (binary64 division: exact enough for a share of a few hundred workgroups, far cheaper than
+    // a 64-bit integer division, and every wavefront that plans runs this same code)
+    wg[c] = tot_u[c] > 0 ? (int64_t)((double)cost[c] * (double)launched / (double)(total > 0 ? total : 1)) : 0;
+    if (tot_u[c] > 0 && wg[c] < 1) wg[c] = 1;
+    used += wg[c];
+    if (cost[c] > cost[biggest]) biggest = c;
+  }
+  // at most kClasses - 1 shares were raised to one, so the biggest class can give those back
+  const int64_t rest = launched - used;
+#pragma unroll
+  for (int c = 0; c < kClasses; ++c)
+    if (c == biggest && wg[c] + rest >= 1) wg[c] += rest;
+  int64_t first = 0;
+#pragma unroll
+  for (int c = 0; c < kClasses; ++c) {
+    int64_t w = wg[c] * (c == 1 ? kWgWaves : 1);  // class 1 workers are single wavefronts
+    const int64_t cap = tot_u[c] / kMinTilesPerWorker[c];
+    if (w > cap) w = cap;
+    if (tot_u[c] > 0 && w < 1) w = 1;
+    workers[c] = w;
+    first_wg[c] = first;
+    first += c == 1 ? (w + kWgWaves - 1) / kWgWaves : w;
+  }
+  first_wg[kClasses] = first;
 }
 
 __global__ __launch_bounds__(kWave) void tva_plan_kernel(
@@ -130,20 +218,9 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   const int b0 = min(batch, t * per), b1 = min(batch, b0 + per);
   int64_t units[kClasses] = {0, 0, 0}, segs[kClasses] = {0, 0, 0}, chunks = 0;
   for (int b = b0; b < b1; ++b) {
-    int len = prefix_len[b];
-    const int cap = max_blocks * kBlock;
-    len = len < 0 ? 0 : (len > cap ? cap : len);
-    const int base = cu_nodes[b];
-    int n = cu_nodes[b + 1] - base;
-    if (base < 0 || n < 0 || base + n > total_nodes) n = 0;
-    n = n > SMART_MAX_NODES ? SMART_MAX_NODES : n;
-    const int rows = n * G;
-    SeqInfo si;
-    si.len = len;
-    si.n = n;
-    si.tiles = (len + kTile - 1) / kTile;
-    si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
+    const SeqInfo si = sequence_info(prefix_len[b], cu_nodes[b], cu_nodes[b + 1], total_nodes, G, max_blocks);
     pv.info[b] = si;
+    const int rows = si.n * G;
     const int c = seq_class(rows);
     units[c] += (int64_t)si.tiles * Hkv * si.rg;
     segs[c] += Hkv * si.rg;
@@ -156,36 +233,16 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   }
   int64_t ch = wave_excl_scan(chunks, t, &tot_c);
   if (t == 0) {
-    // The prefix kernel is ONE launch of `workgroups` (+ slack) workgroups; the classes share
-    // them in proportion to their work, so that all of them finish together.  A class-2 tile
-    // costs more than its bytes (it is multiplied against up to 256 rows).
-    const int64_t weight[kClasses] = {2, 2, 3};
-    int64_t cost[kClasses], total = 0;
-    for (int c = 0; c < kClasses; ++c) {
-      cost[c] = tot_u[c] * weight[c];
-      total += cost[c];
-    }
-    int64_t wg[kClasses], used = 0;
-    for (int c = 0; c < kClasses; ++c) {
-      wg[c] = tot_u[c] > 0 ? (cost[c] * workgroups + total / 2) / total : 0;
-      if (tot_u[c] > 0 && wg[c] < 1) wg[c] = 1;
-      used += wg[c];
-    }
-    // rounding may overshoot by at most one per class; the launch carries that much slack
-    int64_t first = 0;
+    int64_t workers[kClasses], first_wg[kClasses + 1];
+    apportion(tot_u, workgroups, workers, first_wg);
     for (int c = 0; c < kClasses; ++c) {
       pv.cum_units[c][batch] = tot_u[c];
       pv.cum_segs[c][batch] = (int32_t)tot_s[c];
-      int64_t w = wg[c] * (c == 1 ? kWgWaves : 1);  // class 1 workers are single wavefronts
-      const int64_t cap = tot_u[c] / kMinTilesPerWorker[c];
-      if (w > cap) w = cap;
-      if (tot_u[c] > 0 && w < 1) w = 1;
       pv.header[2 * c] = tot_u[c];
-      pv.header[2 * c + 1] = w;
-      pv.header[6 + c] = first;
-      first += c == 1 ? (w + kWgWaves - 1) / kWgWaves : w;
+      pv.header[2 * c + 1] = workers[c];
+      pv.header[6 + c] = first_wg[c];
     }
-    pv.header[6 + kClasses] = first;
+    pv.header[6 + kClasses] = first_wg[kClasses];
     pv.cum_chunks[batch] = (int32_t)tot_c;
   }
   for (int b = b0; b < b1; ++b) {
@@ -203,6 +260,46 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   }
 }
 
+// The same plan for a batch of at most 64 sequences, computed by a wavefront for itself: lane
+// b holds sequence b (lanes past the batch: an empty sequence, so their prefix sums are the
+// totals).  One round trip to memory and a few shuffle scans replace a kernel launch.
+struct LanePlan {
+  SeqInfo si;                   // per lane
+  int32_t cu;                   // cu_nodes[lane]
+  int64_t cum_units[kClasses];  // per lane: units before this sequence
+  int32_t cum_segs[kClasses];
+  int32_t cum_chunks;
+  int64_t units[kClasses];      // uniform: totals
+  int32_t total_segs[kClasses];
+  int64_t workers[kClasses];
+  int64_t first_wg[kClasses + 1];
+  int32_t chunks;
+};
+
+__device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const int32_t* cu_nodes, int batch,
+                                 int total_nodes, int G, int Hkv, int max_blocks, int workgroups, int lane) {
+  const int b = min(lane, batch - 1);
+  const int32_t len = prefix_len[b], base = cu_nodes[min(lane, batch)], next = cu_nodes[b + 1];
+  SeqInfo si = sequence_info(len, base, next, total_nodes, G, max_blocks);
+  if (lane >= batch) si.len = si.n = si.tiles = si.rg = 0;
+  p.si = si;
+  p.cu = base;
+  const int rows = si.n * G;
+  const int cls = seq_class(rows);
+  const int64_t my_units = (int64_t)si.tiles * Hkv * si.rg;
+  const int64_t my_segs = Hkv * si.rg;
+  int64_t tot_s, tot_c;
+#pragma unroll
+  for (int c = 0; c < kClasses; ++c) {
+    p.cum_units[c] = wave_excl_scan(cls == c ? my_units : 0, lane, &p.units[c]);
+    p.cum_segs[c] = (int32_t)wave_excl_scan(cls == c ? my_segs : 0, lane, &tot_s);
+    p.total_segs[c] = (int32_t)tot_s;
+  }
+  p.cum_chunks = (int32_t)wave_excl_scan((int64_t)Hkv * ((rows + kCombineRows - 1) / kCombineRows), lane, &tot_c);
+  p.chunks = (int32_t)tot_c;
+  apportion(p.units, workgroups, p.workers, p.first_wg);
+}
+
 // ---------------------------------------------------------------------------
 // prefix kernels
 // ---------------------------------------------------------------------------
@@ -212,10 +309,11 @@ struct MainArgs {
   const __bf16* v_cache;
   const int32_t* block_table;
   const int32_t* cu_nodes;
-  void* plan;
+  const int32_t* prefix_len;
+  void* plan;  // written by the planning kernel; unused for batches of at most 64 sequences
   float* ws[3];  // partial slots per class
   int64_t block_stride, head_stride;
-  int32_t batch, Hq, Hkv, G, max_blocks, num_blocks;
+  int32_t batch, total_nodes, Hq, Hkv, G, max_blocks, num_blocks, workgroups;
   float scale_log2e;
 };
 
@@ -513,13 +611,22 @@ struct PlanWindow {
   int32_t cum_segs;
   int32_t cu_nodes;
   int32_t len, n, tiles, rg;
+  int64_t total_units;  // entry 64 of a window that holds a whole batch of 64 (uniform)
 };
 
-__device__ inline int64_t readlane64(int64_t v, int lane) {
-  const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, lane);
-  const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)v >> 32), lane);
-  return (int64_t)(((uint64_t)hi << 32) | lo);
+// Units before the sequence at window index i (0 .. 64).
+__device__ inline int64_t window_cum_units(const PlanWindow& w, int i) {
+  return i < kWave ? readlane64(w.cum_units, i) : w.total_units;
 }
+
+// A workgroup's copy of the plan when its first wavefront derived it (batches of at most 64).
+struct PlanShare {
+  int64_t cum_units[kClasses][kWave];
+  int32_t cum_segs[kClasses][kWave];
+  int32_t cu[kWave];
+  SeqInfo info[kWave];
+  int64_t units[kClasses], workers[kClasses], first_wg[kClasses + 1];
+};
 
 __device__ inline void load_window(PlanWindow& w, const PlanView& pv, const int32_t* cu_nodes,
                                    int cls, int batch, int first, int lane) {
@@ -534,6 +641,7 @@ __device__ inline void load_window(PlanWindow& w, const PlanView& pv, const int3
   w.n = si.n;
   w.tiles = si.tiles;
   w.rg = si.rg;
+  w.total_units = 0;  // never read: such a window is reloaded before its last lane is passed
 }
 
 __device__ inline SeqInfo window_info(const PlanWindow& w, int b) {
@@ -546,18 +654,33 @@ __device__ inline SeqInfo window_info(const PlanWindow& w, int b) {
   return si;
 }
 
+// What a worker needs of the plan: its class's unit and worker counts, and the window (held in
+// registers for the whole batch when the wavefront planned for itself, else loaded from the
+// plan in memory as the worker moves along).
+struct ClassPlan {
+  int64_t U, W;
+  bool resident;
+  PlanWindow win;
+};
+
 // Sequence that holds unit u0 of class `cls`, with its plan window loaded.
-__device__ inline int locate(PlanWindow& w, const PlanView& pv, const int32_t* cu_nodes, int cls,
+__device__ inline int locate(ClassPlan& cp, const PlanView& pv, const int32_t* cu_nodes, int cls,
                              int batch, int64_t u0, int lane) {
   if (batch <= kWave) {
-    load_window(w, pv, cu_nodes, cls, batch, 0, lane);
+    if (!cp.resident) load_window(cp.win, pv, cu_nodes, cls, batch, 0, lane);
     // cum_units is non-decreasing: the lanes with cum <= u0 are a prefix, its last lane is b
-    const uint64_t below = __ballot(lane < batch && w.cum_units <= u0);
+    const uint64_t below = __ballot(lane < batch && cp.win.cum_units <= u0);
     return __popcll(below) - 1;
   }
   const int b = find_sequence(pv.cum_units[cls], batch, u0);
-  load_window(w, pv, cu_nodes, cls, batch, b, lane);
+  load_window(cp.win, pv, cu_nodes, cls, batch, b, lane);
   return b;
+}
+
+// Moves the window along when sequence b is its last lane (a resident window never moves).
+__device__ inline void follow(ClassPlan& cp, const PlanView& pv, const int32_t* cu_nodes, int cls, int batch,
+                              int b, int lane) {
+  if (!cp.resident && b - cp.win.first >= kWave - 1) load_window(cp.win, pv, cu_nodes, cls, batch, b, lane);
 }
 
 // One workgroup of eight wavefronts per worker (two per SIMD).  Worker w owns
@@ -568,21 +691,21 @@ __device__ inline int locate(PlanWindow& w, const PlanView& pv, const int32_t* c
 // partial in memory however many wavefronts streamed it.
 constexpr int kSmallWaves = kWgWaves;
 
-__device__ inline void small_worker(const MainArgs& a, int64_t w, float* merge_lds /* 66 KB */) {
+__device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 66 KB */) {
   const PlanView pv = plan_view(a.plan, a.batch);
-  const int64_t U = sload(pv.header), W = sload(pv.header + 1);
+  const int64_t U = cp.U, W = cp.W;
+  PlanWindow& win = cp.win;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
   if (u0 >= u1) return;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  PlanWindow win;
-  int b = locate(win, pv, a.cu_nodes, 0, a.batch, u0, lane);
+  int b = locate(cp, pv, a.cu_nodes, 0, a.batch, u0, lane);
   while (u0 < u1 && b < a.batch) {
-    if (b - win.first >= kWave - 1) load_window(win, pv, a.cu_nodes, 0, a.batch, b, lane);
-    const int64_t seq_begin = readlane64(win.cum_units, b - win.first);
-    const int64_t seq_end = readlane64(win.cum_units, b + 1 - win.first);
+    follow(cp, pv, a.cu_nodes, 0, a.batch, b, lane);
+    const int64_t seq_begin = window_cum_units(win, b - win.first);
+    const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
     if (u0 >= seq_end) { ++b; continue; }  // also skips sequences without units in this class
     const SeqInfo si = window_info(win, b);
     const int64_t local = u0 - seq_begin;
@@ -998,21 +1121,21 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
   if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane);
 }
 
-__device__ inline void large_worker(const MainArgs& a, int64_t w, bf16x8* lds /* 128 KB: kStages tiles */) {
+__device__ inline void large_worker(const MainArgs& a, int64_t w, ClassPlan& cp, bf16x8* lds /* 128 KB: kStages tiles */) {
   const PlanView pv = plan_view(a.plan, a.batch);
-  const int64_t U = sload(pv.header + 4), W = sload(pv.header + 5);
+  const int64_t U = cp.U, W = cp.W;
+  PlanWindow& win = cp.win;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
   if (u0 >= u1) return;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  PlanWindow win;
-  int b = locate(win, pv, a.cu_nodes, 2, a.batch, u0, lane);
+  int b = locate(cp, pv, a.cu_nodes, 2, a.batch, u0, lane);
   while (u0 < u1 && b < a.batch) {
-    if (b - win.first >= kWave - 1) load_window(win, pv, a.cu_nodes, 2, a.batch, b, lane);
-    const int64_t seq_begin = readlane64(win.cum_units, b - win.first);
-    const int64_t seq_end = readlane64(win.cum_units, b + 1 - win.first);
+    follow(cp, pv, a.cu_nodes, 2, a.batch, b, lane);
+    const int64_t seq_begin = window_cum_units(win, b - win.first);
+    const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
     if (u0 >= seq_end) { ++b; continue; }
     const SeqInfo si = window_info(win, b);
     const int64_t local = u0 - seq_begin;
@@ -1033,20 +1156,20 @@ __device__ inline void large_worker(const MainArgs& a, int64_t w, bf16x8* lds /*
 }
 
 // ---- class 1: 33 .. 64 rows: one wavefront per worker, two MFMA row tiles -----------------
-__device__ inline void medium_worker(const MainArgs& a, int64_t w, bf16x8* q_lds /* 16 KB of this wavefront */) {
+__device__ inline void medium_worker(const MainArgs& a, int64_t w, ClassPlan& cp, bf16x8* q_lds /* 16 KB of this wavefront */) {
   const PlanView pv = plan_view(a.plan, a.batch);
-  const int64_t U = sload(pv.header + 2), W = sload(pv.header + 3);
+  const int64_t U = cp.U, W = cp.W;
+  PlanWindow& win = cp.win;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
   if (u0 >= u1) return;
   const int lane = threadIdx.x & (kWave - 1);
-  PlanWindow win;
-  int b = locate(win, pv, a.cu_nodes, 1, a.batch, u0, lane);
+  int b = locate(cp, pv, a.cu_nodes, 1, a.batch, u0, lane);
   while (u0 < u1 && b < a.batch) {
-    if (b - win.first >= kWave - 1) load_window(win, pv, a.cu_nodes, 1, a.batch, b, lane);
-    const int64_t seq_begin = readlane64(win.cum_units, b - win.first);
-    const int64_t seq_end = readlane64(win.cum_units, b + 1 - win.first);
+    follow(cp, pv, a.cu_nodes, 1, a.batch, b, lane);
+    const int64_t seq_begin = window_cum_units(win, b - win.first);
+    const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
     if (u0 >= seq_end) { ++b; continue; }
     const SeqInfo si = window_info(win, b);
     const int64_t local = u0 - seq_begin;
@@ -1066,17 +1189,95 @@ __device__ inline void medium_worker(const MainArgs& a, int64_t w, bf16x8* q_lds
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
   __shared__ float4 lds_raw[8192];  // 128 KB, carved up per class
-  const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t wg = blockIdx.x;
-  const int64_t first1 = sload(pv.header + 7), first2 = sload(pv.header + 8), end = sload(pv.header + 9);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  ClassPlan cp;
+  int64_t first1, first2, end;
+  if (a.batch <= kWave) {
+    // No planning kernel ran: wavefront 0 derives the plan and hands it to the others through
+    // LDS; workgroup 0 also writes it to memory for the combine kernel.
+    __shared__ PlanShare share;
+    if (wv == 0) {
+      LanePlan lp;
+      lane_plan(lp, a.prefix_len, a.cu_nodes, a.batch, a.total_nodes, a.G, a.Hkv, a.max_blocks, a.workgroups, lane);
+#pragma unroll
+      for (int c = 0; c < kClasses; ++c) {
+        share.cum_units[c][lane] = lp.cum_units[c];
+        share.cum_segs[c][lane] = lp.cum_segs[c];
+      }
+      share.cu[lane] = lp.cu;
+      share.info[lane] = lp.si;
+      if (lane == 0) {
+#pragma unroll
+        for (int c = 0; c < kClasses; ++c) {
+          share.units[c] = lp.units[c];
+          share.workers[c] = lp.workers[c];
+          share.first_wg[c] = lp.first_wg[c];
+        }
+        share.first_wg[kClasses] = lp.first_wg[kClasses];
+      }
+      if (wg == 0) {
+        const PlanView pv = plan_view(a.plan, a.batch);
+        if (lane <= a.batch) {
+#pragma unroll
+          for (int c = 0; c < kClasses; ++c) {
+            pv.cum_units[c][lane] = lp.cum_units[c];
+            pv.cum_segs[c][lane] = lp.cum_segs[c];
+          }
+          pv.cum_chunks[lane] = lp.cum_chunks;
+        }
+        if (a.batch == kWave && lane == 0) {  // entry 64 has no lane: the totals
+#pragma unroll
+          for (int c = 0; c < kClasses; ++c) {
+            pv.cum_units[c][kWave] = lp.units[c];
+            pv.cum_segs[c][kWave] = lp.total_segs[c];
+          }
+          pv.cum_chunks[kWave] = lp.chunks;
+        }
+        if (lane < a.batch) pv.info[lane] = lp.si;
+        if (lane == 0) {
+#pragma unroll
+          for (int c = 0; c < kClasses; ++c) {
+            pv.header[2 * c] = lp.units[c];
+            pv.header[2 * c + 1] = lp.workers[c];
+            pv.header[6 + c] = lp.first_wg[c];
+          }
+          pv.header[6 + kClasses] = lp.first_wg[kClasses];
+        }
+      }
+    }
+    __syncthreads();
+    first1 = uniform64(share.first_wg[1]), first2 = uniform64(share.first_wg[2]), end = uniform64(share.first_wg[3]);
+    const int cls = wg < first1 ? 0 : (wg < first2 ? 1 : 2);
+    cp.U = uniform64(share.units[cls]);
+    cp.W = uniform64(share.workers[cls]);
+    cp.resident = true;
+    cp.win.first = 0;
+    cp.win.cum_units = share.cum_units[cls][lane];
+    cp.win.cum_segs = share.cum_segs[cls][lane];
+    cp.win.cu_nodes = share.cu[lane];
+    const SeqInfo si = share.info[lane];
+    cp.win.len = si.len;
+    cp.win.n = si.n;
+    cp.win.tiles = si.tiles;
+    cp.win.rg = si.rg;
+    cp.win.total_units = cp.U;
+  } else {
+    const PlanView pv = plan_view(a.plan, a.batch);
+    first1 = sload(pv.header + 7), first2 = sload(pv.header + 8), end = sload(pv.header + 9);
+    const int cls = wg < first1 ? 0 : (wg < first2 ? 1 : 2);
+    cp.U = sload(pv.header + 2 * cls);
+    cp.W = sload(pv.header + 2 * cls + 1);
+    cp.resident = false;
+  }
   if (wg >= end) return;
   if (wg < first1) {
-    small_worker(a, wg, (float*)lds_raw);
+    small_worker(a, wg, cp, (float*)lds_raw);
   } else if (wg < first2) {
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    medium_worker(a, (wg - first1) * kWgWaves + wv, (bf16x8*)lds_raw + wv * (2 * 8 * kWave));
+    medium_worker(a, (wg - first1) * kWgWaves + wv, cp, (bf16x8*)lds_raw + wv * (2 * 8 * kWave));
   } else {
-    large_worker(a, wg - first2, (bf16x8*)lds_raw);
+    large_worker(a, wg - first2, cp, (bf16x8*)lds_raw);
   }
 }
 
@@ -1112,9 +1313,9 @@ __device__ inline uint16_t f32_to_bf16(float v) {
 constexpr int kKeyBatch = 4;
 
 __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
-  const PlanView pv = plan_view(a.plan, a.batch);
   const int wc = blockIdx.x;
   const int lane = threadIdx.x;
+  const PlanView pv = plan_view(a.plan, a.batch);
   int b;
   if (a.batch <= kWave) {
     // cum_chunks is non-decreasing: lanes with cum <= wc are a prefix whose last lane is b
@@ -1133,8 +1334,7 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
     b = lo;
   }
   const SeqInfo si = sload(pv.info + b);
-  const int M = si.n * a.G;
-  const int cls = seq_class(M);
+  const int cls = seq_class(si.n * a.G);
   const int chunk_base = sload(pv.cum_chunks + b);
   const int base = sload(a.cu_nodes + b);
   const int64_t U = sload(pv.header + 2 * cls), W = sload(pv.header + 2 * cls + 1);
@@ -1143,6 +1343,7 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   const int64_t* units_c = cls == 0 ? pv.cum_units[0] : (cls == 1 ? pv.cum_units[1] : pv.cum_units[2]);
   const int64_t seg_base = sload(segs_c + b);
   const int64_t unit_base = sload(units_c + b);
+  const int M = si.n * a.G;
   const int per_g = (M + kCombineRows - 1) / kCombineRows;
   const int local = wc - chunk_base;
   const int g = local / per_g, chunk = local % per_g;
@@ -1276,7 +1477,8 @@ static int32_t prefix_workgroups(const smart_ctx* ctx) {
   return ctx->num_cus > 0 ? ctx->num_cus : 256;
 }
 static int32_t class_workers(const smart_ctx* ctx, int cls) {
-  const int32_t wg = prefix_workgroups(ctx) + 1;
+  const int32_t asked = prefix_workgroups(ctx);
+  const int32_t wg = asked > kClasses ? asked : kClasses;
   return cls == 1 ? wg * kWgWaves : wg;
 }
 int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return prefix_workgroups(ctx); }
@@ -1319,10 +1521,12 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   for (int c = 1; c < kClasses; ++c)
     ws[c] = ws[c - 1] + class_slots(ctx, c - 1, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads) * class_slot(c - 1);
 
-  hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
-                     p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
-                     p.d_cu_nodes);
-  SMART_HIP_CHECK(hipGetLastError());
+  if (p.batch > kWave) {  // smaller batches: every wavefront derives the plan for itself
+    hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
+                       p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
+                       p.d_cu_nodes);
+    SMART_HIP_CHECK(hipGetLastError());
+  }
 
   MainArgs ma;
   ma.q = (const __bf16*)p.d_q;
@@ -1330,6 +1534,9 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.v_cache = (const __bf16*)p.d_v_cache;
   ma.block_table = p.d_block_table;
   ma.cu_nodes = p.d_cu_nodes;
+  ma.prefix_len = p.d_prefix_len;
+  ma.total_nodes = p.total_nodes;
+  ma.workgroups = workgroups;
   ma.plan = ctx->plan;
   for (int c = 0; c < kClasses; ++c) ma.ws[c] = ws[c];
   ma.block_stride = p.cache_block_stride;
@@ -1343,8 +1550,9 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.scale_log2e = p.softmax_scale * kLog2e;
   rc = profile_begin(ctx, stream);
   if (rc != SMART_OK) return rc;
-  // the plan may round every class up by one workgroup
-  hipLaunchKernelGGL(tva_prefix_kernel, dim3(workgroups + kClasses), dim3(kWgWaves * kWave), 0, stream, ma);
+  // (every class with work needs a workgroup, however few were asked for)
+  hipLaunchKernelGGL(tva_prefix_kernel, dim3(workgroups > kClasses ? workgroups : kClasses), dim3(kWgWaves * kWave), 0,
+                     stream, ma);
   SMART_HIP_CHECK(hipGetLastError());
   rc = profile_end(ctx, stream);
   if (rc != SMART_OK) return rc;
