@@ -576,8 +576,7 @@ __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, in
   }
 }
 
-// Folds another wavefront's running softmax state (read from LDS, where the
-// partner wrote it register by register, lane by lane) into this one's.
+// A wavefront's running softmax state in LDS: register by register, lane by lane.
 constexpr int kStateFloats = (64 + 2) * kWave;  // 64 accumulator registers + max + sum, per lane
 
 __device__ inline void state_to_lds(const SmallState& S, float* region, int lane) {
@@ -589,18 +588,53 @@ __device__ inline void state_to_lds(const SmallState& S, float* region, int lane
   region[65 * kWave + lane] = S.l;
 }
 
-__device__ inline void merge_from_lds(SmallState& S, const float* region, int lane, float c) {
-  const float mb = region[64 * kWave + lane], lb = region[65 * kWave + lane];
-  const float m_new = fmaxf(S.m, mb);
-  // an empty state has max -inf and contributes nothing; two empty states stay empty
-  const float sa = S.m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((S.m - m_new) * c);
-  const float sb = mb == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mb - m_new) * c);
-  S.l = S.l * sa + lb * sb;
+
+// The eight running states of a piece become ONE partial: every wavefront puts its state in
+// LDS, and after one barrier wavefront w merges accumulator registers 8 w .. 8 w + 7 of the
+// eight states (always in wavefront order, so the result does not depend on timing) and
+// stores that slice of the partial; wavefront 0 also stores the row maxima and sums.
+__device__ inline void fold_and_store(const SmallState& S, float* lds, float* slot, int wv, int lane, float c) {
+  const int h = lane >> 5, j = lane & 31;
+  state_to_lds(S, lds + wv * kStateFloats, lane);
+  __syncthreads();
+  float mk[kWgWaves], lk[kWgWaves];
 #pragma unroll
-  for (int jt = 0; jt < 4; ++jt)
+  for (int k = 0; k < kWgWaves; ++k) {
+    mk[k] = lds[k * kStateFloats + 64 * kWave + lane];
+    lk[k] = lds[k * kStateFloats + 65 * kWave + lane];
+  }
+  floatx4 part[kWgWaves][2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) S.o[jt][r] = S.o[jt][r] * sa + region[(jt * 16 + r) * kWave + lane] * sb;
-  S.m = m_new;
+  for (int k = 0; k < kWgWaves; ++k)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) part[k][u][i] = lds[k * kStateFloats + (8 * wv + 4 * u + i) * kWave + lane];
+  float m_new = mk[0];
+#pragma unroll
+  for (int k = 1; k < kWgWaves; ++k) m_new = fmaxf(m_new, mk[k]);
+  float l_new = 0.f;
+  floatx4 x[2] = {(floatx4)(0.f), (floatx4)(0.f)};
+#pragma unroll
+  for (int k = 0; k < kWgWaves; ++k) {
+    // an empty state has max -inf and contributes nothing
+    const float sc = mk[k] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mk[k] - m_new) * c);
+    l_new += lk[k] * sc;
+    x[0] += part[k][0] * sc;
+    x[1] += part[k][1] * sc;
+  }
+  // accumulator register 16 jt + 4 r4 + i of lane (h, j) is row j, head dims 4 (8 jt + 2 r4 + h) + i
+  const int jt = wv >> 1, r4 = 2 * (wv & 1);
+  *(floatx4*)(slot + ((size_t)(jt * 8 + 2 * r4 + h) * 32 + j) * 4) = x[0];
+  *(floatx4*)(slot + ((size_t)(jt * 8 + 2 * (r4 + 1) + h) * 32 + j) * 4) = x[1];
+  if (wv == 0) {
+    const float lsum = sum_across_halves(l_new);
+    if (h == 0) {
+      slot[kSmallRows * kD + j] = m_new;
+      slot[kSmallRows * kD + kSmallRows + j] = lsum;
+    }
+  }
+  __syncthreads();  // the next piece reuses the LDS regions
 }
 
 // The plan entries of 64 consecutive sequences, one per lane, fetched with one
@@ -691,7 +725,7 @@ __device__ inline void follow(ClassPlan& cp, const PlanView& pv, const int32_t* 
 // partial in memory however many wavefronts streamed it.
 constexpr int kSmallWaves = kWgWaves;
 
-__device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 66 KB */) {
+__device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 132 KB: eight states */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = cp.U, W = cp.W;
   PlanWindow& win = cp.win;
@@ -720,15 +754,7 @@ __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
     const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kSmallWaves);
     SmallState S;
     small_segment(S, a, b, g, base, s0, s1, si, lane);
-    // fold: waves [half, 2 half) hand their state to waves [0, half)
-#pragma unroll
-    for (int half = kSmallWaves / 2; half >= 1; half >>= 1) {
-      if (wv >= half && wv < 2 * half) state_to_lds(S, merge_lds + (wv - half) * kStateFloats, lane);
-      __syncthreads();
-      if (wv < half) merge_from_lds(S, merge_lds + wv * kStateFloats, lane, a.scale_log2e);
-      __syncthreads();
-    }
-    if (wv == 0) store_partial(a.ws[0] + (size_t)(w + seg) * kSmallSlot, kSmallRows, 0, S.o, S.m, S.l, lane);
+    fold_and_store(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e);
     u0 += nt;
   }
 }
@@ -1188,7 +1214,7 @@ __device__ inline void medium_worker(const MainArgs& a, int64_t w, ClassPlan& cp
 // ---- the prefix kernel: one launch, workgroups apportioned to the classes by the plan ------
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
-  __shared__ float4 lds_raw[8192];  // 128 KB, carved up per class
+  __shared__ float4 lds_raw[8448];  // 132 KB, carved up per class (class 0: eight states of 16.5 KB)
   const int64_t wg = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
