@@ -258,8 +258,8 @@ typedef struct {
   void* d_out;
   float* d_lse; /* [total_nodes][Hq] or NULL */
   /* Optional host copy of d_cu_nodes (the host that ran smart_select_tree has it), or NULL.
-   * Used only to skip launching kernels no sequence of the batch needs; results do not
-   * depend on it.  It must agree with d_cu_nodes. */
+   * A hint only: results never depend on it and the present kernels plan on the device
+   * without it.  If given it must agree with d_cu_nodes. */
   const int32_t* h_cu_nodes;
 } tva_params;
 

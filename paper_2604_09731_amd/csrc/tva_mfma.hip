@@ -13,9 +13,15 @@
 //    row's softmax reduction stays inside a lane, and the probabilities come
 //    out of the first product already in the operand layout of the second.
 //    The key range of the whole batch is cut into equal shares, one per
-//    wavefront ("worker"), independent of sequence boundaries, so ragged
-//    prefix lengths do not unbalance the machine; each (worker, segment) pair
-//    leaves an unnormalised partial (max, sum, O).
+//    worker, independent of sequence boundaries, so ragged prefix lengths do
+//    not unbalance the machine; each (worker, segment) pair leaves an
+//    unnormalised partial (max, sum, O).  Sequences fall in three classes by
+//    their rows per kv head (<= 32, <= 64, more); ONE kernel launch serves all
+//    three, its workgroups dealt to the classes in proportion to their work:
+//    class 0 streams K/V from HBM straight into operand registers (eight
+//    wavefronts share a worker's tiles), class 1 does the same with two row
+//    tiles per wavefront, class 2 stages tiles in LDS (HBM -> LDS without
+//    passing through registers) for eight wavefronts of 32 rows each.
 //
 //  * the tree part (a node sees only itself and its ancestors: a handful of
 //    keys selected by a 128-bit mask) is sparse and tiny.  It is evaluated in
