@@ -126,3 +126,49 @@ def accept_by_path_enumeration(cu_nodes, parent, token, target_next, max_depth):
         lens[b] = best_len
         ends[b] = best_end
     return lens, ends
+
+
+def commit(cu_nodes, accept_len, accept_path, k_tree, v_tree, k_cache, v_cache, block_table,
+           prefix_len, max_depth):
+    """Makes the tokens a verify step produced part of their sequences.
+
+    A step yields, per sequence, the root and the accept_len accepted draft
+    nodes (the path tree_accept walked; "accepted" prefix by prefix, Sec. 3.1
+    below Eq. "cum_prob").  Node accept_path[b][i] sits at depth i, so its
+    position id is prefix_len[b] + i: its K/V row goes to that token position
+    of sequence b's paged cache (block block_table[b][pos // block_size], slot
+    pos % block_size), and the prefix grows to prefix_len[b] + accept_len[b] + 1.
+
+    Plain layout on this side: k_cache, v_cache are [num_blocks][Hkv][block_size][D]
+    numpy arrays, modified in place; k_tree, v_tree are [N][Hkv][D].
+    Returns (new_prefix_len, status); status[b] is 0, -3 (no room in the block
+    table: nothing is written for b and its length stays) or -2 (a path that is
+    not a path of the tree's size: same treatment).
+    """
+    B = len(cu_nodes) - 1
+    block_size = k_cache.shape[2]
+    max_blocks = block_table.shape[1]
+    new_len = [int(x) for x in prefix_len]
+    status = [0] * B
+    for b in range(B):
+        base = int(cu_nodes[b])
+        n_b = int(cu_nodes[b + 1]) - base
+        a = int(accept_len[b])
+        nodes = [int(accept_path[b][i]) for i in range(max(0, min(a, max_depth)) + 1)]
+        if a < 0 or a > max_depth or any(not (0 <= v < n_b) for v in nodes):
+            status[b] = -2
+            continue
+        start = int(prefix_len[b])
+        if start < 0 or start + a + 1 > max_blocks * block_size:
+            status[b] = -3
+            continue
+        blocks = [int(block_table[b][(start + i) // block_size]) for i in range(a + 1)]
+        if any(not (0 <= blk < k_cache.shape[0]) for blk in blocks):
+            status[b] = -2
+            continue
+        for i, v in enumerate(nodes):
+            pos = start + i
+            k_cache[blocks[i], :, pos % block_size, :] = k_tree[base + v]
+            v_cache[blocks[i], :, pos % block_size, :] = v_tree[base + v]
+        new_len[b] = start + a + 1
+    return new_len, status

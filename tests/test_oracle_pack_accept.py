@@ -87,3 +87,127 @@ def test_accept_degenerate_cases():
     assert alen == [5, 1] and bonus[0] == 42 and paths[1][:2] == [0, 1]   # smallest sibling wins the tie
     alen, _, bonus = PA.accept(cu, parent, token, target, 3)
     assert alen[0] == 3 and bonus[0] == 4
+
+
+def _commit_case(seed, block_size=16):
+    import numpy as np
+    from paper_2604_09731_amd import workloads as W
+    rng = np.random.default_rng(seed)
+    B, Hkv, D, max_depth = 3, 2, 8, 5
+    sizes = [int(rng.integers(1, 12)) for _ in range(B)]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([W.random_tree(n, rng, "random") for n in sizes]).astype(np.int32)
+    N = int(cu[-1])
+    prefix_len = rng.integers(0, 3 * block_size, size=B).astype(np.int32)
+    max_blocks = 4
+    perm = rng.permutation(B * max_blocks + 2)
+    block_table = perm[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+    k_cache = rng.standard_normal((B * max_blocks + 2, Hkv, block_size, D))
+    v_cache = rng.standard_normal(k_cache.shape)
+    k_tree = rng.standard_normal((N, Hkv, D))
+    v_tree = rng.standard_normal((N, Hkv, D))
+    # a real root-to-node path per sequence
+    depth, _, _, _ = PA.pack(cu, parent, prefix_len)
+    accept_len, paths = [], []
+    for b in range(B):
+        base, n = int(cu[b]), sizes[b]
+        v = int(rng.integers(0, n))
+        while depth[base + v] > max_depth:
+            v = int(parent[base + v])
+        chain = []
+        while v >= 0:
+            chain.append(v)
+            v = int(parent[base + v])
+        chain = chain[::-1]
+        accept_len.append(len(chain) - 1)
+        paths.append(chain + [-1] * (max_depth + 1 - len(chain)))
+    return dict(cu=cu, parent=parent, prefix_len=prefix_len, block_table=block_table, k_cache=k_cache,
+                v_cache=v_cache, k_tree=k_tree, v_tree=v_tree, accept_len=accept_len, paths=paths,
+                max_depth=max_depth, Hkv=Hkv, D=D, sizes=sizes)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_commit_writes_exactly_the_path_tokens(seed):
+    """Every cache element is either untouched or the K/V row of the path node whose position
+    id it is (position ids come from the independently pinned pack()), and lengths grow by
+    the number of tokens the step produced."""
+    import numpy as np
+    c = _commit_case(seed)
+    k0, v0 = c["k_cache"].copy(), c["v_cache"].copy()
+    new_len, status = PA.commit(c["cu"], c["accept_len"], c["paths"], c["k_tree"], c["v_tree"], c["k_cache"],
+                                c["v_cache"], c["block_table"], c["prefix_len"], c["max_depth"])
+    assert status == [0] * len(status)
+    _, position, node_seq, _ = PA.pack(c["cu"], c["parent"], c["prefix_len"])
+    touched = np.zeros(k0.shape[:1] + k0.shape[2:3], bool)   # [block][slot]
+    bs = k0.shape[2]
+    for b in range(len(c["sizes"])):
+        base = int(c["cu"][b])
+        assert new_len[b] == int(c["prefix_len"][b]) + c["accept_len"][b] + 1
+        for v in c["paths"][b]:
+            if v < 0:
+                continue
+            pos = position[base + v]
+            blk = int(c["block_table"][b][pos // bs])
+            assert not touched[blk, pos % bs]
+            touched[blk, pos % bs] = True
+            assert (c["k_cache"][blk, :, pos % bs, :] == c["k_tree"][base + v]).all()
+            assert (c["v_cache"][blk, :, pos % bs, :] == c["v_tree"][base + v]).all()
+    untouched = ~touched
+    assert (c["k_cache"].transpose(0, 2, 1, 3)[untouched] == k0.transpose(0, 2, 1, 3)[untouched]).all()
+    assert (c["v_cache"].transpose(0, 2, 1, 3)[untouched] == v0.transpose(0, 2, 1, 3)[untouched]).all()
+
+
+def test_commit_then_decode_equals_attending_the_path(oracle_attention):
+    """After the commit, a fresh single-node tree over the longer prefix sees exactly the keys
+    the deepest accepted node saw before it (old prefix + its ancestors and itself): both
+    attentions, computed by the attention oracle, agree."""
+    import numpy as np
+    c = _commit_case(11)
+    OA = oracle_attention
+    B = len(c["sizes"])
+    rng = np.random.default_rng(5)
+    q_new = rng.standard_normal((B, 4, c["D"]))          # one query node per sequence, 4 heads (G = 2)
+    scale = 0.3
+    # before: a tree that is the accepted path plus one extra leaf below its end carrying q_new;
+    # the leaf's own key is a new token k*, v*
+    k_star, v_star = rng.standard_normal((B, c["Hkv"], c["D"])), rng.standard_normal((B, c["Hkv"], c["D"]))
+    cu2, par2, q2, kt2, vt2 = [0], [], [], [], []
+    for b in range(B):
+        base = int(c["cu"][b])
+        path = [v for v in c["paths"][b] if v >= 0]
+        for i, v in enumerate(path):
+            par2.append(i - 1)
+            q2.append(np.zeros((4, c["D"])))
+            kt2.append(c["k_tree"][base + v])
+            vt2.append(c["v_tree"][base + v])
+        par2.append(len(path) - 1)
+        q2.append(q_new[b])
+        kt2.append(k_star[b])
+        vt2.append(v_star[b])
+        cu2.append(cu2[-1] + len(path) + 1)
+    before, _ = OA.tree_attention(np.array(q2), np.array(kt2), np.array(vt2), c["k_cache"].copy(), c["v_cache"].copy(),
+                                  c["block_table"], c["prefix_len"], np.array(cu2, np.int32), np.array(par2, np.int32), scale)
+    new_len, status = PA.commit(c["cu"], c["accept_len"], c["paths"], c["k_tree"], c["v_tree"], c["k_cache"],
+                                c["v_cache"], c["block_table"], c["prefix_len"], c["max_depth"])
+    assert status == [0] * B
+    after, _ = OA.tree_attention(q_new, k_star, v_star, c["k_cache"], c["v_cache"], c["block_table"],
+                                 np.array(new_len, np.int32), np.arange(B + 1, dtype=np.int32),
+                                 np.full(B, -1, np.int32), scale)
+    leaf_rows = np.array(cu2[1:]) - 1
+    assert np.abs(before[leaf_rows] - after).max() < 1e-12
+
+
+def test_commit_refuses_what_does_not_fit_or_is_no_path():
+    import numpy as np
+    c = _commit_case(2)
+    k0 = c["k_cache"].copy()
+    # sequence 0: the block table is full; sequence 1: a path entry outside the tree
+    c["prefix_len"][0] = c["block_table"].shape[1] * k0.shape[2] - c["accept_len"][0]
+    c["paths"][1][0] = c["sizes"][1]
+    new_len, status = PA.commit(c["cu"], c["accept_len"], c["paths"], c["k_tree"], c["v_tree"], c["k_cache"],
+                                c["v_cache"], c["block_table"], c["prefix_len"], c["max_depth"])
+    assert status[0] == -3 and status[1] == -2 and status[2] == 0
+    assert new_len[0] == c["prefix_len"][0] and new_len[1] == c["prefix_len"][1]
+    for b in (0, 1):
+        for blk in c["block_table"][b]:
+            assert (c["k_cache"][blk] == k0[blk]).all()
