@@ -21,6 +21,8 @@
  *                          prefix, Sec. 3.1 below Eq. "cum_prob")
  *   kv_cache_write         writes token K/V rows into the paged cache in the
  *                          layout tree_verify_attention streams fastest
+ *   tree_commit            appends the accepted path's K/V rows to the cache and
+ *                          advances the prefix lengths (closes the step's loop)
  *
  * Conventions
  *   - Every function returns int32_t: SMART_OK (0) or a negative error code.
@@ -282,6 +284,36 @@ int32_t tree_accept(smart_ctx* ctx, void* stream, int32_t batch, int32_t max_dep
                     const int32_t* d_cu_nodes, const int32_t* d_parent, const int32_t* d_token,
                     const int32_t* d_target_next,
                     int32_t* d_accept_len, int32_t* d_accept_path, int32_t* d_bonus_token);
+
+/* ---------------------------------------------------------------------------
+ * tree_commit (device)
+ *
+ * Makes the tokens a verify step produced part of their sequences (a draft
+ * path is accepted prefix by prefix, Sec. 3.1 below Eq. "cum_prob"; the root is
+ * the token every step yields): for i = 0 .. accept_len[b], node
+ * accept_path[b][i] (depth i, position id prefix_len[b] + i) has its row of
+ * d_k_tree / d_v_tree written to token position prefix_len[b] + i of sequence
+ * b's paged cache (block d_block_table[b][pos / block_size], slot
+ * pos % block_size, in the given layout), and
+ * d_new_prefix_len[b] = prefix_len[b] + accept_len[b] + 1.
+ * d_status[b] = 0; SMART_ECAP if the block table has no room for the new
+ * tokens; SMART_ETREE if accept_len[b] is outside [0, max_depth], a path entry
+ * is not a node of the tree or a block id is outside the cache.  A sequence
+ * with a non-zero status keeps its length and nothing of it is written.
+ * d_new_prefix_len must not alias d_prefix_len.
+ * Host errors: SMART_EINVAL (null pointers, sizes, dtype, layout, strides as for
+ * kv_cache_write).
+ * ------------------------------------------------------------------------- */
+int32_t tree_commit(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layout,
+                    int32_t batch, int32_t max_depth, int32_t num_kv_heads, int32_t head_dim,
+                    int32_t block_size, int32_t max_blocks_per_seq, int32_t num_blocks,
+                    const int32_t* d_cu_nodes, const int32_t* d_accept_len, const int32_t* d_accept_path,
+                    const void* d_k_tree, const void* d_v_tree,
+                    const int32_t* d_block_table, const int32_t* d_prefix_len,
+                    void* d_k_cache, void* d_v_cache,
+                    int64_t cache_block_stride, int64_t cache_head_stride,
+                    int64_t cache_token_stride /* PLAIN only */,
+                    int32_t* d_new_prefix_len, int32_t* d_status);
 
 #ifdef __cplusplus
 }

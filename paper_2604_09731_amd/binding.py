@@ -27,7 +27,7 @@ SMART_MAX_NODES = 128
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "tree_upload",
            "tree_pack",
-           "kv_cache_write", "tree_verify_attention", "tree_accept"]
+           "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
 
 
 class SmartError(RuntimeError):
@@ -92,6 +92,9 @@ def _lib():
                                        i64, i64, i64]
         lib.tree_verify_attention.restype = i32
         lib.tree_verify_attention.argtypes = [vp, vp, ctypes.POINTER(TvaParams)]
+        lib.tree_commit.restype = i32
+        lib.tree_commit.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp,
+                                    vp, vp, i64, i64, i64, vp, vp]
         lib.tree_accept.restype = i32
         lib.tree_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         _libh = lib
@@ -314,3 +317,21 @@ class SmartTree:
                                 _ptr(bonus))
         _check(rc, "tree_accept")
         return accept_len, accept_path, bonus
+
+    # -- tree_commit -------------------------------------------------------
+    def tree_commit(self, cu_nodes, accept_len, accept_path, k_tree, v_tree, k_cache, v_cache, block_table,
+                    prefix_len, layout, block_size, num_blocks, block_stride, head_stride, token_stride=0):
+        """Appends the accepted path's K/V rows to the paged cache (in place); returns
+        (new_prefix_len, status)."""
+        torch = _torch()
+        B = cu_nodes.shape[0] - 1
+        _, Hkv, D = k_tree.shape
+        new_len = torch.empty(B, dtype=torch.int32, device=cu_nodes.device)
+        status = torch.empty(B, dtype=torch.int32, device=cu_nodes.device)
+        rc = _lib().tree_commit(self._h, _stream_ptr(), _dtype_code(k_tree), layout, B, accept_path.shape[1] - 1,
+                                Hkv, D, block_size, block_table.shape[1], num_blocks, _ptr(cu_nodes),
+                                _ptr(accept_len), _ptr(accept_path), _ptr(k_tree), _ptr(v_tree), _ptr(block_table),
+                                _ptr(prefix_len), _ptr(k_cache), _ptr(v_cache), block_stride, head_stride,
+                                token_stride, _ptr(new_len), _ptr(status))
+        _check(rc, "tree_commit")
+        return new_len, status

@@ -1,4 +1,4 @@
-// kv_cache_write: scatter token K/V rows into the paged cache.
+// kv_cache_write / tree_commit: scatter token K/V rows into the paged cache.
 //
 // The interleaved layout groups 8 elements into one matrix-core operand vector
 // (K: 8 consecutive head dims of one token; V: 8 consecutive tokens of one head
@@ -34,7 +34,104 @@ __global__ __launch_bounds__(256) void kv_cache_write_kernel(
   }
 }
 
+// One workgroup per (path index i, sequence b).  Every workgroup of a sequence takes the same
+// accept / refuse decision from the same inputs; workgroup i = 0 reports it.
+template <typename T>
+__global__ __launch_bounds__(256) void tree_commit_kernel(
+    int layout, int batch, int max_depth, int Hkv, int D, int block_size, int max_blocks, int num_blocks,
+    const int32_t* __restrict__ cu_nodes, const int32_t* __restrict__ accept_len,
+    const int32_t* __restrict__ accept_path, const T* __restrict__ k_tree, const T* __restrict__ v_tree,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ prefix_len,
+    T* __restrict__ k_cache, T* __restrict__ v_cache, int64_t block_stride, int64_t head_stride,
+    int64_t token_stride, int32_t* __restrict__ new_prefix_len, int32_t* __restrict__ status) {
+  const int i = blockIdx.x, b = blockIdx.y;
+  const int base = cu_nodes[b];
+  const int n = cu_nodes[b + 1] - base;
+  const int a = accept_len[b];
+  const int start = prefix_len[b];
+  const int32_t* path = accept_path + (size_t)b * (max_depth + 1);
+  int verdict = SMART_OK;
+  if (base < 0 || a < 0 || a > max_depth) {
+    verdict = SMART_ETREE;
+  } else if (start < 0 || (int64_t)start + a + 1 > (int64_t)max_blocks * block_size) {
+    verdict = SMART_ECAP;
+  } else {
+    for (int k = 0; k <= a; ++k) {  // at most max_depth + 1 <= 129 entries
+      const int v = path[k];
+      const int blk = block_table[(size_t)b * max_blocks + (start + k) / block_size];
+      if (v < 0 || v >= n || blk < 0 || blk >= num_blocks) verdict = SMART_ETREE;
+    }
+  }
+  if (i == 0 && threadIdx.x == 0) {
+    status[b] = verdict;
+    new_prefix_len[b] = verdict == SMART_OK ? start + a + 1 : start;
+  }
+  if (verdict != SMART_OK || i > a) return;
+  const int pos = start + i;
+  const int64_t blk = block_table[(size_t)b * max_blocks + pos / block_size];
+  const int slot = pos % block_size;
+  const size_t src = (size_t)(base + path[i]) * Hkv * D;
+  for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+    const int g = e / D, d = e % D;
+    const int64_t page = blk * block_stride + (int64_t)g * head_stride;
+    int64_t ko, vo;
+    if (layout == SMART_KV_PLAIN) {
+      ko = vo = page + (int64_t)slot * token_stride + d;
+    } else {
+      ko = page + ((int64_t)(d / 8) * block_size + slot) * 8 + d % 8;
+      vo = page + ((int64_t)(slot / 8) * D + d) * 8 + slot % 8;
+    }
+    k_cache[ko] = k_tree[src + e];
+    v_cache[vo] = v_tree[src + e];
+  }
+}
+
 }  // namespace
+
+extern "C" int32_t tree_commit(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layout,
+                               int32_t batch, int32_t max_depth, int32_t num_kv_heads, int32_t head_dim,
+                               int32_t block_size, int32_t max_blocks_per_seq, int32_t num_blocks,
+                               const int32_t* d_cu_nodes, const int32_t* d_accept_len,
+                               const int32_t* d_accept_path, const void* d_k_tree, const void* d_v_tree,
+                               const int32_t* d_block_table, const int32_t* d_prefix_len,
+                               void* d_k_cache, void* d_v_cache, int64_t cache_block_stride,
+                               int64_t cache_head_stride, int64_t cache_token_stride,
+                               int32_t* d_new_prefix_len, int32_t* d_status) {
+  if (!ctx || batch < 0 || max_depth < 0 || max_depth > SMART_MAX_NODES || num_kv_heads <= 0 ||
+      head_dim <= 0 || block_size <= 0 || max_blocks_per_seq < 0 || num_blocks < 0)
+    return SMART_EINVAL;
+  if (dtype != SMART_F32 && dtype != SMART_BF16) return SMART_EINVAL;
+  if (kv_layout != SMART_KV_PLAIN && kv_layout != SMART_KV_INTERLEAVED) return SMART_EINVAL;
+  if (kv_layout == SMART_KV_INTERLEAVED && (block_size % 8 != 0 || head_dim % 8 != 0))
+    return SMART_EINVAL;
+  const int64_t page = (int64_t)block_size * head_dim;
+  if (kv_layout == SMART_KV_PLAIN && cache_token_stride < head_dim) return SMART_EINVAL;
+  if (cache_head_stride < (kv_layout == SMART_KV_PLAIN ? (block_size - 1) * cache_token_stride + head_dim : page))
+    return SMART_EINVAL;
+  if (cache_block_stride < cache_head_stride) return SMART_EINVAL;
+  if (batch == 0) return SMART_OK;
+  if (batch > 65535) return SMART_EINVAL;  // grid y
+  if (!d_cu_nodes || !d_accept_len || !d_accept_path || !d_k_tree || !d_v_tree || !d_block_table ||
+      !d_prefix_len || !d_k_cache || !d_v_cache || !d_new_prefix_len || !d_status ||
+      d_new_prefix_len == d_prefix_len)
+    return SMART_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  const dim3 grid(max_depth + 1, batch);
+  if (dtype == SMART_F32)
+    hipLaunchKernelGGL(tree_commit_kernel<float>, grid, dim3(256), 0, s, kv_layout, batch, max_depth,
+                       num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks, d_cu_nodes,
+                       d_accept_len, d_accept_path, (const float*)d_k_tree, (const float*)d_v_tree,
+                       d_block_table, d_prefix_len, (float*)d_k_cache, (float*)d_v_cache,
+                       cache_block_stride, cache_head_stride, cache_token_stride, d_new_prefix_len, d_status);
+  else
+    hipLaunchKernelGGL(tree_commit_kernel<uint16_t>, grid, dim3(256), 0, s, kv_layout, batch, max_depth,
+                       num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks, d_cu_nodes,
+                       d_accept_len, d_accept_path, (const uint16_t*)d_k_tree, (const uint16_t*)d_v_tree,
+                       d_block_table, d_prefix_len, (uint16_t*)d_k_cache, (uint16_t*)d_v_cache,
+                       cache_block_stride, cache_head_stride, cache_token_stride, d_new_prefix_len, d_status);
+  SMART_HIP_CHECK(hipGetLastError());
+  return SMART_OK;
+}
 
 extern "C" int32_t kv_cache_write(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layout,
                                   int32_t n_tokens, int32_t num_kv_heads, int32_t head_dim,

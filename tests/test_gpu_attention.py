@@ -287,3 +287,65 @@ def test_chain_single_node_and_empty_batch(lib, oracle_attention):
                                     torch.empty((0, 2), dtype=torch.int64, device="cuda"),
                                     0.1, B.SMART_KV_INTERLEAVED)
     assert out.shape[0] == 0
+
+
+def test_two_steps_of_the_loop_through_commit(lib, oracle_attention):
+    """verify -> accept -> commit -> verify again.  The second step's attention runs on the
+    device over the cache the device grew; the oracle does the same walk on its own cache.
+    Accept decisions are integers (bit-exact), so both sides commit the same nodes; the
+    second step's output must match to the bf16 tolerance, and the rows must see the new
+    tokens (their output changes when the committed V rows are what they were not)."""
+    import torch
+    from oracle import pack_accept as PA
+    w = W.Workload("loop", "bf16", 5, 8, 2, 128, 0, 0)
+    rng = np.random.default_rng(77)
+    sizes = [9, 30, 4, 17, 12]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([W.random_tree(n, rng, "random") for n in sizes]).astype(np.int32)
+    N = int(cu[-1])
+    max_depth = 6
+    prefix_len = np.array([200, 1000, 40, 520, 8], np.int32)      # 8 free slots in every last block
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=prefix_len, trees=(cu, parent))
+    token = rng.integers(0, 3, size=N).astype(np.int32)           # few distinct tokens: long accepted paths
+    target = rng.integers(0, 3, size=N).astype(np.int32)
+    # step 1 on the device
+    out1, _ = case.run(lib)
+    acc_len, acc_path, _ = lib.tree_accept(case.cu_nodes, case.parent_d, torch.from_numpy(token).cuda(),
+                                           torch.from_numpy(target).cuda(), max_depth)
+    nb = case.inp.meta["num_blocks"]
+    new_len, status = lib.tree_commit(case.cu_nodes, acc_len, acc_path, case.k_tree, case.v_tree, case.k_cache,
+                                      case.v_cache, case.block_table, case.prefix_len, B.SMART_KV_INTERLEAVED, 16, nb,
+                                      w.num_kv_heads * 16 * 128, 16 * 128)
+    torch.cuda.synchronize()
+    assert not status.cpu().numpy().any()
+    # the same walk on the oracle's side
+    ref_len, ref_path, _ = PA.accept(cu, parent, token, target, max_depth)
+    assert acc_len.cpu().numpy().tolist() == ref_len and acc_path.cpu().numpy().tolist() == ref_path
+    assert max(ref_len) >= 2
+    i = case.inp
+    ok, oc = i.k_cache.copy(), i.v_cache.copy()
+    grown, st = PA.commit(cu, ref_len, ref_path, i.k_tree, i.v_tree, ok, oc, i.block_table, prefix_len, max_depth)
+    assert st == [0] * w.batch and new_len.cpu().numpy().tolist() == grown
+    # step 2: new trees, new queries, over the grown prefixes
+    sizes2 = [5, 3, 20, 8, 33]
+    cu2 = np.concatenate([[0], np.cumsum(sizes2)]).astype(np.int32)
+    parent2 = np.concatenate([W.random_tree(n, rng, "random") for n in sizes2]).astype(np.int32)
+    N2 = int(cu2[-1])
+    q2 = W._normal(5, 1, (N2, w.num_q_heads, 128), 1.0, "bf16")
+    k2 = W._normal(5, 2, (N2, w.num_kv_heads, 128), 1.0, "bf16")
+    v2 = W._normal(5, 3, (N2, w.num_kv_heads, 128), 1.0, "bf16")
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    _, _, _, mask2, st2 = lib.tree_pack(d(cu2), d(parent2), new_len)
+    assert not st2.cpu().numpy().any()
+    out2, _ = lib.tree_verify_attention(H.torch_elems(q2, "bf16", "cuda"), H.torch_elems(k2, "bf16", "cuda"),
+                                        H.torch_elems(v2, "bf16", "cuda"), case.k_cache, case.v_cache, case.block_table,
+                                        new_len, d(cu2), mask2, i.scale, B.SMART_KV_INTERLEAVED, want_lse=True)
+    torch.cuda.synchronize()
+    grown = np.array(grown, np.int32)
+    ref2, _ = oracle_attention.tree_attention(q2, k2, v2, ok, oc, i.block_table, grown, cu2, parent2, i.scale)
+    got2 = H.out_to_f64(out2, "bf16")
+    assert np.isfinite(got2).all()
+    assert H.rel_err(got2, ref2) <= H.TOL["bf16"]
+    # and the committed tokens matter: without them the oracle's answer is measurably different
+    stale, _ = oracle_attention.tree_attention(q2, k2, v2, i.k_cache, i.v_cache, i.block_table, prefix_len, cu2, parent2, i.scale)
+    assert H.rel_err(stale, ref2) > 10 * H.TOL["bf16"] or np.abs(stale - ref2).max() > 0.05

@@ -179,3 +179,51 @@ def test_tree_upload_refuses_pageable_memory(lib):
     assert e.value.code == B.SMART_EINVAL
     torch.cuda.synchronize()
     assert (dev.cpu().numpy() == 5).all()
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("seed", range(2))
+def test_tree_commit_matches_oracle(lib, dtype, D, seed):
+    """Accepted paths from the library's own accept walk are committed on the device in both
+    cache layouts; caches, new lengths and status equal the oracle's, bit for bit.  One
+    sequence has no room left in its block table, one has a corrupted path."""
+    import torch
+    rng = np.random.default_rng(100 + seed)
+    Bsz, Hkv, bs, max_depth, max_blocks = 7, 2, 16, 6, 5
+    sizes = [int(x) for x in rng.integers(1, 40, size=Bsz)]
+    cu, parent, _ = _random_batch(seed + 50, sizes)
+    N = int(cu[-1])
+    token = rng.integers(0, 6, size=N).astype(np.int32)
+    target = rng.integers(0, 6, size=N).astype(np.int32)
+    prefix_len = rng.integers(0, (max_blocks - 1) * bs, size=Bsz).astype(np.int32)
+    nb = Bsz * max_blocks + 3
+    block_table = rng.permutation(nb)[:Bsz * max_blocks].reshape(Bsz, max_blocks).astype(np.int32)
+    k_tree = W._normal(seed, 1, (N, Hkv, D), 1.0, dtype)
+    v_tree = W._normal(seed, 2, (N, Hkv, D), 1.0, dtype)
+    plain_k = W._normal(seed, 3, (nb, Hkv, bs, D), 1.0, dtype)
+    plain_v = W._normal(seed, 4, (nb, Hkv, bs, D), 1.0, dtype)
+    acc_len, acc_path, _ = lib.tree_accept(_dev(cu), _dev(parent), _dev(token), _dev(target), max_depth)
+    h_len, h_path = acc_len.cpu().numpy().copy(), acc_path.cpu().numpy().copy()
+    assert h_len.max() >= 1                                   # some draft token is accepted
+    prefix_len[2] = max_blocks * bs - int(h_len[2])           # one token too many for sequence 2
+    h_path[4, 0] = sizes[4]                                   # not a node of sequence 4's tree
+    ref_k, ref_v = plain_k.copy(), plain_v.copy()
+    ref_len, ref_status = PA.commit(cu, h_len, h_path, k_tree, v_tree, ref_k, ref_v, block_table, prefix_len, max_depth)
+    assert ref_status[2] == B.SMART_ECAP and ref_status[4] == B.SMART_ETREE and sum(s == 0 for s in ref_status) == Bsz - 2
+    raw = lambda t: t.cpu().view(torch.int16 if dtype == "bf16" else torch.float32).numpy().view(k_tree.dtype)
+    tk, tv = H.torch_elems(k_tree, dtype, "cuda"), H.torch_elems(v_tree, dtype, "cuda")
+    for layout in (B.SMART_KV_PLAIN, B.SMART_KV_INTERLEAVED):
+        kc, vc = H.torch_elems(plain_k, dtype, "cuda"), H.torch_elems(plain_v, dtype, "cuda")
+        if layout == B.SMART_KV_INTERLEAVED:
+            kc, vc = B.interleave_kv_cache(kc, vc)
+        new_len, status = lib.tree_commit(_dev(cu), _dev(h_len), _dev(h_path), tk, tv, kc, vc, _dev(block_table),
+                                          _dev(prefix_len), layout, bs, nb, Hkv * bs * D, bs * D, D)
+        torch.cuda.synchronize()
+        assert status.cpu().numpy().tolist() == ref_status
+        assert new_len.cpu().numpy().tolist() == ref_len
+        if layout == B.SMART_KV_PLAIN:
+            assert np.array_equal(raw(kc).reshape(ref_k.shape), ref_k)
+            assert np.array_equal(raw(vc).reshape(ref_v.shape), ref_v)
+        else:
+            assert np.array_equal(raw(kc).reshape(nb, Hkv, -1), KL.interleave_plain_cache(ref_k, "k"))
+            assert np.array_equal(raw(vc).reshape(nb, Hkv, -1), KL.interleave_plain_cache(ref_v, "v"))

@@ -132,6 +132,19 @@ def test_device_entry_points_validate_on_the_host_first():
     assert lib.kv_cache_write(ctx, None, 5, 0, 1, 8, 128, 16, 4, ptr, ptr, ptr, ptr, ptr, 16384, 2048, 128) == B.SMART_EINVAL
     assert lib.kv_cache_write(ctx, None, 1, 1, 1, 8, 128, 12, 4, ptr, ptr, ptr, ptr, ptr, 16384, 2048, 128) == B.SMART_EINVAL
     assert lib.kv_cache_write(ctx, None, 1, 1, 1, 8, 128, 16, 4, ptr, ptr, ptr, ptr, ptr, 16384, 100, 128) == B.SMART_EINVAL
+    commit = lambda **kw: lib.tree_commit(*[kw.get(k, v) for k, v in dict(
+        ctx=ctx, stream=None, dtype=1, layout=1, batch=2, max_depth=4, Hkv=8, D=128, bs=16, max_blocks=4, nb=8,
+        cu=ptr, alen=ptr, apath=ptr, kt=ptr, vt=ptr, bt=ptr, plen=ptr, kc=ptr, vc=ptr, bstride=16384,
+        hstride=2048, tstride=128, nlen=ctypes.cast(fake, ctypes.c_void_p), st=ptr).items()])
+    assert commit(ctx=None) == B.SMART_EINVAL
+    assert commit(dtype=7) == B.SMART_EINVAL
+    assert commit(layout=3) == B.SMART_EINVAL
+    assert commit(max_depth=-1) == B.SMART_EINVAL
+    assert commit(bs=12) == B.SMART_EINVAL            # interleaved layout needs multiples of 8
+    assert commit(hstride=100) == B.SMART_EINVAL
+    assert commit(kt=None) == B.SMART_EINVAL
+    assert commit(nlen=ptr) == B.SMART_EINVAL         # new lengths may not alias the old ones
+    assert commit(batch=0) == B.SMART_OK
     assert lib.smart_set_option(None, 1, 0) == B.SMART_EINVAL
     assert lib.smart_set_option(ctx, B.SMART_OPT_TVA_PROFILE_STRIDE, 0) == B.SMART_EINVAL
     assert lib.tree_upload(None, None, ptr, ptr, 4) == B.SMART_EINVAL
