@@ -2,7 +2,7 @@
 """Benchmark of the tree-verification hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic input:
-  smart_select_tree (host) -> tree CSR to the GPU -> tree_pack ->
+  smart_select_tree (host) -> tree_upload_pack (tree CSR to the GPU + tree_pack) ->
   tree_verify_attention -> tree_accept.
 K steps are timed back to back (the device calls are asynchronous, so the host
 side of step i+1 overlaps the device side of step i, as it would in a serving
@@ -208,14 +208,16 @@ def main():
         return pack_args, P, acc_args
 
     calls = [device_calls(d_stage[0], 0), device_calls(d_stage[1], 1)]
-    upload_args = [(ctx, stream, vp(stage[i]), vp(d_stage[i]), n_stage) for i in range(2)]
+    hp = lambda t, off: ctypes.c_void_p(t.data_ptr() + 4 * off)
+    upload_pack_args = [(ctx, stream, Bsz, N, hp(stage[i], 0), hp(stage[i], Bsz + 1), hp(stage[i], Bsz + 1 + cap),
+                         hp(d_stage[i], 0), hp(d_stage[i], Bsz + 1), hp(d_stage[i], Bsz + 1 + cap), vp(prefix_len),
+                         vp(depth), vp(position), vp(node_seq), vp(anc_mask), vp(status)) for i in range(2)]
 
     def step(i):
         s = i & 1
         select[s]()                                              # a1: host selection
-        pack_args, P, acc_args = calls[s]
-        rc = L.tree_upload(*upload_args[s])                      # tree CSR to the GPU (copy kernel)
-        rc = rc or L.tree_pack(*pack_args)                       # a2
+        _, P, acc_args = calls[s]
+        rc = L.tree_upload_pack(*upload_pack_args[s])            # tree CSR to the GPU + a2, one launch
         rc = rc or L.tree_verify_attention(ctx, stream, ctypes.byref(P))   # a3 + a4
         rc = rc or L.tree_accept(*acc_args)                      # a5
         if rc:
@@ -271,7 +273,7 @@ def main():
 
     pack_args, P, acc_args = calls[0]
     att_us = time_device(lambda: L.tree_verify_attention(ctx, stream, ctypes.byref(P)))
-    pack_us = time_device(lambda: L.tree_pack(*pack_args))
+    pack_us = time_device(lambda: L.tree_upload_pack(*upload_pack_args[0]))
     acc_us = time_device(lambda: L.tree_accept(*acc_args))
     th0 = time.perf_counter()
     for _ in range(50):
@@ -313,7 +315,7 @@ def main():
                    "prefix_len_min_max": [int(inp.prefix_len.min()), int(inp.prefix_len.max())],
                    "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
                    "block_size": 16, "kv_layout": "interleaved"},
-        "breakdown_us": {"select_host": round(sel_us, 1), "tree_pack": round(pack_us, 2),
+        "breakdown_us": {"select_host": round(sel_us, 1), "tree_upload_pack": round(pack_us, 2),
                          "tree_verify_attention": round(att_us, 2), "tree_accept": round(acc_us, 2)},
         "attended_tokens_per_s": round(work["attended_tokens"] / (att_us * 1e-6), 1),
         "attention_tflops": round(tflops, 2),

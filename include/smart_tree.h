@@ -181,6 +181,29 @@ int32_t tree_upload(smart_ctx* ctx, void* stream, const void* h_pinned_src, void
                     int64_t n_words);
 
 /* ---------------------------------------------------------------------------
+ * tree_upload_pack (pinned host -> device, then tree_pack, in one launch)
+ *
+ * What tree_upload of the three arrays smart_select_tree wrote followed by
+ * tree_pack would do: d_cu_nodes[batch+1], d_parent[total_nodes] and (if both
+ * token pointers are given) d_token[total_nodes] receive copies of the pinned
+ * host arrays, and the outputs of tree_pack are produced from them.  One
+ * wavefront per sequence fetches that sequence's tree over the host link and
+ * packs it from LDS, which saves a kernel launch per verify step.
+ * total_nodes must equal h_pinned_cu_nodes[batch] (a sequence whose offsets
+ * leave [0, total_nodes] gets status SMART_ETREE and nothing of it is copied).
+ * The host must leave the pinned arrays untouched until the kernel has run.
+ * Errors: as tree_pack, plus SMART_EINVAL for pageable host memory and for
+ * token pointers of which only one is NULL.
+ * ------------------------------------------------------------------------- */
+int32_t tree_upload_pack(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nodes,
+                         const int32_t* h_pinned_cu_nodes, const int32_t* h_pinned_parent,
+                         const int32_t* h_pinned_token /* may be NULL */,
+                         int32_t* d_cu_nodes, int32_t* d_parent, int32_t* d_token /* may be NULL */,
+                         const int32_t* d_prefix_len,
+                         int32_t* d_depth, int32_t* d_position, int32_t* d_node_seq,
+                         uint64_t* d_anc_mask, int32_t* d_status);
+
+/* ---------------------------------------------------------------------------
  * tree_pack (device)
  *
  * For every node i of every sequence b (local ids):

@@ -26,7 +26,7 @@ SMART_MAX_NODES = 128
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "tree_upload",
-           "tree_pack",
+           "tree_upload_pack", "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
 
 
@@ -85,6 +85,8 @@ def _lib():
                                           vp, vp, vp, vp, vp, i64, vp, vp]
         lib.tree_upload.restype = i32
         lib.tree_upload.argtypes = [vp, vp, vp, vp, i64]
+        lib.tree_upload_pack.restype = i32
+        lib.tree_upload_pack.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.tree_pack.restype = i32
         lib.tree_pack.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.kv_cache_write.restype = i32
@@ -232,6 +234,24 @@ class SmartTree:
         rc = _lib().tree_upload(self._h, _stream_ptr(), _ptr(pinned_src), _ptr(dst), pinned_src.numel())
         _check(rc, "tree_upload")
         return dst
+
+    # -- tree_upload_pack --------------------------------------------------
+    def tree_upload_pack(self, pinned_cu_nodes, pinned_parent, pinned_token, prefix_len):
+        """Pinned host tree CSR -> device copies + tree_pack outputs, one launch.  Returns
+        (cu_nodes, parent, token, depth, position, node_seq, anc_mask, status) on the device."""
+        torch = _torch()
+        B = pinned_cu_nodes.shape[0] - 1
+        N = int(pinned_cu_nodes[B])
+        dev = prefix_len.device
+        i32 = lambda n: torch.empty(n, dtype=torch.int32, device=dev)
+        cu, par, tok = i32(B + 1), i32(N), (i32(N) if pinned_token is not None else None)
+        depth, position, node_seq, status = i32(N), i32(N), i32(N), i32(B)
+        anc_mask = torch.empty((N, 2), dtype=torch.int64, device=dev)
+        rc = _lib().tree_upload_pack(self._h, _stream_ptr(), B, N, _ptr(pinned_cu_nodes), _ptr(pinned_parent),
+                                     _ptr(pinned_token), _ptr(cu), _ptr(par), _ptr(tok), _ptr(prefix_len),
+                                     _ptr(depth), _ptr(position), _ptr(node_seq), _ptr(anc_mask), _ptr(status))
+        _check(rc, "tree_upload_pack")
+        return cu, par, tok, depth, position, node_seq, anc_mask, status
 
     # -- tree_pack ---------------------------------------------------------
     def tree_pack(self, cu_nodes, parent, prefix_len):

@@ -11,39 +11,28 @@ namespace {
 
 constexpr int kWave = 64;
 
-__global__ __launch_bounds__(kWave) void tree_pack_kernel(
-    int batch, int total_nodes, const int32_t* __restrict__ cu_nodes,
-    const int32_t* __restrict__ parent, const int32_t* __restrict__ prefix_len,
-    int32_t* __restrict__ depth, int32_t* __restrict__ position, int32_t* __restrict__ node_seq,
-    uint64_t* __restrict__ anc_mask, int32_t* __restrict__ status) {
-  const int b = blockIdx.x;
-  const int lane = threadIdx.x;
-  if (b >= batch) return;
-  int base = cu_nodes[b];
-  int end = cu_nodes[b + 1];
-  // keep every access inside the arrays whatever the offsets say
-  const bool bad_range = base < 0 || end < base || end > total_nodes;
-  if (bad_range) {
-    if (lane == 0) status[b] = SMART_ETREE;
-    return;
-  }
-  const int n = end - base;
+// The packing of one sequence by one wavefront; `parent_of(i)` yields the parent of local
+// node i (from device memory, or from LDS when the tree was just fetched from the host).
+template <typename ParentOf>
+__device__ inline void pack_sequence(int b, int lane, int base, int n, int len, ParentOf parent_of,
+                                     int32_t* __restrict__ depth, int32_t* __restrict__ position,
+                                     int32_t* __restrict__ node_seq, uint64_t* __restrict__ anc_mask,
+                                     int32_t* __restrict__ status) {
   bool ok = n >= 1 && n <= SMART_MAX_NODES;
   const int n_clamped = n < SMART_MAX_NODES ? n : SMART_MAX_NODES;
   // validate parents (lane-parallel), then agree across the wavefront
   bool mine_ok = true;
   for (int i = lane; i < n_clamped; i += kWave) {
-    const int p = parent[base + i];
+    const int p = parent_of(i);
     mine_ok = mine_ok && (i == 0 ? p == -1 : (p >= 0 && p < i));
   }
   ok = ok && __all(mine_ok);
-  const int len = prefix_len[b];
   for (int i = lane; i < n; i += kWave) {
     int d = 0;
     uint64_t lo = 0, hi = 0;
     if (ok) {
       // walk to the root; parent < child, so the walk is at most i steps
-      for (int j = i; j >= 0; j = parent[base + j]) {
+      for (int j = i; j >= 0; j = parent_of(j)) {
         if (j < 64) lo |= 1ull << j; else hi |= 1ull << (j - 64);
         ++d;
       }
@@ -56,6 +45,60 @@ __global__ __launch_bounds__(kWave) void tree_pack_kernel(
     anc_mask[2 * (size_t)(base + i) + 1] = hi;
   }
   if (lane == 0) status[b] = ok ? SMART_OK : SMART_ETREE;
+}
+
+__global__ __launch_bounds__(kWave) void tree_pack_kernel(
+    int batch, int total_nodes, const int32_t* __restrict__ cu_nodes,
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ prefix_len,
+    int32_t* __restrict__ depth, int32_t* __restrict__ position, int32_t* __restrict__ node_seq,
+    uint64_t* __restrict__ anc_mask, int32_t* __restrict__ status) {
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (b >= batch) return;
+  const int base = cu_nodes[b];
+  const int end = cu_nodes[b + 1];
+  // keep every access inside the arrays whatever the offsets say
+  if (base < 0 || end < base || end > total_nodes) {
+    if (lane == 0) status[b] = SMART_ETREE;
+    return;
+  }
+  pack_sequence(b, lane, base, end - base, prefix_len[b], [&](int i) { return parent[base + i]; }, depth,
+                position, node_seq, anc_mask, status);
+}
+
+// tree_upload of the selected trees and tree_pack in one launch: the wavefront of sequence b
+// fetches its tree from pinned host memory (two round trips over the host link: offsets, then
+// nodes), leaves device copies for the kernels that follow, and packs from LDS.
+__global__ __launch_bounds__(kWave) void tree_upload_pack_kernel(
+    int batch, int total_nodes, const int32_t* __restrict__ h_cu_nodes, const int32_t* __restrict__ h_parent,
+    const int32_t* __restrict__ h_token, int32_t* __restrict__ cu_nodes, int32_t* __restrict__ parent,
+    int32_t* __restrict__ token, const int32_t* __restrict__ prefix_len, int32_t* __restrict__ depth,
+    int32_t* __restrict__ position, int32_t* __restrict__ node_seq, uint64_t* __restrict__ anc_mask,
+    int32_t* __restrict__ status) {
+  __shared__ int32_t par[SMART_MAX_NODES];
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (b >= batch) return;
+  const int base = h_cu_nodes[b];
+  const int end = h_cu_nodes[b + 1];
+  const int len = prefix_len[b];
+  if (lane == 0) {
+    cu_nodes[b] = base;
+    if (b == batch - 1) cu_nodes[batch] = end;
+  }
+  if (base < 0 || end < base || end > total_nodes) {
+    if (lane == 0) status[b] = SMART_ETREE;
+    return;
+  }
+  const int n = end - base;
+  for (int i = lane; i < n; i += kWave) {
+    const int p = h_parent[base + i];
+    parent[base + i] = p;
+    if (i < SMART_MAX_NODES) par[i] = p;
+    if (token) token[base + i] = h_token[base + i];
+  }
+  __syncthreads();
+  pack_sequence(b, lane, base, n, len, [&](int i) { return par[i]; }, depth, position, node_seq, anc_mask, status);
 }
 
 __global__ __launch_bounds__(kWave) void tree_accept_kernel(
@@ -113,19 +156,22 @@ __global__ __launch_bounds__(256) void tree_upload_kernel(const int32_t* __restr
 
 }  // namespace
 
+static bool device_can_address(const void* p) {
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return attr.type == hipMemoryTypeHost || attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged;
+}
+
 extern "C" int32_t tree_upload(smart_ctx* ctx, void* stream, const void* h_pinned_src, void* d_dst,
                                int64_t n_words) {
   if (!ctx || n_words < 0) return SMART_EINVAL;
   if (n_words == 0) return SMART_OK;
   if (!h_pinned_src || !d_dst) return SMART_EINVAL;
   // a kernel that dereferences pageable host memory faults: refuse what the device cannot address
-  hipPointerAttribute_t attr;
-  if (hipPointerGetAttributes(&attr, h_pinned_src) != hipSuccess) {
-    (void)hipGetLastError();
-    return SMART_EINVAL;
-  }
-  if (attr.type != hipMemoryTypeHost && attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
-    return SMART_EINVAL;
+  if (!device_can_address(h_pinned_src)) return SMART_EINVAL;
   const bool aligned = (reinterpret_cast<uintptr_t>(h_pinned_src) % 16 == 0) &&
                        (reinterpret_cast<uintptr_t>(d_dst) % 16 == 0);
   const int64_t n_vec = aligned ? n_words / 4 : 0;
@@ -134,6 +180,29 @@ extern "C" int32_t tree_upload(smart_ctx* ctx, void* stream, const void* h_pinne
   if (blocks > 0x7fffffff) return SMART_EINVAL;
   hipLaunchKernelGGL(tree_upload_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const int32_t*>(h_pinned_src), static_cast<int32_t*>(d_dst), n_words, n_vec);
+  SMART_HIP_CHECK(hipGetLastError());
+  return SMART_OK;
+}
+
+extern "C" int32_t tree_upload_pack(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nodes,
+                                    const int32_t* h_pinned_cu_nodes, const int32_t* h_pinned_parent,
+                                    const int32_t* h_pinned_token, int32_t* d_cu_nodes, int32_t* d_parent,
+                                    int32_t* d_token, const int32_t* d_prefix_len, int32_t* d_depth,
+                                    int32_t* d_position, int32_t* d_node_seq, uint64_t* d_anc_mask,
+                                    int32_t* d_status) {
+  if (!ctx || batch < 0 || total_nodes < 0) return SMART_EINVAL;
+  if (!h_pinned_cu_nodes || !d_cu_nodes || !d_prefix_len || !d_status) return SMART_EINVAL;
+  if ((h_pinned_token == nullptr) != (d_token == nullptr)) return SMART_EINVAL;
+  if (total_nodes > 0 && (!h_pinned_parent || !d_parent || !d_depth || !d_position || !d_node_seq || !d_anc_mask))
+    return SMART_EINVAL;
+  if (batch == 0) return SMART_OK;
+  // a kernel that dereferences pageable host memory faults: refuse what the device cannot address
+  if (!device_can_address(h_pinned_cu_nodes) || (total_nodes > 0 && !device_can_address(h_pinned_parent)) ||
+      (h_pinned_token && total_nodes > 0 && !device_can_address(h_pinned_token)))
+    return SMART_EINVAL;
+  hipLaunchKernelGGL(tree_upload_pack_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch,
+                     total_nodes, h_pinned_cu_nodes, h_pinned_parent, h_pinned_token, d_cu_nodes, d_parent,
+                     d_token, d_prefix_len, d_depth, d_position, d_node_seq, d_anc_mask, d_status);
   SMART_HIP_CHECK(hipGetLastError());
   return SMART_OK;
 }

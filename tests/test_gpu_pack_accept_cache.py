@@ -227,3 +227,39 @@ def test_tree_commit_matches_oracle(lib, dtype, D, seed):
         else:
             assert np.array_equal(raw(kc).reshape(nb, Hkv, -1), KL.interleave_plain_cache(ref_k, "k"))
             assert np.array_equal(raw(vc).reshape(nb, Hkv, -1), KL.interleave_plain_cache(ref_v, "v"))
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_tree_upload_pack_equals_upload_then_pack(lib, seed):
+    """The fused launch leaves the same device copies and the same packing as the oracle's
+    pack of the host arrays; a malformed sequence is reported, not packed."""
+    import torch
+    sizes = [1, 7, 128, 64, 65, 3, 30]
+    shapes = ["random", "chain", "random", "star", "random", "chain", "random"]
+    cu, parent, rng = _random_batch(300 + seed, sizes, shapes)
+    N = int(cu[-1])
+    token = rng.integers(0, 1000, size=N).astype(np.int32)
+    prefix_len = rng.integers(0, 5000, size=len(sizes)).astype(np.int32)
+    bad = 3
+    parent_bad = parent.copy()
+    parent_bad[cu[bad] + 5] = 7                      # a parent that does not precede its child
+    pin = lambda a: torch.from_numpy(np.ascontiguousarray(a)).pin_memory()
+    d_cu, d_par, d_tok, depth, position, node_seq, mask, status = lib.tree_upload_pack(
+        pin(cu), pin(parent_bad), pin(token), _dev(prefix_len))
+    torch.cuda.synchronize()
+    assert np.array_equal(d_cu.cpu().numpy(), cu)
+    assert np.array_equal(d_par.cpu().numpy(), parent_bad)
+    assert np.array_equal(d_tok.cpu().numpy(), token)
+    st = status.cpu().numpy()
+    assert st[bad] == B.SMART_ETREE and not np.delete(st, bad).any()
+    r_depth, r_pos, r_seq, r_mask = PA.pack(cu, parent, prefix_len)
+    keep = np.ones(N, bool)
+    keep[cu[bad]:cu[bad + 1]] = False
+    assert np.array_equal(depth.cpu().numpy()[keep], np.array(r_depth)[keep])
+    assert np.array_equal(position.cpu().numpy()[keep], np.array(r_pos)[keep])
+    assert np.array_equal(node_seq.cpu().numpy()[keep], np.array(r_seq)[keep])
+    assert np.array_equal(mask.cpu().numpy().view(np.uint64)[keep], _mask_words(r_mask)[keep])
+    assert not depth.cpu().numpy()[~keep].any() and not mask.cpu().numpy()[~keep].any()
+    # pageable memory is refused
+    with pytest.raises(B.SmartError):
+        lib.tree_upload_pack(torch.from_numpy(cu), pin(parent), pin(token), _dev(prefix_len))

@@ -145,6 +145,13 @@ def test_device_entry_points_validate_on_the_host_first():
     assert commit(kt=None) == B.SMART_EINVAL
     assert commit(nlen=ptr) == B.SMART_EINVAL         # new lengths may not alias the old ones
     assert commit(batch=0) == B.SMART_OK
+    up = lambda *a: lib.tree_upload_pack(*a)
+    assert up(None, None, 1, 1, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert up(ctx, None, 1, 1, None, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL
+    assert up(ctx, None, 1, 1, ptr, ptr, None, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL   # token: both or none
+    assert up(ctx, None, 1, 1, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, None, ptr) == B.SMART_EINVAL
+    assert up(ctx, None, 0, 0, ptr, None, None, ptr, None, None, ptr, None, None, None, None, ptr) == B.SMART_OK
+    assert up(ctx, None, 1, 1, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == B.SMART_EINVAL   # pageable
     assert lib.smart_set_option(None, 1, 0) == B.SMART_EINVAL
     assert lib.smart_set_option(ctx, B.SMART_OPT_TVA_PROFILE_STRIDE, 0) == B.SMART_EINVAL
     assert lib.tree_upload(None, None, ptr, ptr, 4) == B.SMART_EINVAL
