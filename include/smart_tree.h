@@ -11,6 +11,8 @@
  *   smart_select_tree      which candidates form each sequence's tree
  *                          (Sec. 3.2, Eqs. "definition" .. "decision_rule",
  *                          Algorithm 1)
+ *   smart_cost_tables,     the fitted device cost models of Sec. 3.1 and the cost
+ *   smart_fit_cost_models  tables the selection rule consumes
  *   tree_pack              depth / position ids / ancestor bitmasks of the
  *                          chosen trees (what "verify the tree in a single
  *                          forward pass", Sec. 1, needs as mask and positions)
@@ -162,6 +164,37 @@ int32_t smart_select_tree(
     int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
     int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
     double* h_out_L, double* h_out_R);
+
+/* ---------------------------------------------------------------------------
+ * smart_cost_tables, smart_fit_cost_models (host)
+ *
+ * The device cost models of Sec. 3.1 ("Cost Modeling"), biases fixed to zero as
+ * the paper does:  C_draft(x) = lambda x  (Eq. "linear_model"),
+ * C_verify(x) = gamma (exp(delta x^rho) - 1)  (Eq. "exp_model"), x = tokens
+ * drafted into one forward pass.
+ *
+ * smart_cost_tables fills what smart_select_tree takes, in units of c_T
+ * (Eq. "definition"): h_cost[n] = (C_draft + C_verify)(tokens_per_node n) / c_T
+ * for n = 0 .. n_max + 1 and, if h_dcost is not NULL, the differentiated
+ * marginal cost of Eq. "marginal_cost" per NODE,
+ * h_dcost[n] = tokens_per_node (lambda + gamma delta rho x^(rho-1) exp(delta x^rho)) / c_T
+ * at x = tokens_per_node n, for n = 0 .. n_max (n = 0 with rho < 1: +inf).
+ * tokens_per_node is the batch size when a batch verifies together.
+ *
+ * smart_fit_cost_models fits the models to n_points timings by least squares:
+ * lambda from (h_x, h_t_draft) if h_t_draft is given; gamma, delta, rho from
+ * (h_x, h_t_verify) if h_t_verify is given (at least 3 points; the paper uses
+ * five forward passes), searched over rho in [0.05, 4] and an exponent
+ * delta max(x)^rho in [1e-6, 40]; *h_sse (may be NULL) receives the summed
+ * squared residual of the verify fit.
+ * Errors: SMART_EINVAL (null outputs, n_points too small, x <= 0, non-finite
+ * samples, non-positive c_T / tokens_per_node / rho, negative parameters).
+ * ------------------------------------------------------------------------- */
+int32_t smart_cost_tables(double lambda, double gamma, double delta, double rho, double c_T,
+                          double tokens_per_node, int32_t n_max, double* h_cost, double* h_dcost);
+int32_t smart_fit_cost_models(int32_t n_points, const double* h_x, const double* h_t_draft,
+                              const double* h_t_verify, double* h_lambda, double* h_gamma,
+                              double* h_delta, double* h_rho, double* h_sse);
 
 /* ---------------------------------------------------------------------------
  * tree_upload (pinned host -> device)

@@ -25,7 +25,7 @@ SMART_OPT_TVA_PROFILE_STRIDE = 4
 SMART_MAX_NODES = 128
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
-           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "tree_upload",
+           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
 
@@ -83,6 +83,10 @@ def _lib():
         lib.smart_select_tree.restype = i32
         lib.smart_select_tree.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, i32, i32,
                                           vp, vp, vp, vp, vp, i64, vp, vp]
+        lib.smart_cost_tables.restype = i32
+        lib.smart_cost_tables.argtypes = [f64, f64, f64, f64, f64, f64, i32, vp, vp]
+        lib.smart_fit_cost_models.restype = i32
+        lib.smart_fit_cost_models.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.tree_upload.restype = i32
         lib.tree_upload.argtypes = [vp, vp, vp, vp, i64]
         lib.tree_upload_pack.restype = i32
@@ -148,6 +152,34 @@ def smart_select_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, dcost=N
     n = int(o_cu[-1])
     return dict(cu_nodes=o_cu, parent=o_parent[:n], token=o_token[:n], cand_index=o_cand[:n],
                 pathprob=o_pp[:n], L=o_L[:batch], R=o_R[:batch])
+
+
+def smart_cost_tables(lam, gamma, delta, rho, c_T, tokens_per_node, n_max, want_dcost=True):
+    """(cost[n_max + 2], dcost[n_max + 1] or None) of the fitted device cost models."""
+    cost = np.zeros(n_max + 2, np.float64)
+    dcost = np.zeros(n_max + 1, np.float64) if want_dcost else None
+    p = lambda a: ctypes.c_void_p(a.ctypes.data) if a is not None else None
+    rc = _lib().smart_cost_tables(float(lam), float(gamma), float(delta), float(rho), float(c_T),
+                                  float(tokens_per_node), int(n_max), p(cost), p(dcost))
+    _check(rc, "smart_cost_tables")
+    return cost, dcost
+
+
+def smart_fit_cost_models(x, t_draft=None, t_verify=None):
+    """Least-squares fits; returns dict with lambda (if t_draft) and gamma, delta, rho, sse (if t_verify)."""
+    x = np.ascontiguousarray(x, np.float64)
+    td = None if t_draft is None else np.ascontiguousarray(t_draft, np.float64)
+    tv = None if t_verify is None else np.ascontiguousarray(t_verify, np.float64)
+    out = [ctypes.c_double(0.0) for _ in range(5)]
+    p = lambda a: ctypes.c_void_p(a.ctypes.data) if a is not None else None
+    rc = _lib().smart_fit_cost_models(x.shape[0], p(x), p(td), p(tv), *[ctypes.byref(o) for o in out])
+    _check(rc, "smart_fit_cost_models")
+    res = {}
+    if td is not None:
+        res["lambda"] = out[0].value
+    if tv is not None:
+        res.update(gamma=out[1].value, delta=out[2].value, rho=out[3].value, sse=out[4].value)
+    return res
 
 
 # ---------------------------------------------------------------------------

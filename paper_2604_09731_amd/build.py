@@ -13,7 +13,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 
 HIP_SOURCES = ["smart_ctx.hip", "tree_pack_accept.hip", "kv_cache_write.hip", "tva_general.hip",
                "tva_mfma.hip", "tva_api.hip"]
-HOST_SOURCES = ["smart_select.cpp"]
+HOST_SOURCES = ["smart_select.cpp", "smart_cost_model.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,

@@ -881,8 +881,6 @@ __device__ inline void large_segment(const MainArgs& a, int b, int g, int base, 
 // MFMA sits at [instruction][lane], so reads are 16 bytes per lane at
 // consecutive addresses, free of bank conflicts -- into one of two buffers:
 // tile t+1 is written while tile t is being multiplied, one barrier per tile.
-constexpr int kLargeWaves = kWgWaves;
-constexpr int kRing = 4;
 
 // K/V tiles travel HBM -> LDS without passing through registers (global_load_lds, 16 bytes a
 // lane).  A stage holds one 32-key tile in operand order: eight K vectors (k steps) then
