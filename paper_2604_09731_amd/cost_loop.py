@@ -1,0 +1,95 @@
+#!/usr/bin/env python3
+"""Cost-model loop on the device (Sec. 3.1 "Cost Modeling" -> Sec. 3.2 of the paper), for the
+attention layer this library implements.
+
+For each batch size: time tree_verify_attention for trees of 1, 4, 8, 16, 32 and 64 nodes per
+sequence (the paper profiles a handful of forward passes per device), take the plain decoding
+step (a tree that is only its root) as c_T, fit the power-exponential model of Eq. "exp_model"
+to the EXTRA time over that step as a function of the drafted tokens batch * (n - 1), build the
+cost tables (cost[n] = 1 + model / c_T) and let smart_select_tree choose trees over the same
+candidate forests.  Prints the fits and the chosen tree sizes per batch size.
+
+This measures ONE attention layer, not a whole target model: the point is the loop (measure,
+fit, select) on this hardware, not the absolute speedups.
+
+    python -m paper_2604_09731_amd.cost_loop [--batches 1 8 32 128] [--prefix 3584]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import numpy as np
+
+
+def main(argv=None):
+    import torch
+    from . import binding as B
+    from . import workloads as W
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--batches", type=int, nargs="+", default=[1, 8, 32, 128])
+    ap.add_argument("--prefix", type=int, default=3584)
+    ap.add_argument("--sizes", type=int, nargs="+", default=[1, 4, 8, 16, 32, 64])
+    ap.add_argument("--reps", type=int, default=50)
+    args = ap.parse_args(argv)
+    assert torch.cuda.is_available(), "needs the MI355X"
+    lib = B.SmartTree(0)
+    base = W.WORKLOADS["cfg3a"]
+    rows = []
+    for batch in args.batches:
+        w = base.scaled(batch=batch, prefix_min=args.prefix, prefix_max=args.prefix)
+        rng = np.random.default_rng(7)
+        big = W.random_tree(max(args.sizes), rng, "random")           # nested trees: the first n nodes of one tree
+        times = []
+        inp = None
+        for n in args.sizes:
+            cu = (np.arange(batch + 1) * n).astype(np.int32)
+            parent = np.tile(big[:n], batch).astype(np.int32)
+            inp = W.make_attention_inputs(w, cu, poison_unused=False)
+            dev = "cuda"
+            t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+            el = lambda a: torch.from_numpy(np.ascontiguousarray(a)).view(torch.int16).view(torch.bfloat16).to(dev)
+            kc, vc = B.interleave_kv_cache(el(inp.k_cache), el(inp.v_cache))
+            d_cu, d_par, d_len = t(cu), t(parent), t(inp.prefix_len)
+            _, _, _, mask, _ = lib.tree_pack(d_cu, d_par, d_len)
+            q, kt, vt, bt = el(inp.q), el(inp.k_tree), el(inp.v_tree), t(inp.block_table)
+            run = lambda: lib.tree_verify_attention(q, kt, vt, kc, vc, bt, d_len, d_cu, mask, inp.scale,
+                                                    B.SMART_KV_INTERLEAVED)
+            for _ in range(5):
+                run()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.reps):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3 / args.reps)       # microseconds per call
+            del kc, vc
+        sizes = np.array(args.sizes, np.float64)
+        times = np.array(times)
+        c_T = times[0] if args.sizes[0] == 1 else float(np.interp(1.0, sizes, times))
+        x = batch * (sizes[1:] - 1.0)
+        extra = np.maximum(times[1:] - c_T, 1e-3)
+        fit = B.smart_fit_cost_models(x, None, extra)
+        n_max = base.budget
+        table, dtable = B.smart_cost_tables(0.0, fit["gamma"], fit["delta"], fit["rho"], c_T, float(batch), n_max)
+        # cost[n]: one plain step plus the fitted extra of the n - 1 drafted nodes
+        cost = np.concatenate([[0.0], 1.0 + table[:n_max + 1]])
+        forest = W.make_forest(base.scaled(batch=min(batch, 32)))
+        sel = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost,
+                                  alpha=base.alpha, max_depth=base.max_depth, budget=n_max)
+        n_sel = np.diff(sel["cu_nodes"])
+        row = dict(batch=batch, sizes=args.sizes, us=[round(float(v), 2) for v in times], c_T_us=round(float(c_T), 2),
+                   gamma=fit["gamma"], delta=fit["delta"], rho=fit["rho"],
+                   rms_us=round(float(np.sqrt(fit["sse"] / len(x))), 3),
+                   tree_nodes_min_median_max=[int(n_sel.min()), int(np.median(n_sel)), int(n_sel.max())],
+                   L_mean=round(float(sel["L"].mean()), 3), R_mean=round(float(sel["R"].mean()), 3))
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+    return rows
+
+
+if __name__ == "__main__":
+    sys.exit(0 if main() else 1)
