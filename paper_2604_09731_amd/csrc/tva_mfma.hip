@@ -50,7 +50,7 @@ constexpr int kBlock = 16;            // tokens per cache block
 constexpr int kTile = 32;             // keys per tile = two cache blocks
 constexpr int kClasses = 3;           // sequences are classed by rows = nodes x group heads per kv head
 constexpr int kSmallRows = 32;        // class 0: all rows fit one 32-row MFMA tile
-constexpr int kMediumRows = 64;       // class 1: all rows fit two MFMA tiles of one wavefront
+constexpr int kMediumRows = 64;       // class 1: all rows fit two 32-row MFMA tiles
 constexpr int kLargeRows = 256;       // class 2: row groups of 256 = one workgroup of eight wavefronts x 32 rows
 constexpr int kWgWaves = 8;           // wavefronts per workgroup of the prefix kernel (two per SIMD)
 constexpr int kSmallSlot = kSmallRows * kD + 2 * kSmallRows;  // floats: O, then max, then sum
@@ -59,7 +59,7 @@ constexpr int kLargeSlot = kLargeRows * kD + 2 * kLargeRows;
 __host__ __device__ inline int class_rows(int cls) { return cls == 0 ? kSmallRows : (cls == 1 ? kMediumRows : kLargeRows); }
 __host__ __device__ inline int class_slot(int cls) { return cls == 0 ? kSmallSlot : (cls == 1 ? kMediumSlot : kLargeSlot); }
 constexpr int kCombineRows = 8;       // rows per combine wavefront (8 lanes per row)
-constexpr int kMinTilesPerWorker[kClasses] = {16, 8, 8};  // class 0 workers are 8-wave workgroups
+constexpr int kMinTilesPerWorker[kClasses] = {16, 32, 8};  // workers are 8-wave workgroups
 constexpr int kChunkTiles = 64;       // tiles whose block ids one pair of registers holds
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -69,7 +69,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 // A "unit" is one 32-key tile of one (sequence, kv head, row group) segment.
 // Sequences fall in three classes with separate unit spaces and kernels:
 //   class 0  n * G <= 32 rows: one row group, eight wavefronts share a worker's tiles
-//   class 1  33 .. 64 rows: one row group, one wavefront per worker, two MFMA row tiles
+//   class 1  33 .. 64 rows: one row group, tiles staged in LDS, two key groups of wavefronts
 //   class 2  more rows: row groups of 256 rows, four wavefronts x 64 rows per worker
 // ---------------------------------------------------------------------------
 struct SeqInfo {
@@ -204,13 +204,13 @@ __device__ inline void apportion(const int64_t (&tot_u)[kClasses], int workgroup
   int64_t first = 0;
 #pragma unroll
   for (int c = 0; c < kClasses; ++c) {
-    int64_t w = wg[c] * (c == 1 ? kWgWaves : 1);  // class 1 workers are single wavefronts
+    int64_t w = wg[c];  // a worker is a workgroup in every class
     const int64_t cap = tot_u[c] / kMinTilesPerWorker[c];
     if (w > cap) w = cap;
     if (tot_u[c] > 0 && w < 1) w = 1;
     workers[c] = w;
     first_wg[c] = first;
-    first += c == 1 ? (w + kWgWaves - 1) / kWgWaves : w;
+    first += w;
   }
   first_wg[kClasses] = first;
 }
@@ -484,7 +484,7 @@ __device__ inline int find_sequence(const int64_t* cum_units, int batch, int64_t
   return lo;
 }
 
-// ---- class 1: bandwidth-bound kernel, rows <= 32 -----------------------------------------
+// ---- class 0: bandwidth-bound kernel, rows <= 32 -----------------------------------------
 //
 // K and V each have one register buffer.  The loop body is straight-line:
 // scores -> request next K -> softmax -> output product -> request next V, so
@@ -765,123 +765,19 @@ __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
   }
 }
 
-// ---- class 2: more than 32 rows per (sequence, kv head) -----------------------------------
+// ---- classes 1 and 2: K/V tiles staged in LDS, shared by the eight wavefronts of a workgroup --
 //
-// A workgroup of four wavefronts (one per SIMD) is the worker; it streams the
-// tiles of its share once for a row group of up to 256 query rows, wavefront w
-// carrying rows 64 w .. 64 w + 63 of the group as two 32-row MFMA tiles.  The
-// four wavefronts read the same K/V tiles at about the same time, so the
-// second to fourth read of a tile is an L1 / L2 hit and HBM sees it once.
-// Wavefronts write disjoint row slices of the worker's partial: no barriers.
-// Query operands live in LDS (64 registers otherwise) and are re-read per tile.
-template <int QT, bool kMasked>
-__device__ inline void large_tile(floatx16 (&o)[QT][4], float (&m)[QT], float (&l)[QT], bf16x8 (&k)[8],
-                                  bf16x8 (&v)[2][4], const bf16x8* q_lds, int lane, float c, int n_valid,
-                                  const MainArgs& a, const TilePages& next) {
-  int q_off = lane;
-  asm volatile("" : "+v"(q_off));  // keeps the query reads inside the loop (they would cost 32 QT registers)
-  // one 32-row tile after the other, so that only one score tile is live at a time; K is
-  // released after the last score product, V after the last output product
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    floatx16 s = (floatx16)(0.f);
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {  // query operands four at a time: 16 registers in flight
-      bf16x8 qop[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) qop[i] = q_lds[(qt * 8 + half * 4 + i) * kWave + q_off];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[half * 4 + i], qop[i], s, 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (qt == QT - 1) load_k(k, a, next, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    if (kMasked) mask_tail(s, v, n_valid, lane >> 5);
-    bf16x8 pb0, pb1;
-    softmax_tile(s, m[qt], l[qt], o[qt], pb0, pb1, c);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt) {
-      o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[0][jt], pb0, o[qt][jt], 0, 0, 0);
-      o[qt][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[1][jt], pb1, o[qt][jt], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  load_v(v, a, next, lane);
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-// Streams tiles [t0, t1) of (sequence b, kv head g) against rows row0 .. row0 + 32 QT - 1 and
-// writes this wavefront's row slice of the partial.
-template <int QT>
-__device__ inline void large_segment(const MainArgs& a, int b, int g, int base, int row0, int t0, int t1,
-                                     const SeqInfo si, float* slot, int rows_in_slot, int qt0, int lane,
-                                     bf16x8* q_lds) {
-  const int h = lane >> 5, j = lane & 31;
-  const int M = si.n * a.G;
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    int rho = row0 + qt * 32 + j;
-    rho = rho < M ? rho : M - 1;  // padding rows repeat the last real row; never read back
-    const int node = base + rho / a.G, head = g * a.G + rho % a.G;
-    const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) q_lds[(qt * 8 + ks) * kWave + lane] = *(const bf16x8*)(qp + ks * 16);
-  }
-  floatx16 o[QT][4];
-  float m[QT], l[QT];
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt) o[qt][jt] = (floatx16)(0.f);
-    m[qt] = -INFINITY;
-    l[qt] = 0.f;
-  }
-  const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
-  const int n_blocks = (si.len + kBlock - 1) / kBlock;
-  const float c = a.scale_log2e;
-
-  for (int tc = t0; tc < t1; tc += kChunkTiles) {
-    const int te = min(t1, tc + kChunkTiles);
-    BlockIds ids;
-    ids.lo = bt_row[min(2 * tc + lane, n_blocks - 1)];
-    ids.hi = bt_row[min(2 * tc + kWave + lane, n_blocks - 1)];
-    asm volatile("" ::"v"(ids.lo), "v"(ids.hi));  // landed before the stream starts (see class 1)
-    const int full_end = min(te, si.len / kTile);
-    bf16x8 k[8], v[2][4];
-    {
-      const TilePages first = pages_from_ids(a, ids, 0, g);
-      load_k(k, a, first, lane);
-      load_v(v, a, first, lane);
-    }
-    int t = tc;
-    for (; t < full_end; ++t) {
-      const TilePages next = pages_from_ids(a, ids, min(t + 1, te - 1) - tc, g);
-      large_tile<QT, false>(o, m, l, k, v, q_lds, lane, c, kTile, a, next);
-    }
-    if (t < te) {  // the ragged last tile of the sequence
-      const TilePages next = pages_from_ids(a, ids, te - 1 - tc, g);
-      large_tile<QT, true>(o, m, l, k, v, q_lds, lane, c, si.len - t * kTile, a, next);
-    }
-  }
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) store_partial(slot, rows_in_slot, qt0 + qt, o[qt], m[qt], l[qt], lane);
-}
-
-// ---- class 2: K/V tiles staged in LDS, shared by the eight wavefronts of a workgroup --------
-//
-// A workgroup of eight wavefronts (two per SIMD) is the worker; it streams the
-// tiles of its share once for a row group of up to 256 query rows, wavefront w
-// carrying rows 32 w .. 32 w + 31 (one MFMA row tile).  A tile (16 KB: 8 K + 8 V
-// operand vectors per lane) is fetched from HBM once per workgroup: each
-// wavefront requests an eighth of it (two vectors per lane), FOUR tiles ahead,
-// into a ring of registers, so a compute unit keeps about 48 KB in flight.  The
-// tile is written to LDS in operand order -- the vector a lane will feed to the
-// MFMA sits at [instruction][lane], so reads are 16 bytes per lane at
-// consecutive addresses, free of bank conflicts -- into one of two buffers:
-// tile t+1 is written while tile t is being multiplied, one barrier per tile.
-
+// A workgroup of eight wavefronts (two per SIMD) is the worker.  A tile (16 KB: 8 K + 8 V
+// operand vectors per lane) is fetched from HBM once per workgroup, each wavefront requesting
+// an eighth of it, straight into LDS in operand order -- the vector a lane will feed to the
+// MFMA sits at [instruction][lane], so reads are 16 bytes per lane at consecutive addresses,
+// free of bank conflicts.
+//   class 2 (more than 64 rows): row groups of up to 256 rows, wavefront w carries rows
+//     32 w .. 32 w + 31; one tile per iteration and barrier; the score product of the next
+//     tile is woven into the softmax of the current one (staged_segment).
+//   class 1 (33 .. 64 rows): row tile = w % 4 (tiles 0 and 1 have rows), key group = w / 4;
+//     two tiles per iteration, one per key group; the two states of a row tile are folded
+//     through LDS at the end of the segment (grouped_segment).
 // K/V tiles travel HBM -> LDS without passing through registers (global_load_lds, 16 bytes a
 // lane).  A stage holds one 32-key tile in operand order: eight K vectors (k steps) then
 // eight V vectors (cache block kk, d tile jt at 4 kk + jt), 64 lanes x 16 bytes each;
@@ -1151,7 +1047,189 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
   if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane);
 }
 
-__device__ inline void large_worker(const MainArgs& a, int64_t w, ClassPlan& cp, bf16x8* lds /* 128 KB: kStages tiles */) {
+// One staged tile against this wavefront's 32 rows, nothing woven in: all 16 operand reads
+// are issued up front, the counts of the waits follow that order.
+__device__ inline void plain_tile(floatx16 (&o)[4], float& m, float& l, const bf16x8 (&q)[8], uint32_t k_addr,
+                                  uint32_t v_addr, float c, int n_valid, int h) {
+  bf16x8 kop[8], vop[8];
+  lds_read_half(kop, k_addr, 0);
+  lds_read_half(kop, k_addr, 1);
+  lds_read_half(vop, v_addr, 0);
+  lds_read_half(vop, v_addr, 1);
+  floatx16 s = (floatx16)(0.f);
+#define SMART_SCORE_STEP(I, N) \
+  SMART_LDS_WAIT(kop[I], N);   \
+  s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[I], q[I], s, 0, 0, 0);
+  SMART_SCORE_STEP(0, 15)
+  SMART_SCORE_STEP(1, 14)
+  SMART_SCORE_STEP(2, 13)
+  SMART_SCORE_STEP(3, 12)
+  SMART_SCORE_STEP(4, 11)
+  SMART_SCORE_STEP(5, 10)
+  SMART_SCORE_STEP(6, 9)
+  SMART_SCORE_STEP(7, 8)
+#undef SMART_SCORE_STEP
+  if (n_valid < kTile) mask_scores(s, n_valid, h);
+  bf16x8 pb0, pb1;
+  softmax_tile(s, m, l, o, pb0, pb1, c);
+#define SMART_OUTPUT_STEP(I, N, PB) \
+  SMART_LDS_WAIT(vop[I], N);        \
+  o[I & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[I], PB, o[I & 3], 0, 0, 0);
+  SMART_OUTPUT_STEP(0, 7, pb0)
+  SMART_OUTPUT_STEP(1, 6, pb0)
+  SMART_OUTPUT_STEP(2, 5, pb0)
+  SMART_OUTPUT_STEP(3, 4, pb0)
+  SMART_OUTPUT_STEP(4, 3, pb1)
+  SMART_OUTPUT_STEP(5, 2, pb1)
+  SMART_OUTPUT_STEP(6, 1, pb1)
+  SMART_OUTPUT_STEP(7, 0, pb1)
+#undef SMART_OUTPUT_STEP
+}
+
+// The states of a grouped segment (R row tiles x K = 8 / R key groups, wavefront = key group *
+// R + row tile) become one partial: all eight states go to LDS, and after one barrier
+// wavefront w merges, for row tile w % R, accumulator registers [(w / R) 64 / K, ...) of
+// that row tile's K states (always in key-group order) and stores that slice.
+template <int R>
+__device__ inline void fold_groups(const SmallState& S, float* lds, float* slot, int rows_in_slot, int wv, int lane,
+                                   float c) {
+  constexpr int K = kWgWaves / R, kRegs = 64 / K;
+  const int h = lane >> 5, j = lane & 31;
+  state_to_lds(S, lds + wv * kStateFloats, lane);
+  __syncthreads();
+  const int rt = wv % R, part_index = wv / R;
+  float mk[K], lk[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const float* src = lds + (k * R + rt) * kStateFloats;
+    mk[k] = src[64 * kWave + lane];
+    lk[k] = src[65 * kWave + lane];
+  }
+  floatx4 part[K][kRegs / 4];
+#pragma unroll
+  for (int k = 0; k < K; ++k)
+#pragma unroll
+    for (int u = 0; u < kRegs / 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        part[k][u][i] = lds[(k * R + rt) * kStateFloats + (part_index * kRegs + 4 * u + i) * kWave + lane];
+  float m_new = mk[0];
+#pragma unroll
+  for (int k = 1; k < K; ++k) m_new = fmaxf(m_new, mk[k]);
+  float l_new = 0.f;
+  floatx4 x[kRegs / 4];
+#pragma unroll
+  for (int u = 0; u < kRegs / 4; ++u) x[u] = (floatx4)(0.f);
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    // an empty state has max -inf and contributes nothing
+    const float sc = mk[k] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mk[k] - m_new) * c);
+    l_new += lk[k] * sc;
+#pragma unroll
+    for (int u = 0; u < kRegs / 4; ++u) x[u] += part[k][u] * sc;
+  }
+  // accumulator register 16 jt + 4 r4 + i of lane (h, j) is row j, head dims 4 (8 jt + 2 r4 + h) + i
+  const bool in_slot = rt * 32 < rows_in_slot;  // a 64-row slot has no room for row tiles 2 and 3 (they hold no rows)
+#pragma unroll
+  for (int u = 0; u < kRegs / 4; ++u) {
+    const int reg = part_index * kRegs + 4 * u, jt = reg >> 4, r4 = (reg & 15) >> 2;
+    if (in_slot) *(floatx4*)(slot + ((size_t)(rt * 32 + jt * 8 + 2 * r4 + h) * 32 + j) * 4) = x[u];
+  }
+  if (part_index == 0) {
+    const float lsum = sum_across_halves(l_new);
+    if (h == 0 && in_slot) {
+      slot[rows_in_slot * kD + rt * 32 + j] = m_new;
+      slot[rows_in_slot * kD + rows_in_slot + rt * 32 + j] = lsum;
+    }
+  }
+  __syncthreads();  // the next segment reuses the LDS
+}
+
+// Segments of at most 32 R rows (R = 2 or 4): the eight wavefronts are R row tiles x K = 8 / R
+// key groups, and an iteration consumes K tiles at once (key group kg takes tile kg of the
+// iteration), so that the stream, not the per-tile arithmetic of one wavefront, sets the pace.
+// Tiles are staged as in staged_segment (every wavefront fetches an eighth of every tile); the
+// iterations 8 / K - 1 ahead of the one being consumed are in flight.
+template <int R>
+__device__ inline void grouped_segment(const MainArgs& a, int b, int g, int base, int t0, int t1, const SeqInfo si,
+                                       float* slot, int rows_in_slot, int wv, int lane, bf16x8* lds) {
+  constexpr int K = kWgWaves / R;
+  constexpr int kAhead = kStages / K - 1;
+  const int rt = wv % R, kg = wv / R;
+  const int h = lane >> 5, j = lane & 31;
+  const int M = si.n * a.G;
+  const bool has_rows = rt * 32 < M;
+  SmallState S;
+  bf16x8 q[8];
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) S.o[jt] = (floatx16)(0.f);
+  S.m = -INFINITY;
+  S.l = 0.f;
+  if (has_rows) {
+    int rho = rt * 32 + j;
+    rho = rho < M ? rho : M - 1;  // padding rows repeat the last real row; never read back
+    const int node = base + rho / a.G, head = g * a.G + rho % a.G;
+    const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) q[ks] = *(const bf16x8*)(qp + ks * 16);
+    asm volatile("" ::"v"(q[0]), "v"(q[7]));  // landed: the counted waits below see tile fetches only
+  }
+  const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
+  const int n_blocks = (si.len + kBlock - 1) / kBlock;
+  const float c = a.scale_log2e;
+  const FetchLane f = fetch_lane(a, wv, lane);
+  const uint32_t rd = lds_address(lds + lane);
+  const int last = t1 - 1;
+  auto stage_of = [&](int t) { return lds + (t & (kStages - 1)) * kStageVecs; };
+  auto block_id = [&](int t, int which) { return sload(bt_row + min(2 * min(t, last) + which, n_blocks - 1)); };
+  auto land = [&](int t) {
+    const int n_valid = si.len - t * kTile;
+    if (t <= last && n_valid < kTile) zero_invalid_v_lds(stage_of(t), wv, lane, n_valid);
+  };
+
+  __builtin_amdgcn_s_barrier();  // the previous segment is done with the LDS
+#pragma unroll
+  for (int i = 0; i < kAhead * K; ++i)  // past the end: the last tile again (L2 hits), never consumed
+    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv);
+  int32_t nb[K][2];
+#pragma unroll
+  for (int x = 0; x < K; ++x) {
+    nb[x][0] = block_id(t0 + kAhead * K + x, 0);
+    nb[x][1] = block_id(t0 + kAhead * K + x, 1);
+  }
+  for (int tb = t0; tb < t1; tb += K) {
+#pragma unroll
+    for (int x = 0; x < K; ++x) asm volatile("" ::"s"(nb[x][0]), "s"(nb[x][1]));  // ids are in (no wait among LDS reads)
+    // this wavefront's share of the K tiles of this iteration has landed: what may still be
+    // outstanding are the kAhead - 1 iterations after it, 2 K fetches each
+    if (K == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+#pragma unroll
+    for (int x = 0; x < K; ++x) land(tb + x);
+    // every share of this iteration's tiles is visible, and everyone is done with the previous iteration's
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int x = 0; x < K; ++x)
+      request_tile(a, f, nb[x][0], nb[x][1], g, stage_of(tb + kAhead * K + x), wv);
+#pragma unroll
+    for (int x = 0; x < K; ++x) {
+      nb[x][0] = block_id(tb + (kAhead + 1) * K + x, 0);
+      nb[x][1] = block_id(tb + (kAhead + 1) * K + x, 1);
+    }
+    const int t = tb + kg;
+    if (has_rows && t < t1) {
+      const uint32_t stage = rd + (t & (kStages - 1)) * (kStageVecs * 16);
+      plain_tile(S.o, S.m, S.l, q, stage, stage + 8 * kWave * 16, c, si.len - t * kTile, h);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no fetch of this segment may land later
+  __builtin_amdgcn_s_barrier();                      // and nobody still reads a stage: the fold reuses the LDS
+  fold_groups<R>(S, (float*)lds, slot, rows_in_slot, wv, lane, c);
+}
+
+// Worker of classes 1 and 2 (kCls): a workgroup walks the pieces of its share of the class's units.
+template <int kCls>
+__device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp, bf16x8* lds /* 132 KB: kStages tiles, or eight states */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = cp.U, W = cp.W;
   PlanWindow& win = cp.win;
@@ -1161,9 +1239,9 @@ __device__ inline void large_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
   if (u0 >= u1) return;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  int b = locate(cp, pv, a.cu_nodes, 2, a.batch, u0, lane);
+  int b = locate(cp, pv, a.cu_nodes, kCls, a.batch, u0, lane);
   while (u0 < u1 && b < a.batch) {
-    follow(cp, pv, a.cu_nodes, 2, a.batch, b, lane);
+    follow(cp, pv, a.cu_nodes, kCls, a.batch, b, lane);
     const int64_t seq_begin = window_cum_units(win, b - win.first);
     const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
     if (u0 >= seq_end) { ++b; continue; }
@@ -1176,41 +1254,19 @@ __device__ inline void large_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
     const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
     const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
     const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
-    float* slot = a.ws[2] + (size_t)(w + seg) * kLargeSlot;
-    // rows of the group are dealt to the eight wavefronts in 32-row tiles
-    const int row0 = rgi * kLargeRows + wv * 32;
-    if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
-    else staged_segment<false>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
-    u0 += nt;
-  }
-}
-
-// ---- class 1: 33 .. 64 rows: one wavefront per worker, two MFMA row tiles -----------------
-__device__ inline void medium_worker(const MainArgs& a, int64_t w, ClassPlan& cp, bf16x8* q_lds /* 16 KB of this wavefront */) {
-  const PlanView pv = plan_view(a.plan, a.batch);
-  const int64_t U = cp.U, W = cp.W;
-  PlanWindow& win = cp.win;
-  if (w >= W || U <= 0) return;
-  int64_t u0 = (w * U) / W;
-  const int64_t u1 = ((w + 1) * U) / W;
-  if (u0 >= u1) return;
-  const int lane = threadIdx.x & (kWave - 1);
-  int b = locate(cp, pv, a.cu_nodes, 1, a.batch, u0, lane);
-  while (u0 < u1 && b < a.batch) {
-    follow(cp, pv, a.cu_nodes, 1, a.batch, b, lane);
-    const int64_t seq_begin = window_cum_units(win, b - win.first);
-    const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
-    if (u0 >= seq_end) { ++b; continue; }
-    const SeqInfo si = window_info(win, b);
-    const int64_t local = u0 - seq_begin;
-    const int g = (int)(local / si.tiles);
-    const int t0 = (int)(local % si.tiles);
-    const int64_t left = u1 - u0;
-    const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
-    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + g;
-    const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
-    large_segment<2>(a, b, g, base, 0, t0, t0 + nt, si, a.ws[1] + (size_t)(w + seg) * kMediumSlot, kMediumRows, 0,
-                     lane, q_lds);
+    if (kCls == 1) {
+      // At most 64 rows: row tiles 0 and 1 of four, times two key groups.  (Two row tiles x four
+      // key groups would keep every wavefront busy but leaves only one iteration of fetches in
+      // flight; measured slower.)
+      grouped_segment<4>(a, b, g, base, t0, t0 + nt, si, a.ws[1] + (size_t)(w + seg) * kMediumSlot, kMediumRows, wv,
+                         lane, lds);
+    } else {
+      float* slot = a.ws[2] + (size_t)(w + seg) * kLargeSlot;
+      // rows of the group are dealt to the eight wavefronts in 32-row tiles
+      const int row0 = rgi * kLargeRows + wv * 32;
+      if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
+      else staged_segment<false>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
+    }
     u0 += nt;
   }
 }
@@ -1305,9 +1361,9 @@ void tva_prefix_kernel(MainArgs a) {
   if (wg < first1) {
     small_worker(a, wg, cp, (float*)lds_raw);
   } else if (wg < first2) {
-    medium_worker(a, (wg - first1) * kWgWaves + wv, cp, (bf16x8*)lds_raw + wv * (2 * 8 * kWave));
+    staged_worker<1>(a, wg - first1, cp, (bf16x8*)lds_raw);
   } else {
-    large_worker(a, wg - first2, cp, (bf16x8*)lds_raw);
+    staged_worker<2>(a, wg - first2, cp, (bf16x8*)lds_raw);
   }
 }
 
@@ -1509,7 +1565,8 @@ static int32_t prefix_workgroups(const smart_ctx* ctx) {
 static int32_t class_workers(const smart_ctx* ctx, int cls) {
   const int32_t asked = prefix_workgroups(ctx);
   const int32_t wg = asked > kClasses ? asked : kClasses;
-  return cls == 1 ? wg * kWgWaves : wg;
+  (void)cls;
+  return wg;  // a worker is a workgroup in every class
 }
 int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return prefix_workgroups(ctx); }
 

@@ -349,3 +349,25 @@ def test_two_steps_of_the_loop_through_commit(lib, oracle_attention):
     # and the committed tokens matter: without them the oracle's answer is measurably different
     stale, _ = oracle_attention.tree_attention(q2, k2, v2, i.k_cache, i.v_cache, i.block_table, prefix_len, cu2, parent2, i.scale)
     assert H.rel_err(stale, ref2) > 10 * H.TOL["bf16"] or np.abs(stale - ref2).max() > 0.05
+
+
+def test_medium_trees_every_tail_of_the_two_tile_iteration(lib, oracle_attention):
+    """Class 1 (33 .. 64 rows per kv head) consumes two tiles per iteration, one per key group,
+    with three iterations of fetches in flight: prefixes of 1 .. 12 tiles, ragged or not, with
+    9 .. 16 nodes at G = 4, hit every phase of that pipeline (short segments, odd tile counts,
+    a ragged last tile in either key group)."""
+    rng = np.random.default_rng(5)
+    lens = np.array([32, 33, 63, 64, 65, 96, 97, 128, 159, 161, 223, 224, 257, 300, 352, 383], np.int32)
+    sizes = [9 + (i % 8) for i in range(len(lens))]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([W.random_tree(n, rng, "random") for n in sizes]).astype(np.int32)
+    w = W.Workload("medium", "bf16", len(sizes), 16, 4, 128, 0, 0, seed=9)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=lens, trees=(cu, parent), seed=9)
+    check_full(lib, oracle_attention, case)
+    # the same with few workers (long shares crossing many segments) and with many (pieces of a tile or two)
+    for workers in (3, 64):
+        lib.set_option(B.SMART_OPT_TVA_WORKERS, workers)
+        try:
+            check_full(lib, oracle_attention, case)
+        finally:
+            lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
