@@ -775,7 +775,7 @@ __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
 //   class 2 (more than 64 rows): row groups of up to 256 rows, wavefront w carries rows
 //     32 w .. 32 w + 31; one tile per iteration and barrier; the score product of the next
 //     tile is woven into the softmax of the current one (staged_segment).
-//   class 1 (33 .. 64 rows): row tile = w % 4 (tiles 0 and 1 have rows), key group = w / 4;
+//   class 1 (33 .. 64 rows): row tile = w / 2 (tiles 0 and 1 have rows), key group = w % 2;
 //     two tiles per iteration, one per key group; the two states of a row tile are folded
 //     through LDS at the end of the segment (grouped_segment).
 // K/V tiles travel HBM -> LDS without passing through registers (global_load_lds, 16 bytes a
@@ -1086,9 +1086,9 @@ __device__ inline void plain_tile(floatx16 (&o)[4], float& m, float& l, const bf
 #undef SMART_OUTPUT_STEP
 }
 
-// The states of a grouped segment (R row tiles x K = 8 / R key groups, wavefront = key group *
-// R + row tile) become one partial: all eight states go to LDS, and after one barrier
-// wavefront w merges, for row tile w % R, accumulator registers [(w / R) 64 / K, ...) of
+// The states of a grouped segment (R row tiles x K = 8 / R key groups, wavefront = row tile *
+// K + key group) become one partial: all eight states go to LDS, and after one barrier
+// wavefront w merges, for row tile w / K, accumulator registers [(w % K) 64 / K, ...) of
 // that row tile's K states (always in key-group order) and stores that slice.
 template <int R>
 __device__ inline void fold_groups(const SmallState& S, float* lds, float* slot, int rows_in_slot, int wv, int lane,
@@ -1097,11 +1097,11 @@ __device__ inline void fold_groups(const SmallState& S, float* lds, float* slot,
   const int h = lane >> 5, j = lane & 31;
   state_to_lds(S, lds + wv * kStateFloats, lane);
   __syncthreads();
-  const int rt = wv % R, part_index = wv / R;
+  const int rt = wv / K, part_index = wv % K;
   float mk[K], lk[K];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const float* src = lds + (k * R + rt) * kStateFloats;
+    const float* src = lds + (rt * K + k) * kStateFloats;
     mk[k] = src[64 * kWave + lane];
     lk[k] = src[65 * kWave + lane];
   }
@@ -1112,7 +1112,7 @@ __device__ inline void fold_groups(const SmallState& S, float* lds, float* slot,
     for (int u = 0; u < kRegs / 4; ++u)
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        part[k][u][i] = lds[(k * R + rt) * kStateFloats + (part_index * kRegs + 4 * u + i) * kWave + lane];
+        part[k][u][i] = lds[(rt * K + k) * kStateFloats + (part_index * kRegs + 4 * u + i) * kWave + lane];
   float m_new = mk[0];
 #pragma unroll
   for (int k = 1; k < K; ++k) m_new = fmaxf(m_new, mk[k]);
@@ -1155,7 +1155,8 @@ __device__ inline void grouped_segment(const MainArgs& a, int b, int g, int base
                                        float* slot, int rows_in_slot, int wv, int lane, bf16x8* lds) {
   constexpr int K = kWgWaves / R;
   constexpr int kAhead = kStages / K - 1;
-  const int rt = wv % R, kg = wv / R;
+  // (row tile = wv / K: when only the first row tiles hold rows, the busy wavefronts sit on different SIMDs)
+  const int rt = wv / K, kg = wv % K;
   const int h = lane >> 5, j = lane & 31;
   const int M = si.n * a.G;
   const bool has_rows = rt * 32 < M;
