@@ -186,3 +186,23 @@ def test_device_entry_points_validate_on_the_host_first():
                 dict(cache_block_stride=1024), dict(batch=-1), dict(d_q=None), dict(d_anc_mask=None),
                 dict(d_k_cache=None), dict(kv_layout=0, cache_token_stride=64), dict(num_blocks=0)):
         assert tva(**bad) == B.SMART_EINVAL, bad
+
+
+def test_hand_worked_example_library():
+    """The same hand-worked forest through the C ABI."""
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "selection_hand_worked.json")) as f:
+        g = json.load(f)
+    fo = g["forest"]
+    cost = np.array([1.0 + n / 8.0 for n in range(9)])
+    modes = {"BEST_FIRST": B.SMART_BEST_FIRST, "LAYERWISE": B.SMART_LAYERWISE}
+    dil = {"NONE": B.SMART_DILUTION_NONE, "PATH_MEAN": B.SMART_DILUTION_PATH_MEAN}
+    for case in g["cases"]:
+        r = B.smart_select_tree(np.array([0, 6], np.int32), fo["parent"], fo["prob"], fo["token"], cost,
+                                alpha=case["alpha"], max_depth=g["max_depth"], budget=g["budget"],
+                                schedule=modes[case["schedule"]], dilution=dil[case["dilution"]])
+        assert r["cand_index"].tolist() == case["cand_index"], case["name"]
+        assert r["parent"].tolist() == case["parent"], case["name"]
+        assert r["pathprob"].tolist() == [fo["path_prob"][i] for i in case["cand_index"]]
+        assert r["L"][0] == case["L"] and r["R"][0] == case["R"], case["name"]

@@ -243,3 +243,28 @@ def test_relabelled_forest_selects_the_same_set():
     t1 = S.select_tree(par, pr, tok, cost, alpha=0.8, max_depth=6, budget=96)
     t2 = S.select_tree(par2, pr2, tok2, cost, alpha=0.8, max_depth=6, budget=96)
     assert sorted(t1.cand_index) == sorted(order[i] for i in t2.cand_index)
+
+
+def _hand_worked():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "selection_hand_worked.json")) as f:
+        return json.load(f)
+
+
+def test_hand_worked_example_oracle():
+    """Decisions, node order, L and R of a forest worked by hand from the paper's equations
+    (tests/golden/selection_hand_worked.json, all numbers dyadic: exact in binary64)."""
+    g = _hand_worked()
+    fo = g["forest"]
+    P, _ = S.path_prob_and_depth(fo["parent"], fo["prob"])
+    assert P == fo["path_prob"]
+    cost = [1.0 + n / 8.0 for n in range(9)]
+    for case in g["cases"]:
+        t = S.select_tree(fo["parent"], fo["prob"], fo["token"], cost, alpha=case["alpha"], max_depth=g["max_depth"],
+                          budget=g["budget"], schedule=getattr(S, case["schedule"]),
+                          dilution=getattr(S, "DILUTION_" + case["dilution"]))
+        assert t.cand_index == case["cand_index"], case["name"]
+        assert t.parent == case["parent"], case["name"]
+        assert t.token == [fo["token"][i] for i in case["cand_index"]]
+        assert t.L == case["L"] and t.R == case["R"], case["name"]
