@@ -244,3 +244,83 @@ def brute_force_best(cand_parent, cand_prob, cost, max_depth=8, budget=64,
         elif R == best_R:
             best_sets.append(tuple(members))
     return best_R, best_sets
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 one layer at a time (a live draft model proposes the children of
+# the previous layer's survivors, the rule prunes them, and only the survivors
+# are expanded next).
+# ---------------------------------------------------------------------------
+class LayerState:
+    """The tree built so far.  Nodes of the newest layer (the active set
+    A_{l-1} of Sec. 3.2 "Sequential Decision Formulation") are
+    ``layer_begin .. len(parent) - 1``."""
+    __slots__ = ("parent", "token", "pathprob", "layer_begin", "L_sum", "L", "R")
+
+    def __init__(self, root_token, cost):
+        self.parent = [-1]
+        self.token = [int(root_token)]
+        self.pathprob = [1.0]
+        self.layer_begin = 0
+        self.L_sum = 1.0
+        self.L = 1.0
+        self.R = 1.0 / float(cost[1])
+
+    def __len__(self):
+        return len(self.parent)
+
+
+def select_layer(state, cand_parent_node, cand_prob, cand_token, cost, dcost=None, alpha=0.8,
+                 budget=64, dilution=DILUTION_NONE):
+    """One iteration of Algorithm 1's loop over layers.
+
+    ``cand_parent_node[c]`` is the tree node (of the newest layer) that
+    candidate c extends, ``cand_prob[c]`` its conditional draft probability.
+    The terms L, n, #paths are those of the tree before this layer (frozen);
+    every candidate is tested against them; if more survive than the budget
+    leaves room for, the lowest-P ones are dropped (ties: larger index first);
+    survivors are appended in candidate order and become the next active set.
+    Returns, per candidate, its new node id or -1.  ``state.L`` and ``state.R``
+    are refreshed.
+    """
+    n = len(state)
+    C = len(cand_parent_node)
+    out_node = [-1] * C
+    P = [0.0] * C
+    for c in range(C):
+        par = int(cand_parent_node[c])
+        if not (state.layer_begin <= par < n):
+            raise ValueError("a candidate must extend a node of the newest layer")
+        pr = float(cand_prob[c])
+        if not (0.0 <= pr <= 1.0):
+            raise ValueError("probabilities lie in [0, 1]")
+        P[c] = state.pathprob[par] * pr
+    survivors = []
+    if n < budget:
+        if dilution == DILUTION_NONE:
+            L, paths = state.L_sum, 1
+        else:
+            L, paths = path_mean_L(state.parent, state.pathprob)
+        dC = _marginal_cost(cost, dcost, n)
+        cost_n = float(cost[n])
+        for c in range(C):
+            benefit = P[c] if dilution == DILUTION_NONE else P[c] / paths
+            if _rule(alpha, benefit, dC, L, cost_n):
+                survivors.append(c)
+        room = budget - n
+        if len(survivors) > room:
+            survivors = sorted(survivors, key=lambda c: (-P[c], c))[:room]
+        survivors.sort()
+    state.layer_begin = n
+    for c in survivors:
+        out_node[c] = len(state.parent)
+        state.parent.append(int(cand_parent_node[c]))
+        state.token.append(int(cand_token[c]))
+        state.pathprob.append(P[c])
+        state.L_sum = state.L_sum + P[c]
+    if dilution == DILUTION_NONE:
+        state.L = state.L_sum
+    else:
+        state.L, _ = path_mean_L(state.parent, state.pathprob)
+    state.R = state.L / float(cost[len(state)])
+    return out_node

@@ -77,3 +77,30 @@ def rel_err(out: np.ndarray, ref: np.ndarray) -> float:
 
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def drive_layers(cand_parent, max_depth, step):
+    """Feeds a complete candidate forest to a layer-at-a-time selector the way a live draft
+    model would: layer l offers the children (in candidate order) of the candidates kept in
+    layer l - 1.  ``step(cand_ids, parent_nodes) -> node id or -1 per offered candidate``.
+    Returns the candidate index of every node, in node order.  Holds no arithmetic."""
+    C = len(cand_parent)
+    children = [[] for _ in range(C)]
+    for u in range(1, C):
+        children[cand_parent[u]].append(u)
+    node_of = {0: 0}
+    cand_of_node = [0]
+    active = [0]
+    for _layer in range(max_depth):
+        offered = sorted(u for a in active for u in children[a])
+        out = step(offered, [node_of[cand_parent[u]] for u in offered])
+        kept = [u for u, nid in zip(offered, out) if nid >= 0]
+        for u, nid in zip(offered, out):
+            if nid >= 0:
+                assert nid == len(cand_of_node)
+                node_of[u] = nid
+                cand_of_node.append(u)
+        active = kept
+        if not active:
+            break
+    return cand_of_node

@@ -268,3 +268,79 @@ def test_hand_worked_example_oracle():
         assert t.parent == case["parent"], case["name"]
         assert t.token == [fo["token"][i] for i in case["cand_index"]]
         assert t.L == case["L"] and t.R == case["R"], case["name"]
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 one layer at a time
+# ---------------------------------------------------------------------------
+def _stepwise(parent, prob, token, cost, dcost=None, alpha=0.8, max_depth=8, budget=64, dilution=S.DILUTION_NONE):
+    from tests.helpers import drive_layers
+    st = S.LayerState(token[0], cost)
+    cand = drive_layers(parent, max_depth, lambda ids, par_nodes: S.select_layer(
+        st, par_nodes, [prob[u] for u in ids], [token[u] for u in ids], cost, dcost, alpha=alpha,
+        budget=budget, dilution=dilution))
+    return st, cand
+
+
+def test_hand_worked_example_layer_at_a_time():
+    """The layer-wise cases of the hand-worked forest, fed one layer at a time."""
+    g = _hand_worked()
+    fo = g["forest"]
+    cost = [1.0 + n / 8.0 for n in range(9)]
+    seen = 0
+    for case in g["cases"]:
+        if case["schedule"] != "LAYERWISE":
+            continue
+        seen += 1
+        st, cand = _stepwise(fo["parent"], fo["prob"], fo["token"], cost, alpha=case["alpha"],
+                             max_depth=g["max_depth"], budget=g["budget"],
+                             dilution=getattr(S, "DILUTION_" + case["dilution"]))
+        assert cand == case["cand_index"] and st.parent == case["parent"], case["name"]
+        assert st.token == [fo["token"][i] for i in case["cand_index"]]
+        assert st.L == case["L"] and st.R == case["R"], case["name"]
+    assert seen >= 1
+
+
+@pytest.mark.parametrize("dilution", [S.DILUTION_NONE, S.DILUTION_PATH_MEAN])
+@pytest.mark.parametrize("seed", range(8))
+def test_layer_at_a_time_equals_the_whole_forest_schedule(seed, dilution):
+    """Algorithm 1 looks at one layer per iteration, so running it on a forest known in advance
+    and on layers that arrive one by one must give the same tree, bit for bit, also when the
+    budget cuts a layer and when the depth cap ends the loop."""
+    parent, prob, token = tiny_forest(seed, k=3, d=4)
+    cost = [1.0 + 0.01 * n + 0.002 * n * n for n in range(130)]
+    dcost = [0.01 + 0.004 * n for n in range(129)] if seed % 2 else None
+    for budget, max_depth in ((128, 4), (9, 4), (4, 4), (1, 4), (40, 2)):
+        t = S.select_tree(parent, prob, token, cost, dcost, alpha=0.9, max_depth=max_depth, budget=budget,
+                          schedule=S.LAYERWISE, dilution=dilution)
+        st, cand = _stepwise(parent, prob, token, cost, dcost, alpha=0.9, max_depth=max_depth, budget=budget,
+                             dilution=dilution)
+        assert cand == t.cand_index and st.parent == t.parent and st.token == t.token
+        assert st.pathprob == t.pathprob and st.L == t.L and st.R == t.R
+
+
+def test_one_layer_against_exact_rational_arithmetic():
+    """One layer on dyadic inputs, decided again in exact fractions: the kept set is
+    {c : alpha P(c) / dC > L / cost[n]}, cut to the room the budget leaves by largest P."""
+    from fractions import Fraction as F
+    cost = [1.0 + n / 8.0 for n in range(12)]
+    st = S.LayerState(7, cost)
+    out = S.select_layer(st, [0, 0, 0, 0], [0.5, 0.25, 0.125, 0.0625], [1, 2, 3, 4], cost, alpha=0.5, budget=8)
+    # threshold L / cost[1] = 1 / 1.125 = 8/9; alpha p / 0.125 = 4 p: 2, 1, 0.5, 0.25
+    assert out == [1, 2, -1, -1] and st.L == 1.75 and st.layer_begin == 1 and len(st) == 3
+    cands = [(1, 0.5), (1, 0.5), (2, 0.75), (2, 0.25), (1, 0.125)]
+    P = [F(st.pathprob[p]) * F(q) for p, q in cands]
+    thr = F(st.L) / F(cost[3])
+    passing = [c for c in range(5) if F(1) * P[c] / (F(cost[4]) - F(cost[3])) > thr]
+    assert passing == [0, 1, 2]                                        # 2, 2, 1.5 > 14/11 > 0.5, 0.5
+    room = 2
+    expect = sorted(sorted(passing, key=lambda c: (-P[c], c))[:room])
+    out = S.select_layer(st, [p for p, _ in cands], [q for _, q in cands], [5, 6, 7, 8, 9], cost, alpha=1.0,
+                         budget=len(st) + room)
+    assert [c for c in range(5) if out[c] >= 0] == expect == [0, 1]     # P = 0.1875 goes, the tie at 0.25 stays
+    assert [out[c] for c in expect] == [3, 4] and st.layer_begin == 3
+    # a full tree accepts nothing more and has no active layer left
+    out = S.select_layer(st, [3], [1.0], [1], cost, alpha=1.0, budget=len(st))
+    assert out == [-1] and st.layer_begin == len(st) == 5
+    with pytest.raises(ValueError):
+        S.select_layer(st, [3], [1.0], [1], cost, budget=8)            # node 3 is not in the newest layer
