@@ -166,6 +166,102 @@ int32_t smart_select_tree(
     double* h_out_L, double* h_out_R);
 
 /* ---------------------------------------------------------------------------
+ * Algorithm 1 one layer at a time: smart_select_begin / smart_select_layer
+ * (host) and smart_select_begin_device / smart_select_layer_device (device)
+ *
+ * With a live draft model the candidates of layer l exist only after the
+ * survivors of layer l - 1 are known (Sec. 3.2 "Sequential Decision
+ * Formulation": U_l are the expansions of the active set A_{l-1}).  These calls
+ * run one iteration of Algorithm 1's loop per call: the caller offers, per
+ * sequence, the children of the newest layer's nodes with their conditional
+ * draft probabilities; every candidate is tested with the terms L, n, #paths
+ * of the tree before this layer (frozen); survivors beyond the budget are
+ * dropped lowest-P first (ties: larger index first); survivors are appended in
+ * candidate order and become the active set of the next call.  Feeding a
+ * forest's layers one by one gives exactly the tree, L and R that
+ * smart_select_tree with SMART_LAYERWISE gives for the whole forest.
+ * The device form is the same arithmetic in binary64 on the GPU, one wavefront
+ * per sequence, for draft probabilities that never leave the device; nothing
+ * synchronises.
+ *
+ * smart_layer_state: the trees under construction, caller-owned arrays (all
+ * host pointers for the host calls, all device pointers for the device calls;
+ * the struct itself is always read on the host).  Node arrays have `budget`
+ * entries per sequence.  path_sum may be NULL with SMART_DILUTION_NONE.
+ * smart_select_begin(_device) sets every tree to its root.
+ *
+ * smart_select_layer: h_cand_cu[batch+1] CSR offsets of this layer's
+ * candidates (a sequence may offer none); per candidate the node id (within
+ * its sequence's tree) it extends, which must be one of layer_begin .. n-1,
+ * its conditional probability in [0,1] and its token.  h_out_node[c] receives
+ * the candidate's new node id or -1.  h_cost[budget+2], h_dcost[budget+1] or
+ * NULL, alpha and dilution as for smart_select_tree (same dilution on every
+ * call of one tree).  After the call n, layer_begin (= the old n), sum_P, the
+ * node arrays, L and R = L / cost[n] are current.  A sequence whose tree is
+ * full, or whose layer keeps nothing, ends with an empty active set.
+ * Errors (host form; nothing is modified): SMART_EINVAL (null pointers, budget
+ * outside 1..SMART_MAX_NODES, alpha outside (0,1], unknown dilution, PATH_MEAN
+ * without path_sum), SMART_ETREE (offsets not ascending from 0, state
+ * inconsistent, a parent outside the newest layer, a probability outside
+ * [0,1]).
+ * Device form: cand_cap is the capacity (entries) of the candidate arrays and
+ * d_out_node; per sequence d_status[b] = SMART_OK, SMART_ETREE (as above; also
+ * offsets leaving [0, cand_cap]) or SMART_ECAP (more than
+ * SMART_MAX_LAYER_CAND candidates); a sequence with a non-zero status is left
+ * as it was and its candidates (where addressable) get -1.
+ * ------------------------------------------------------------------------- */
+#define SMART_MAX_LAYER_CAND 2048
+
+typedef struct smart_layer_state {
+  int32_t batch;
+  int32_t budget;       /* nodes a tree may hold, root included (1 .. SMART_MAX_NODES) */
+  int32_t* n;           /* [batch] nodes so far                                          */
+  int32_t* layer_begin; /* [batch] first node of the newest layer (active set: .. n-1)  */
+  double* sum_P;        /* [batch] sum of P over the nodes, in node order                */
+  int32_t* parent;      /* [batch * budget] local parent node id, -1 for the root        */
+  int32_t* token;       /* [batch * budget]                                              */
+  double* pathprob;     /* [batch * budget] P(u), Eq. "cum_prob"                         */
+  double* path_sum;     /* [batch * budget] sum of P from the root down to the node      */
+  double* L;            /* [batch] expected acceptance length of the current tree        */
+  double* R;            /* [batch] L / cost[n]                                           */
+} smart_layer_state;
+
+int32_t smart_select_begin(const smart_layer_state* h_state, const int32_t* h_root_token,
+                           const double* h_cost);
+int32_t smart_select_layer(const smart_layer_state* h_state, const int32_t* h_cand_cu,
+                           const int32_t* h_cand_parent_node, const double* h_cand_prob,
+                           const int32_t* h_cand_token, const double* h_cost, const double* h_dcost,
+                           double alpha, int32_t dilution, int32_t* h_out_node);
+int32_t smart_select_begin_device(smart_ctx* ctx, void* stream, const smart_layer_state* d_state,
+                                  const int32_t* d_root_token, const double* d_cost);
+int32_t smart_select_layer_device(smart_ctx* ctx, void* stream, const smart_layer_state* d_state,
+                                  const int32_t* d_cand_cu, const int32_t* d_cand_parent_node,
+                                  const double* d_cand_prob, const int32_t* d_cand_token,
+                                  int64_t cand_cap, const double* d_cost, const double* d_dcost,
+                                  double alpha, int32_t dilution, int32_t* d_out_node,
+                                  int32_t* d_status);
+
+/* ---------------------------------------------------------------------------
+ * tree_compact_pack (device)
+ *
+ * Turns the trees of a smart_layer_state (device pointers) into what the rest
+ * of the step takes, in one launch and without the host learning the sizes:
+ * d_cu_nodes[batch+1] (running sum of n), d_parent and d_token in CSR order,
+ * and the outputs of tree_pack.  total_cap, the capacity (nodes) of the
+ * per-node outputs, must be at least batch * budget; the number of nodes
+ * actually written is d_cu_nodes[batch].  tree_verify_attention
+ * may then be called with total_nodes = total_cap (see there).
+ * d_status as for tree_pack (a sequence with n outside 1 .. budget counts as
+ * malformed and contributes no nodes).
+ * Host errors: SMART_EINVAL (null pointers, total_cap < batch * budget).
+ * ------------------------------------------------------------------------- */
+int32_t tree_compact_pack(smart_ctx* ctx, void* stream, const smart_layer_state* d_state,
+                          int32_t total_cap, const int32_t* d_prefix_len, int32_t* d_cu_nodes,
+                          int32_t* d_parent, int32_t* d_token, int32_t* d_depth,
+                          int32_t* d_position, int32_t* d_node_seq, uint64_t* d_anc_mask,
+                          int32_t* d_status);
+
+/* ---------------------------------------------------------------------------
  * smart_cost_tables, smart_fit_cost_models (host)
  *
  * The device cost models of Sec. 3.1 ("Cost Modeling"), biases fixed to zero as
@@ -292,6 +388,9 @@ int32_t kv_cache_write(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_l
  * (entries past a sequence's prefix are never read; read entries are clamped
  * to [0, num_blocks)); prefix_len is clamped to
  * [0, max_blocks_per_seq * block_size]; anc_mask as written by tree_pack.
+ * total_nodes may exceed d_cu_nodes[batch] (a capacity, when only the device
+ * knows the trees' sizes: see tree_compact_pack): rows from d_cu_nodes[batch]
+ * on are then either left untouched or zero-filled, never read.
  * Host errors: SMART_EINVAL for null pointers, Hq % Hkv != 0, G > 16,
  * head_dim not in {64, 128}, block_size not a multiple of 8 or > 64,
  * unknown dtype / layout, strides smaller than a page; SMART_ENOMEM / SMART_EHIP.

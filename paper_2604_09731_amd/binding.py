@@ -23,9 +23,11 @@ SMART_DILUTION_NONE, SMART_DILUTION_PATH_MEAN = 0, 1
 SMART_OPT_TVA_WORKERS, SMART_OPT_TVA_FORCE_GENERAL, SMART_OPT_TVA_PROFILE = 1, 2, 3
 SMART_OPT_TVA_PROFILE_STRIDE = 4
 SMART_MAX_NODES = 128
+SMART_MAX_LAYER_CAND = 2048
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
-           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
+           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_begin", "smart_select_layer",
+           "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
 
@@ -56,6 +58,17 @@ class TvaParams(ctypes.Structure):
     ]
 
 
+class LayerStateStruct(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("budget", ctypes.c_int32),
+                ("n", ctypes.c_void_p), ("layer_begin", ctypes.c_void_p), ("sum_P", ctypes.c_void_p),
+                ("parent", ctypes.c_void_p), ("token", ctypes.c_void_p), ("pathprob", ctypes.c_void_p),
+                ("path_sum", ctypes.c_void_p), ("L", ctypes.c_void_p), ("R", ctypes.c_void_p)]
+
+
+_STATE_FIELDS = (("n", "i4", False), ("layer_begin", "i4", False), ("sum_P", "f8", False),
+                 ("parent", "i4", True), ("token", "i4", True), ("pathprob", "f8", True),
+                 ("path_sum", "f8", True), ("L", "f8", False), ("R", "f8", False))
+
 _libh = None
 
 
@@ -83,6 +96,17 @@ def _lib():
         lib.smart_select_tree.restype = i32
         lib.smart_select_tree.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, i32, i32,
                                           vp, vp, vp, vp, vp, i64, vp, vp]
+        sp = ctypes.POINTER(LayerStateStruct)
+        lib.smart_select_begin.restype = i32
+        lib.smart_select_begin.argtypes = [sp, vp, vp]
+        lib.smart_select_layer.restype = i32
+        lib.smart_select_layer.argtypes = [sp, vp, vp, vp, vp, vp, vp, f64, i32, vp]
+        lib.smart_select_begin_device.restype = i32
+        lib.smart_select_begin_device.argtypes = [vp, vp, sp, vp, vp]
+        lib.smart_select_layer_device.restype = i32
+        lib.smart_select_layer_device.argtypes = [vp, vp, sp, vp, vp, vp, vp, i64, vp, vp, f64, i32, vp, vp]
+        lib.tree_compact_pack.restype = i32
+        lib.tree_compact_pack.argtypes = [vp, vp, sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.smart_cost_tables.restype = i32
         lib.smart_cost_tables.argtypes = [f64, f64, f64, f64, f64, f64, i32, vp, vp]
         lib.smart_fit_cost_models.restype = i32
@@ -152,6 +176,69 @@ def smart_select_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, dcost=N
     n = int(o_cu[-1])
     return dict(cu_nodes=o_cu, parent=o_parent[:n], token=o_token[:n], cand_index=o_cand[:n],
                 pathprob=o_pp[:n], L=o_L[:batch], R=o_R[:batch])
+
+
+class HostLayerState:
+    """Trees under construction by Algorithm 1 one layer at a time, in host (numpy) arrays."""
+
+    def __init__(self, batch: int, budget: int, path_sum: bool = True):
+        self.batch, self.budget = int(batch), int(budget)
+        self.struct = LayerStateStruct(batch=self.batch, budget=self.budget)
+        for name, kind, per_node in _STATE_FIELDS:
+            if name == "path_sum" and not path_sum:
+                arr = None
+            else:
+                arr = np.zeros(max(1, self.batch * (self.budget if per_node else 1)), np.dtype(kind))
+            setattr(self, name, arr)
+            setattr(self.struct, name, arr.ctypes.data if arr is not None else None)
+
+    def begin(self, root_token, cost):
+        root_token = np.ascontiguousarray(root_token, np.int32)
+        cost = np.ascontiguousarray(cost, np.float64)
+        assert root_token.shape[0] == self.batch and cost.shape[0] >= self.budget + 2
+        rc = _lib().smart_select_begin(ctypes.byref(self.struct), root_token.ctypes.data, cost.ctypes.data)
+        _check(rc, "smart_select_begin")
+
+    def layer(self, cand_cu, cand_parent_node, cand_prob, cand_token, cost, dcost=None, alpha=0.8,
+              dilution=SMART_DILUTION_NONE):
+        """Offers one layer of candidates; returns the node id (or -1) of each."""
+        cand_cu = np.ascontiguousarray(cand_cu, np.int32)
+        cand_parent_node = np.ascontiguousarray(cand_parent_node, np.int32)
+        cand_prob = np.ascontiguousarray(cand_prob, np.float64)
+        cand_token = np.ascontiguousarray(cand_token, np.int32)
+        cost = np.ascontiguousarray(cost, np.float64)
+        assert cand_cu.shape[0] == self.batch + 1 and cost.shape[0] >= self.budget + 2
+        if dcost is not None:
+            dcost = np.ascontiguousarray(dcost, np.float64)
+            assert dcost.shape[0] >= self.budget + 1
+        out = np.full(max(1, cand_parent_node.shape[0]), -1, np.int32)
+        p = lambda a: ctypes.c_void_p(a.ctypes.data) if a is not None else None
+        rc = _lib().smart_select_layer(ctypes.byref(self.struct), p(cand_cu), p(cand_parent_node), p(cand_prob),
+                                       p(cand_token), p(cost), p(dcost), float(alpha), int(dilution), p(out))
+        _check(rc, "smart_select_layer")
+        return out[:cand_parent_node.shape[0]]
+
+    def tree(self, b: int):
+        """(parent, token, pathprob) lists of sequence b."""
+        n, o = int(self.n[b]), b * self.budget
+        return self.parent[o:o + n].tolist(), self.token[o:o + n].tolist(), self.pathprob[o:o + n].tolist()
+
+
+class DeviceLayerState:
+    """The same state in device (torch) tensors."""
+
+    def __init__(self, batch: int, budget: int, device, path_sum: bool = True):
+        torch = _torch()
+        self.batch, self.budget = int(batch), int(budget)
+        self.struct = LayerStateStruct(batch=self.batch, budget=self.budget)
+        for name, kind, per_node in _STATE_FIELDS:
+            if name == "path_sum" and not path_sum:
+                t = None
+            else:
+                t = torch.zeros(max(1, self.batch * (self.budget if per_node else 1)),
+                                dtype=torch.int32 if kind == "i4" else torch.float64, device=device)
+            setattr(self, name, t)
+            setattr(self.struct, name, t.data_ptr() if t is not None else None)
 
 
 def smart_cost_tables(lam, gamma, delta, rho, c_T, tokens_per_node, n_max, want_dcost=True):
@@ -284,6 +371,45 @@ class SmartTree:
                                      _ptr(depth), _ptr(position), _ptr(node_seq), _ptr(anc_mask), _ptr(status))
         _check(rc, "tree_upload_pack")
         return cu, par, tok, depth, position, node_seq, anc_mask, status
+
+    # -- Algorithm 1 one layer at a time, on the device ---------------------
+    def select_begin(self, state: DeviceLayerState, root_token, cost):
+        rc = _lib().smart_select_begin_device(self._h, _stream_ptr(), ctypes.byref(state.struct), _ptr(root_token),
+                                              _ptr(cost))
+        _check(rc, "smart_select_begin_device")
+
+    def select_layer(self, state: DeviceLayerState, cand_cu, cand_parent_node, cand_prob, cand_token, cost,
+                     dcost=None, alpha=0.8, dilution=SMART_DILUTION_NONE, out_node=None, status=None):
+        """Device tensors in, (out_node, status) device tensors out; nothing synchronises."""
+        torch = _torch()
+        cap = cand_parent_node.shape[0]
+        if out_node is None:
+            out_node = torch.empty(max(1, cap), dtype=torch.int32, device=cand_cu.device)
+        if status is None:
+            status = torch.empty(max(1, state.batch), dtype=torch.int32, device=cand_cu.device)
+        rc = _lib().smart_select_layer_device(self._h, _stream_ptr(), ctypes.byref(state.struct), _ptr(cand_cu),
+                                              _ptr(cand_parent_node), _ptr(cand_prob), _ptr(cand_token), cap,
+                                              _ptr(cost), _ptr(dcost), float(alpha), int(dilution), _ptr(out_node),
+                                              _ptr(status))
+        _check(rc, "smart_select_layer_device")
+        return out_node[:cap], status[:state.batch]
+
+    def tree_compact_pack(self, state: DeviceLayerState, prefix_len, total_cap=None):
+        """Returns (cu_nodes, parent, token, depth, position, node_seq, anc_mask, status); the per-node
+        tensors have total_cap rows of which cu_nodes[-1] are in use."""
+        torch = _torch()
+        B = state.batch
+        N = int(total_cap if total_cap is not None else B * state.budget)
+        dev = prefix_len.device
+        i32 = lambda n: torch.zeros(max(1, n), dtype=torch.int32, device=dev)
+        cu, par, tok = i32(B + 1), i32(N), i32(N)
+        depth, position, node_seq, status = i32(N), i32(N), i32(N), i32(B)
+        anc_mask = torch.zeros((max(1, N), 2), dtype=torch.int64, device=dev)
+        rc = _lib().tree_compact_pack(self._h, _stream_ptr(), ctypes.byref(state.struct), N, _ptr(prefix_len),
+                                      _ptr(cu), _ptr(par), _ptr(tok), _ptr(depth), _ptr(position), _ptr(node_seq),
+                                      _ptr(anc_mask), _ptr(status))
+        _check(rc, "tree_compact_pack")
+        return cu, par[:N], tok[:N], depth[:N], position[:N], node_seq[:N], anc_mask[:N], status[:B]
 
     # -- tree_pack ---------------------------------------------------------
     def tree_pack(self, cu_nodes, parent, prefix_len):

@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libsmart_tree.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 HIP_SOURCES = ["smart_ctx.hip", "tree_pack_accept.hip", "kv_cache_write.hip", "tva_general.hip",
-               "tva_mfma.hip", "tva_api.hip"]
+               "tva_mfma.hip", "tva_api.hip", "smart_select_device.hip"]
 HOST_SOURCES = ["smart_select.cpp", "smart_cost_model.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -21,6 +21,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUD
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-function"]
 # selection decisions must be bit-identical everywhere: no FMA contraction
+HIP_EXTRA = {"smart_select_device.hip": ["-ffp-contract=off"]}
 HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-I", INCLUDE, "-Wall", "-pthread"]
 
 
@@ -39,7 +40,7 @@ def build_library(verbose: bool = False) -> str:
     objs = []
     for s in HIP_SOURCES:
         o = os.path.join(OBJ_DIR, s + ".o")
-        _run([HIPCC, *HIP_FLAGS, "-c", os.path.join(CSRC, s), "-o", o])
+        _run([HIPCC, *HIP_FLAGS, *HIP_EXTRA.get(s, []), "-c", os.path.join(CSRC, s), "-o", o])
         objs.append(o)
     for s in HOST_SOURCES:
         o = os.path.join(OBJ_DIR, s + ".o")

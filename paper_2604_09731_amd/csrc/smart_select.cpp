@@ -376,3 +376,133 @@ extern "C" int32_t smart_select_tree(
   }
   return SMART_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Algorithm 1 one layer per call (the candidates of a layer exist only once the
+// previous layer's survivors are known).
+// ---------------------------------------------------------------------------
+namespace {
+
+bool layer_state_ok(const smart_layer_state* s, int32_t dilution) {
+  if (!s || s->batch < 0 || s->budget < 1 || s->budget > SMART_MAX_NODES) return false;
+  if (s->batch > 0 && (!s->n || !s->layer_begin || !s->sum_P || !s->parent || !s->token || !s->pathprob ||
+                       !s->L || !s->R))
+    return false;
+  if (dilution == SMART_DILUTION_PATH_MEAN && s->batch > 0 && !s->path_sum) return false;
+  return true;
+}
+
+// Eq. "expected_acc_length" of the first n nodes of one tree: leaves in increasing node id,
+// each contributing the sum of P from the root down to it.
+void path_mean(const int32_t* parent, const double* path_sum, int n, double* L, double* paths) {
+  bool has_child[SMART_MAX_NODES] = {};
+  for (int i = 1; i < n; ++i) has_child[parent[i]] = true;
+  double total = 0.0;
+  int leaves = 0;
+  for (int i = 0; i < n; ++i)
+    if (!has_child[i]) {
+      total = total + path_sum[i];
+      ++leaves;
+    }
+  *L = total / (double)leaves;
+  *paths = (double)leaves;
+}
+
+}  // namespace
+
+extern "C" int32_t smart_select_begin(const smart_layer_state* s, const int32_t* h_root_token,
+                                      const double* h_cost) {
+  if (!layer_state_ok(s, SMART_DILUTION_NONE) || !h_cost) return SMART_EINVAL;
+  if (s->batch > 0 && !h_root_token) return SMART_EINVAL;
+  for (int b = 0; b < s->batch; ++b) {
+    const size_t o = (size_t)b * s->budget;
+    s->n[b] = 1;
+    s->layer_begin[b] = 0;
+    s->sum_P[b] = 1.0;
+    s->parent[o] = -1;
+    s->token[o] = h_root_token[b];
+    s->pathprob[o] = 1.0;
+    if (s->path_sum) s->path_sum[o] = 0.0 + 1.0;
+    s->L[b] = 1.0;
+    s->R[b] = 1.0 / h_cost[1];
+  }
+  return SMART_OK;
+}
+
+extern "C" int32_t smart_select_layer(const smart_layer_state* s, const int32_t* h_cand_cu,
+                                      const int32_t* h_cand_parent_node, const double* h_cand_prob,
+                                      const int32_t* h_cand_token, const double* h_cost,
+                                      const double* h_dcost, double alpha, int32_t dilution,
+                                      int32_t* h_out_node) {
+  if (dilution != SMART_DILUTION_NONE && dilution != SMART_DILUTION_PATH_MEAN) return SMART_EINVAL;
+  if (!layer_state_ok(s, dilution) || !h_cand_cu || !h_cost || !(alpha > 0.0 && alpha <= 1.0)) return SMART_EINVAL;
+  const int batch = s->batch, budget = s->budget;
+  if (h_cand_cu[0] != 0) return SMART_ETREE;
+  for (int b = 0; b < batch; ++b)
+    if (h_cand_cu[b + 1] < h_cand_cu[b]) return SMART_ETREE;
+  const int64_t total = h_cand_cu[batch];
+  if (total > 0 && (!h_cand_parent_node || !h_cand_prob || !h_cand_token || !h_out_node)) return SMART_EINVAL;
+  // everything is checked before anything changes
+  for (int b = 0; b < batch; ++b) {
+    const int n = s->n[b], lb = s->layer_begin[b];
+    if (n < 1 || n > budget || lb < 0 || lb > n) return SMART_ETREE;
+    for (int c = h_cand_cu[b]; c < h_cand_cu[b + 1]; ++c) {
+      const int p = h_cand_parent_node[c];
+      const double pr = h_cand_prob[c];
+      if (p < lb || p >= n || !(pr >= 0.0 && pr <= 1.0)) return SMART_ETREE;
+    }
+  }
+  static thread_local std::vector<double> P;
+  static thread_local std::vector<int32_t> survivors;
+  for (int b = 0; b < batch; ++b) {
+    const size_t o = (size_t)b * budget;
+    int32_t* parent = s->parent + o;
+    double* pathprob = s->pathprob + o;
+    double* path_sum = s->path_sum ? s->path_sum + o : nullptr;
+    const int lo = h_cand_cu[b], C = h_cand_cu[b + 1] - lo;
+    const int n = s->n[b];
+    P.resize(C);
+    survivors.clear();
+    for (int c = 0; c < C; ++c) {
+      P[c] = pathprob[h_cand_parent_node[lo + c]] * h_cand_prob[lo + c];
+      h_out_node[lo + c] = -1;
+    }
+    if (n < budget) {
+      double L = s->sum_P[b], paths = 1.0;
+      if (dilution == SMART_DILUTION_PATH_MEAN) path_mean(parent, path_sum, n, &L, &paths);
+      const double dC = h_dcost ? h_dcost[n] : h_cost[n + 1] - h_cost[n];
+      const double cost_n = h_cost[n];
+      for (int c = 0; c < C; ++c) {
+        const double benefit = dilution == SMART_DILUTION_NONE ? P[c] : P[c] / paths;
+        if (keep(alpha, benefit, dC, L, cost_n)) survivors.push_back(c);
+      }
+      const int room = budget - n;
+      if ((int)survivors.size() > room) {
+        std::sort(survivors.begin(), survivors.end(),
+                  [&](int x, int y) { return P[x] > P[y] || (P[x] == P[y] && x < y); });
+        survivors.resize(room);
+        std::sort(survivors.begin(), survivors.end());
+      }
+    }
+    int node = n;
+    double sum_P = s->sum_P[b];
+    for (int c : survivors) {
+      const int p = h_cand_parent_node[lo + c];
+      parent[node] = p;
+      s->token[o + node] = h_cand_token[lo + c];
+      pathprob[node] = P[c];
+      if (path_sum) path_sum[node] = path_sum[p] + P[c];
+      sum_P = sum_P + P[c];
+      h_out_node[lo + c] = node;
+      ++node;
+    }
+    s->layer_begin[b] = n;
+    s->n[b] = node;
+    s->sum_P[b] = sum_P;
+    double L = sum_P, paths = 1.0;
+    if (dilution == SMART_DILUTION_PATH_MEAN) path_mean(parent, path_sum, node, &L, &paths);
+    s->L[b] = L;
+    s->R[b] = L / h_cost[node];
+  }
+  return SMART_OK;
+}

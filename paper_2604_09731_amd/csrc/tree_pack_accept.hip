@@ -101,6 +101,47 @@ __global__ __launch_bounds__(kWave) void tree_upload_pack_kernel(
   pack_sequence(b, lane, base, n, len, [&](int i) { return par[i]; }, depth, position, node_seq, anc_mask, status);
 }
 
+// The trees of a layer-at-a-time selection (`stride` entries per sequence, n[b] of them used)
+// into CSR order, packed in the same launch.  Every wavefront sums the sizes before its own
+// sequence itself: batches are small and this saves a scan kernel.
+__global__ __launch_bounds__(kWave) void tree_compact_pack_kernel(
+    int batch, int stride, const int32_t* __restrict__ n_of, const int32_t* __restrict__ s_parent,
+    const int32_t* __restrict__ s_token, int32_t* __restrict__ cu_nodes, int32_t* __restrict__ parent,
+    int32_t* __restrict__ token, const int32_t* __restrict__ prefix_len, int32_t* __restrict__ depth,
+    int32_t* __restrict__ position, int32_t* __restrict__ node_seq, uint64_t* __restrict__ anc_mask,
+    int32_t* __restrict__ status) {
+  __shared__ int32_t par[SMART_MAX_NODES];
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (b >= batch) return;
+  auto nodes_of = [&](int i) {
+    const int n = n_of[i];
+    return (n >= 1 && n <= stride) ? n : 0;
+  };
+  int before = 0;
+  for (int i = lane; i < b; i += kWave) before += nodes_of(i);
+  for (int sh = 32; sh >= 1; sh >>= 1) before += __shfl_xor(before, sh);
+  const int base = before;
+  const int n = nodes_of(b);
+  if (lane == 0) {
+    cu_nodes[b] = base;
+    if (b == batch - 1) cu_nodes[batch] = base + n;
+  }
+  if (n == 0) {
+    if (lane == 0) status[b] = SMART_ETREE;
+    return;
+  }
+  for (int i = lane; i < n; i += kWave) {
+    const int p = s_parent[(size_t)b * stride + i];
+    parent[base + i] = p;
+    par[i] = p;
+    token[base + i] = s_token[(size_t)b * stride + i];
+  }
+  __syncthreads();
+  pack_sequence(b, lane, base, n, prefix_len[b], [&](int i) { return par[i]; }, depth, position, node_seq,
+                anc_mask, status);
+}
+
 __global__ __launch_bounds__(kWave) void tree_accept_kernel(
     int batch, int max_depth, const int32_t* __restrict__ cu_nodes,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ token,
@@ -203,6 +244,27 @@ extern "C" int32_t tree_upload_pack(smart_ctx* ctx, void* stream, int32_t batch,
   hipLaunchKernelGGL(tree_upload_pack_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch,
                      total_nodes, h_pinned_cu_nodes, h_pinned_parent, h_pinned_token, d_cu_nodes, d_parent,
                      d_token, d_prefix_len, d_depth, d_position, d_node_seq, d_anc_mask, d_status);
+  SMART_HIP_CHECK(hipGetLastError());
+  return SMART_OK;
+}
+
+extern "C" int32_t tree_compact_pack(smart_ctx* ctx, void* stream, const smart_layer_state* d_state,
+                                     int32_t total_cap, const int32_t* d_prefix_len, int32_t* d_cu_nodes,
+                                     int32_t* d_parent, int32_t* d_token, int32_t* d_depth,
+                                     int32_t* d_position, int32_t* d_node_seq, uint64_t* d_anc_mask,
+                                     int32_t* d_status) {
+  if (!ctx || !d_state || d_state->batch < 0 || d_state->budget < 1 || d_state->budget > SMART_MAX_NODES)
+    return SMART_EINVAL;
+  if (!d_cu_nodes || !d_prefix_len || !d_status) return SMART_EINVAL;
+  const int32_t batch = d_state->batch;
+  if (total_cap < 0 || (int64_t)total_cap < (int64_t)batch * d_state->budget) return SMART_EINVAL;
+  if (batch == 0) return SMART_OK;
+  if (!d_state->n || !d_state->parent || !d_state->token || !d_parent || !d_token || !d_depth || !d_position ||
+      !d_node_seq || !d_anc_mask)
+    return SMART_EINVAL;
+  hipLaunchKernelGGL(tree_compact_pack_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch,
+                     d_state->budget, d_state->n, d_state->parent, d_state->token, d_cu_nodes, d_parent, d_token,
+                     d_prefix_len, d_depth, d_position, d_node_seq, d_anc_mask, d_status);
   SMART_HIP_CHECK(hipGetLastError());
   return SMART_OK;
 }

@@ -104,3 +104,39 @@ def drive_layers(cand_parent, max_depth, step):
         if not active:
             break
     return cand_of_node
+
+
+def drive_layers_batch(cand_parents, max_depth, step):
+    """The batched form of drive_layers: every sequence advances one layer per call of
+    ``step(cand_cu, parent_nodes, offered) -> flat node ids``, where ``offered[b]`` lists the
+    candidates sequence b offers.  Sequences with nothing left offer nothing.  Returns the
+    candidate index of every node, per sequence."""
+    B = len(cand_parents)
+    children = []
+    for par in cand_parents:
+        ch = [[] for _ in par]
+        for u in range(1, len(par)):
+            ch[par[u]].append(u)
+        children.append(ch)
+    node_of = [{0: 0} for _ in range(B)]
+    cand_of_node = [[0] for _ in range(B)]
+    active = [[0] for _ in range(B)]
+    for _layer in range(max_depth):
+        offered = [sorted(u for a in active[b] for u in children[b][a]) for b in range(B)]
+        cu = np.zeros(B + 1, np.int32)
+        cu[1:] = np.cumsum([len(o) for o in offered])
+        parent_nodes = [node_of[b][cand_parents[b][u]] for b in range(B) for u in offered[b]]
+        out = list(step(cu, parent_nodes, offered))
+        for b in range(B):
+            kept = []
+            for j, u in enumerate(offered[b]):
+                nid = int(out[cu[b] + j])
+                if nid >= 0:
+                    assert nid == len(cand_of_node[b])
+                    node_of[b][u] = nid
+                    cand_of_node[b].append(u)
+                    kept.append(u)
+            active[b] = kept
+        if not any(active):
+            break
+    return cand_of_node

@@ -188,12 +188,16 @@ def test_device_entry_points_validate_on_the_host_first():
         assert tva(**bad) == B.SMART_EINVAL, bad
 
 
-def test_hand_worked_example_library():
-    """The same hand-worked forest through the C ABI."""
+def _hand_worked():
     import json
     import os
     with open(os.path.join(os.path.dirname(__file__), "golden", "selection_hand_worked.json")) as f:
-        g = json.load(f)
+        return json.load(f)
+
+
+def test_hand_worked_example_library():
+    """The same hand-worked forest through the C ABI."""
+    g = _hand_worked()
     fo = g["forest"]
     cost = np.array([1.0 + n / 8.0 for n in range(9)])
     modes = {"BEST_FIRST": B.SMART_BEST_FIRST, "LAYERWISE": B.SMART_LAYERWISE}
@@ -206,3 +210,124 @@ def test_hand_worked_example_library():
         assert r["parent"].tolist() == case["parent"], case["name"]
         assert r["pathprob"].tolist() == [fo["path_prob"][i] for i in case["cand_index"]]
         assert r["L"][0] == case["L"] and r["R"][0] == case["R"], case["name"]
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 one layer at a time (host form)
+# ---------------------------------------------------------------------------
+def _layered_forests(seed, batch):
+    rng = np.random.default_rng(seed)
+    forests = []
+    for _ in range(batch):
+        k, d = int(rng.integers(2, 5)), int(rng.integers(2, 5))
+        parent, prob, depth = [-1], [1.0], [0]
+        i = 0
+        while i < len(parent) and len(parent) < 400:
+            if depth[i] < d:
+                p = rng.dirichlet(np.ones(k + 1))[:k]
+                for j in np.argsort(-p):
+                    parent.append(i)
+                    prob.append(float(p[j]))
+                    depth.append(depth[i] + 1)
+            i += 1
+        forests.append((parent, prob, list(rng.integers(0, 32000, len(parent)))))
+    return forests
+
+
+def _library_layers(forests, cost, dcost, alpha, max_depth, budget, dilution):
+    from tests.helpers import drive_layers_batch
+    st = B.HostLayerState(len(forests), budget)
+    st.begin([f[2][0] for f in forests], cost)
+
+    def step(cu, parent_nodes, offered):
+        prob = [forests[b][1][u] for b in range(len(forests)) for u in offered[b]]
+        tok = [forests[b][2][u] for b in range(len(forests)) for u in offered[b]]
+        return st.layer(cu, parent_nodes, prob, tok, cost, dcost, alpha=alpha, dilution=dilution)
+
+    cand = drive_layers_batch([f[0] for f in forests], max_depth, step)
+    return st, cand
+
+
+@pytest.mark.parametrize("dilution", [B.SMART_DILUTION_NONE, B.SMART_DILUTION_PATH_MEAN])
+@pytest.mark.parametrize("seed", range(4))
+def test_layer_at_a_time_bit_exact_against_the_oracle(seed, dilution):
+    forests = _layered_forests(seed, batch=9)
+    cost = np.array([1.0 + 0.01 * n + 0.0005 * n * n for n in range(130)])
+    dcost = np.array([0.01 + 0.001 * n for n in range(129)]) if seed % 2 else None
+    for budget, max_depth in ((128, 4), (12, 4), (3, 3), (1, 2)):
+        st, cand = _library_layers(forests, cost, dcost, 0.85, max_depth, budget, dilution)
+        for b, (parent, prob, token) in enumerate(forests):
+            t = S.select_tree(parent, prob, token, cost.tolist(), None if dcost is None else dcost.tolist(),
+                              alpha=0.85, max_depth=max_depth, budget=budget, schedule=S.LAYERWISE,
+                              dilution=dilution)
+            par_b, tok_b, pp_b = st.tree(b)
+            assert cand[b] == t.cand_index and par_b == t.parent and tok_b == [int(x) for x in t.token]
+            assert pp_b == t.pathprob                               # bit for bit
+            assert st.L[b] == t.L and st.R[b] == t.R
+
+
+def test_layer_at_a_time_hand_worked_example_library():
+    from tests.helpers import drive_layers_batch
+    g = _hand_worked()
+    fo = g["forest"]
+    cost = np.array([1.0 + n / 8.0 for n in range(9)])
+    for case in g["cases"]:
+        if case["schedule"] != "LAYERWISE":
+            continue
+        st, cand = _library_layers([(fo["parent"], fo["prob"], fo["token"])], cost, None, case["alpha"],
+                                   g["max_depth"], g["budget"], getattr(B, "SMART_DILUTION_" + case["dilution"]))
+        par, tok, _ = st.tree(0)
+        assert cand[0] == case["cand_index"] and par == case["parent"], case["name"]
+        assert st.L[0] == case["L"] and st.R[0] == case["R"], case["name"]
+
+
+def test_layer_at_a_time_error_paths_leave_the_state_alone():
+    cost = np.array([1.0 + n / 8.0 for n in range(12)])
+    st = B.HostLayerState(2, 8)
+    st.begin([5, 6], cost)
+    st.layer([0, 2, 3], [0, 0, 0], [0.5, 0.25, 0.5], [1, 2, 3], cost, alpha=1.0)
+    snap = {k: getattr(st, k).copy() for k in ("n", "layer_begin", "sum_P", "parent", "token", "pathprob", "L", "R")}
+
+    def refused(code, *a, **kw):
+        with pytest.raises(B.SmartError) as e:
+            st.layer(*a, **kw)
+        assert e.value.code == code
+        for k, v in snap.items():
+            assert np.array_equal(getattr(st, k), v), k
+
+    refused(B.SMART_ETREE, [0, 1, 1], [0], [0.5], [1], cost)              # node 0 is no longer in the newest layer
+    refused(B.SMART_ETREE, [0, 1, 2], [1, 5], [0.5, 0.5], [1, 2], cost)   # node 5 does not exist
+    refused(B.SMART_ETREE, [0, 1, 1], [1], [1.5], [1], cost)              # not a probability
+    refused(B.SMART_ETREE, [0, 1, 1], [1], [float("nan")], [1], cost)
+    refused(B.SMART_ETREE, [1, 1, 1], [1], [0.5], [1], cost)              # offsets must start at 0
+    refused(B.SMART_ETREE, [0, 1, 0], [1], [0.5], [1], cost)              # ... and ascend
+    refused(B.SMART_EINVAL, [0, 1, 1], [1], [0.5], [1], cost, alpha=0.0)
+    refused(B.SMART_EINVAL, [0, 1, 1], [1], [0.5], [1], cost, dilution=7)
+    no_sum = B.HostLayerState(1, 8, path_sum=False)
+    no_sum.begin([1], cost)
+    with pytest.raises(B.SmartError) as e:
+        no_sum.layer([0, 1], [0], [0.5], [1], cost, dilution=B.SMART_DILUTION_PATH_MEAN)
+    assert e.value.code == B.SMART_EINVAL
+    assert no_sum.layer([0, 1], [0], [0.5], [9], cost, alpha=1.0).tolist() == [1]   # fine without dilution
+    # a layer that offers nothing ends the tree: no active node is left
+    assert st.layer([0, 0, 0], [], [], [], cost).tolist() == []
+    assert st.layer_begin.tolist() == st.n.tolist()
+    refused2 = pytest.raises(B.SmartError)
+    with refused2 as e:
+        st.layer([0, 1, 1], [1], [0.5], [1], cost)
+    assert e.value.code == B.SMART_ETREE
+
+
+def test_device_layer_entry_points_validate_on_the_host_first():
+    import ctypes
+    lib = B._lib()
+    st = B.LayerStateStruct(batch=1, budget=8)
+    one = ctypes.c_void_p(8)
+    assert lib.smart_select_begin_device(None, None, ctypes.byref(st), one, one) == B.SMART_EINVAL
+    assert lib.smart_select_layer_device(None, None, ctypes.byref(st), one, one, one, one, 4, one, None, 0.8, 0,
+                                         one, one) == B.SMART_EINVAL
+    assert lib.tree_compact_pack(None, None, ctypes.byref(st), 8, one, one, one, one, one, one, one, one,
+                                 one) == B.SMART_EINVAL
+    assert lib.smart_select_begin(None, one, one) == B.SMART_EINVAL
+    bad = B.LayerStateStruct(batch=1, budget=129)
+    assert lib.smart_select_begin(ctypes.byref(bad), one, one) == B.SMART_EINVAL
