@@ -324,3 +324,46 @@ def select_layer(state, cand_parent_node, cand_prob, cand_token, cost, dcost=Non
         state.L, _ = path_mean_L(state.parent, state.pathprob)
     state.R = state.L / float(cost[len(state)])
     return out_node
+
+
+# ---------------------------------------------------------------------------
+# The likelihood-maximising policy SMART is compared with (Sec. 3.1, first
+# paragraph; Fig. "method-comparison" (a), (b)).
+# ---------------------------------------------------------------------------
+def baseline_tree(cand_parent, cand_prob, cand_token, cost, k=10, max_depth=6, g=60):
+    """Expansion phase: layer by layer, the k candidates of the layer with the
+    largest cumulative probability P are expanded (their children, as the
+    candidate forest lists them, form the next layer); the first layer is the
+    root's children.  Rerank phase: every candidate generated in layers
+    1 .. max_depth is ranked by P and the best g are kept (ties anywhere:
+    smaller candidate index first; the root is kept besides).  Nodes are numbered
+    by layer, then candidate index.  L = sum of P over the kept nodes, R = L /
+    cost[n] as for the other policies (dilution NONE)."""
+    P, depth = path_prob_and_depth(cand_parent, cand_prob)
+    C = len(cand_parent)
+    children = [[] for _ in range(C)]
+    for u in range(1, C):
+        children[cand_parent[u]].append(u)
+    generated = []
+    expanded = [0]
+    for _layer in range(1, max_depth + 1):
+        layer = [u for e in expanded for u in children[e]]
+        if not layer:
+            break
+        generated += layer
+        expanded = sorted(layer, key=lambda u: (-P[u], u))[:k]
+    kept = sorted(generated, key=lambda u: (-P[u], u))[:g]
+    kept = [0] + sorted(kept, key=lambda u: (depth[u], u))
+    out = SelectedTree()
+    node_of = {}
+    L = 0.0
+    for u in kept:
+        node_of[u] = len(out.parent)
+        out.parent.append(-1 if u == 0 else node_of[cand_parent[u]])
+        out.token.append(int(cand_token[u]))
+        out.cand_index.append(u)
+        out.pathprob.append(P[u])
+        L = L + P[u]
+    out.L = L
+    out.R = L / float(cost[len(out)])
+    return out

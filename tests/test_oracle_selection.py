@@ -344,3 +344,70 @@ def test_one_layer_against_exact_rational_arithmetic():
     assert out == [-1] and st.layer_begin == len(st) == 5
     with pytest.raises(ValueError):
         S.select_layer(st, [3], [1.0], [1], cost, budget=8)            # node 3 is not in the newest layer
+
+
+# ---------------------------------------------------------------------------
+# The likelihood-maximising baseline policy
+# ---------------------------------------------------------------------------
+def _baseline_hand_worked():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "baseline_hand_worked.json")) as f:
+        return json.load(f)
+
+
+def test_baseline_policy_hand_worked_example_oracle():
+    g = _baseline_hand_worked()
+    fo = g["forest"]
+    P, _ = S.path_prob_and_depth(fo["parent"], fo["prob"])
+    assert P == fo["path_prob"]
+    cost = [1.0 + n / 8.0 for n in range(70)]
+    for case in g["cases"]:
+        t = S.baseline_tree(fo["parent"], fo["prob"], fo["token"], cost, k=case["k"],
+                            max_depth=case.get("max_depth", g["max_depth"]), g=case["g"])
+        assert t.cand_index == case["cand_index"] and t.parent == case["parent"], case["name"]
+        assert t.token == [fo["token"][i] for i in case["cand_index"]]
+        assert t.L == case["L"] and t.R == case["R"], case["name"]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_baseline_policy_properties(seed):
+    parent, prob, token = tiny_forest(seed, k=3, d=4)
+    P, dep = S.path_prob_and_depth(parent, prob)
+    cost = [1.0 + 0.05 * n for n in range(len(parent) + 2)]
+    C = len(parent)
+    # expanding everything and keeping everything returns the whole forest down to the depth cap
+    t = S.baseline_tree(parent, prob, token, cost, k=C, max_depth=3, g=C)
+    assert sorted(t.cand_index) == [u for u in range(C) if dep[u] <= 3]
+    for k, g in ((2, 5), (3, 9), (1, 4), (2, 100)):
+        t = S.baseline_tree(parent, prob, token, cost, k=k, max_depth=4, g=g)
+        kept = set(t.cand_index)
+        assert all(parent[u] in kept for u in kept if u)                       # a tree
+        # what the expansion phase generates, by a recursion of its own: a node is generated iff its parent
+        # is the root or was among its layer's k best generated nodes
+        gen_by_layer, expanded = {}, {0}
+        for layer in range(1, 5):
+            gen = [u for u in range(1, C) if dep[u] == layer and parent[u] in expanded]
+            gen_by_layer[layer] = gen
+            expanded = set(sorted(gen, key=lambda u: (-P[u], u))[:k])
+        generated = [u for gen in gen_by_layer.values() for u in gen]
+        assert kept - {0} <= set(generated) and len(kept) - 1 == min(g, len(generated))
+        # nothing left out is better than anything kept
+        worst_kept = min((P[u], -u) for u in kept - {0})
+        assert all((P[u], -u) < worst_kept for u in generated if u not in kept)
+        assert abs(t.L - sum(P[u] for u in kept)) < 1e-12 and t.R == t.L / cost[len(kept)]
+        dl = [dep[u] for u in t.cand_index]
+        assert dl == sorted(dl)                                                # numbered layer by layer
+
+
+def test_smart_never_loses_to_the_baseline_in_modelled_speedup_when_the_rule_is_optimal():
+    """With alpha = 1, exact marginals and a convex cost the node-by-node rule maximises R over all
+    parent-closed subsets (pinned above by exhaustive search), so no tree the baseline policy keeps can
+    have a larger modelled speedup."""
+    for seed in range(8):
+        parent, prob, token = tiny_forest(seed, k=3, d=4)
+        cost = [1.0 + 0.02 * n + 0.004 * n * n for n in range(len(parent) + 2)]
+        smart = S.select_tree(parent, prob, token, cost, alpha=1.0, max_depth=4, budget=len(parent))
+        for k, g in ((2, 8), (3, 20), (3, 60)):
+            base = S.baseline_tree(parent, prob, token, cost, k=k, max_depth=4, g=g)
+            assert smart.R >= base.R * (1 - 1e-12)
