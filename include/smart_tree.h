@@ -166,6 +166,32 @@ int32_t smart_select_tree(
     double* h_out_L, double* h_out_R);
 
 /* ---------------------------------------------------------------------------
+ * smart_baseline_tree (host, batched over sequences)
+ *
+ * The likelihood-maximising two-phase policy the paper compares SMART with
+ * (Sec. 3.1, first paragraph; Fig. "method-comparison" (a), (b)), over the same
+ * candidate forests and with the same outputs as smart_select_tree, so that
+ * both policies' trees can be fed to the verification kernels and their
+ * modelled speedups R compared under one cost table.
+ *   Expansion: layer 1 is the root's children; of every layer the k candidates
+ *   with the largest cumulative probability P are expanded, their children (as
+ *   the forest lists them) form the next layer; max_depth layers.
+ *   Rerank: all generated candidates are ranked by P and the best g kept,
+ *   besides the root.  Ties anywhere: smaller candidate index first.
+ * Nodes are numbered by layer, then candidate index.  L = sum of P over the
+ * kept nodes (root included), R = L / h_cost[n]; h_cost needs g + 2 entries.
+ * Errors: SMART_EINVAL (null, k < 1, max_depth < 0, g outside
+ * 0 .. SMART_MAX_NODES - 1), SMART_ETREE, SMART_ECAP as for smart_select_tree.
+ * ------------------------------------------------------------------------- */
+int32_t smart_baseline_tree(
+    int32_t batch, const int32_t* h_cand_cu, const int32_t* h_cand_parent,
+    const double* h_cand_prob, const int32_t* h_cand_token, const double* h_cost,
+    int32_t k, int32_t max_depth, int32_t g,
+    int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
+    int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
+    double* h_out_L, double* h_out_R);
+
+/* ---------------------------------------------------------------------------
  * Algorithm 1 one layer at a time: smart_select_begin / smart_select_layer
  * (host) and smart_select_begin_device / smart_select_layer_device (device)
  *

@@ -26,7 +26,7 @@ SMART_MAX_NODES = 128
 SMART_MAX_LAYER_CAND = 2048
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
-           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_begin", "smart_select_layer",
+           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
            "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
@@ -96,6 +96,8 @@ def _lib():
         lib.smart_select_tree.restype = i32
         lib.smart_select_tree.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, i32, i32,
                                           vp, vp, vp, vp, vp, i64, vp, vp]
+        lib.smart_baseline_tree.restype = i32
+        lib.smart_baseline_tree.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp]
         sp = ctypes.POINTER(LayerStateStruct)
         lib.smart_select_begin.restype = i32
         lib.smart_select_begin.argtypes = [sp, vp, vp]
@@ -176,6 +178,31 @@ def smart_select_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, dcost=N
     n = int(o_cu[-1])
     return dict(cu_nodes=o_cu, parent=o_parent[:n], token=o_token[:n], cand_index=o_cand[:n],
                 pathprob=o_pp[:n], L=o_L[:batch], R=o_R[:batch])
+
+
+def smart_baseline_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, k=10, max_depth=6, g=60):
+    """The expand-top-k / keep-top-g policy; same result dict as smart_select_tree."""
+    cand_cu = np.ascontiguousarray(cand_cu, np.int32)
+    cand_parent = np.ascontiguousarray(cand_parent, np.int32)
+    cand_prob = np.ascontiguousarray(cand_prob, np.float64)
+    cand_token = np.ascontiguousarray(cand_token, np.int32)
+    cost = np.ascontiguousarray(cost, np.float64)
+    if cost.shape[0] < g + 2:
+        raise ValueError("cost needs g + 2 entries")
+    batch = cand_cu.shape[0] - 1
+    cap = max(1, batch * (g + 1))
+    o_cu = np.zeros(batch + 1, np.int32)
+    o_parent, o_token, o_cand = (np.zeros(cap, np.int32) for _ in range(3))
+    o_pp = np.zeros(cap, np.float64)
+    o_L, o_R = np.zeros(max(batch, 1), np.float64), np.zeros(max(batch, 1), np.float64)
+    p = lambda a: ctypes.c_void_p(a.ctypes.data)
+    rc = _lib().smart_baseline_tree(batch, p(cand_cu), p(cand_parent), p(cand_prob), p(cand_token), p(cost), int(k),
+                                    int(max_depth), int(g), p(o_cu), p(o_parent), p(o_token), p(o_cand), p(o_pp),
+                                    cap, p(o_L), p(o_R))
+    _check(rc, "smart_baseline_tree")
+    n = int(o_cu[-1])
+    return dict(cu_nodes=o_cu, parent=o_parent[:n], token=o_token[:n], cand_index=o_cand[:n], pathprob=o_pp[:n],
+                L=o_L[:batch], R=o_R[:batch])
 
 
 class HostLayerState:

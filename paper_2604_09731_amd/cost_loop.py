@@ -7,7 +7,9 @@ sequence (the paper profiles a handful of forward passes per device), take the p
 step (a tree that is only its root) as c_T, fit the power-exponential model of Eq. "exp_model"
 to the EXTRA time over that step as a function of the drafted tokens batch * (n - 1), build the
 cost tables (cost[n] = 1 + model / c_T) and let smart_select_tree choose trees over the same
-candidate forests.  Prints the fits and the chosen tree sizes per batch size.
+candidate forests.  The likelihood-maximising expand-and-rerank policy (Sec. 3.1, first paragraph)
+is run over the same forests for comparison: its modelled speedup under the same cost table, and
+the measured attention time of both policies' trees.  Prints one JSON row per batch size.
 
 This measures ONE attention layer, not a whole target model: the point is the loop (measure,
 fit, select) on this hardware, not the absolute speedups.
@@ -32,41 +34,55 @@ def main(argv=None):
     ap.add_argument("--prefix", type=int, default=3584)
     ap.add_argument("--sizes", type=int, nargs="+", default=[1, 4, 8, 16, 32, 64])
     ap.add_argument("--reps", type=int, default=50)
+    ap.add_argument("--baseline-k", type=int, default=8)
+    ap.add_argument("--baseline-depth", type=int, default=6)
+    ap.add_argument("--baseline-g", type=int, default=59)
     args = ap.parse_args(argv)
     assert torch.cuda.is_available(), "needs the MI355X"
     lib = B.SmartTree(0)
     base = W.WORKLOADS["cfg3a"]
     rows = []
+
+    def time_attention(w, cu, parent):
+        """Microseconds per tree_verify_attention call for these trees (cache and queries synthetic)."""
+        inp = W.make_attention_inputs(w, cu, poison_unused=False)
+        dev = "cuda"
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        el = lambda a: torch.from_numpy(np.ascontiguousarray(a)).view(torch.int16).view(torch.bfloat16).to(dev)
+        kc, vc = B.interleave_kv_cache(el(inp.k_cache), el(inp.v_cache))
+        d_cu, d_par, d_len = t(cu), t(parent), t(inp.prefix_len)
+        _, _, _, mask, _ = lib.tree_pack(d_cu, d_par, d_len)
+        q, kt, vt, bt = el(inp.q), el(inp.k_tree), el(inp.v_tree), t(inp.block_table)
+        run = lambda: lib.tree_verify_attention(q, kt, vt, kc, vc, bt, d_len, d_cu, mask, inp.scale,
+                                                B.SMART_KV_INTERLEAVED)
+        for _ in range(5):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / args.reps
+
+    def tiled(sel, batch):
+        """The trees of a selection result, repeated until there are `batch` of them."""
+        n_seq = sel["cu_nodes"].shape[0] - 1
+        sizes = np.diff(sel["cu_nodes"])
+        order = [b % n_seq for b in range(batch)]
+        cu = np.concatenate([[0], np.cumsum(sizes[order])]).astype(np.int32)
+        parent = np.concatenate([sel["parent"][sel["cu_nodes"][b]:sel["cu_nodes"][b + 1]] for b in order])
+        return cu, parent.astype(np.int32), float(np.mean(sel["L"][order]))
+
     for batch in args.batches:
         w = base.scaled(batch=batch, prefix_min=args.prefix, prefix_max=args.prefix)
         rng = np.random.default_rng(7)
         big = W.random_tree(max(args.sizes), rng, "random")           # nested trees: the first n nodes of one tree
         times = []
-        inp = None
         for n in args.sizes:
             cu = (np.arange(batch + 1) * n).astype(np.int32)
-            parent = np.tile(big[:n], batch).astype(np.int32)
-            inp = W.make_attention_inputs(w, cu, poison_unused=False)
-            dev = "cuda"
-            t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-            el = lambda a: torch.from_numpy(np.ascontiguousarray(a)).view(torch.int16).view(torch.bfloat16).to(dev)
-            kc, vc = B.interleave_kv_cache(el(inp.k_cache), el(inp.v_cache))
-            d_cu, d_par, d_len = t(cu), t(parent), t(inp.prefix_len)
-            _, _, _, mask, _ = lib.tree_pack(d_cu, d_par, d_len)
-            q, kt, vt, bt = el(inp.q), el(inp.k_tree), el(inp.v_tree), t(inp.block_table)
-            run = lambda: lib.tree_verify_attention(q, kt, vt, kc, vc, bt, d_len, d_cu, mask, inp.scale,
-                                                    B.SMART_KV_INTERLEAVED)
-            for _ in range(5):
-                run()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(args.reps):
-                run()
-            e1.record()
-            torch.cuda.synchronize()
-            times.append(e0.elapsed_time(e1) * 1e3 / args.reps)       # microseconds per call
-            del kc, vc
+            times.append(time_attention(w, cu, np.tile(big[:n], batch).astype(np.int32)))
         sizes = np.array(args.sizes, np.float64)
         times = np.array(times)
         c_T = times[0] if args.sizes[0] == 1 else float(np.interp(1.0, sizes, times))
@@ -86,6 +102,18 @@ def main(argv=None):
                    rms_us=round(float(np.sqrt(fit["sse"] / len(x))), 3),
                    tree_nodes_min_median_max=[int(n_sel.min()), int(np.median(n_sel)), int(n_sel.max())],
                    L_mean=round(float(sel["L"].mean()), 3), R_mean=round(float(sel["R"].mean()), 3))
+        # The fixed expand-and-rerank policy over the same forests, under the same cost table: its modelled
+        # speedup, and what the kernel really takes for both policies' trees (measured R = L c_T / time).
+        fixed = B.smart_baseline_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost,
+                                      k=args.baseline_k, max_depth=args.baseline_depth, g=min(args.baseline_g, n_max - 1))
+        for name, res in (("smart", sel), ("baseline", fixed)):
+            cu, parent, L_mean = tiled(res, batch)
+            us = time_attention(w, cu, parent)
+            row[name + "_us"] = round(float(us), 2)
+            row[name + "_measured_R"] = round(L_mean * float(c_T) / float(us), 3)
+        row["baseline_nodes"] = int(np.median(np.diff(fixed["cu_nodes"])))
+        row["baseline_L_mean"] = round(float(fixed["L"].mean()), 3)
+        row["baseline_R_mean"] = round(float(fixed["R"].mean()), 3)
         rows.append(row)
         print(json.dumps(row), flush=True)
     return rows

@@ -506,3 +506,115 @@ extern "C" int32_t smart_select_layer(const smart_layer_state* s, const int32_t*
   }
   return SMART_OK;
 }
+
+// ---------------------------------------------------------------------------
+// The likelihood-maximising policy SMART is compared with (Sec. 3.1, first
+// paragraph): expand the k most probable candidates of each layer, then keep the
+// g most probable of everything generated.
+// ---------------------------------------------------------------------------
+namespace {
+
+struct BaselineArgs {
+  const int32_t* cand_cu;
+  const int32_t* cand_parent;
+  const double* cand_prob;
+  const int32_t* cand_token;
+  const double* cost;
+  int32_t k, max_depth, g;
+};
+
+void baseline_one(const BaselineArgs& a, int b, SeqResult* out) {
+  const int lo = a.cand_cu[b], C = a.cand_cu[b + 1] - lo;
+  const int32_t* cpar = a.cand_parent + lo;
+  const double* cprob = a.cand_prob + lo;
+  out->clear();
+  if (C < 1 || cpar[0] != -1) { out->err = SMART_ETREE; return; }
+  std::vector<double> P(C);
+  std::vector<int32_t> depth(C), next_sibling(C, -1), first_child(C, -1), last_child(C, -1);
+  P[0] = 1.0;
+  depth[0] = 0;
+  for (int u = 1; u < C; ++u) {
+    const int p = cpar[u];
+    const double pr = cprob[u];
+    if (p < 0 || p >= u || !(pr >= 0.0 && pr <= 1.0)) { out->err = SMART_ETREE; return; }
+    P[u] = P[p] * pr;
+    depth[u] = depth[p] + 1;
+    if (first_child[p] < 0) first_child[p] = u; else next_sibling[last_child[p]] = u;
+    last_child[p] = u;
+  }
+  auto better = [&](int x, int y) { return P[x] > P[y] || (P[x] == P[y] && x < y); };
+  std::vector<int32_t> generated, expanded(1, 0), layer;
+  for (int l = 1; l <= a.max_depth; ++l) {
+    layer.clear();
+    for (int e : expanded)
+      for (int u = first_child[e]; u >= 0; u = next_sibling[u]) layer.push_back(u);
+    if (layer.empty()) break;
+    generated.insert(generated.end(), layer.begin(), layer.end());
+    if ((int)layer.size() > a.k) {
+      std::partial_sort(layer.begin(), layer.begin() + a.k, layer.end(), better);
+      layer.resize(a.k);
+    }
+    expanded = layer;
+  }
+  if ((int)generated.size() > a.g) {
+    std::partial_sort(generated.begin(), generated.begin() + a.g, generated.end(), better);
+    generated.resize(a.g);
+  }
+  std::sort(generated.begin(), generated.end(),
+            [&](int x, int y) { return depth[x] < depth[y] || (depth[x] == depth[y] && x < y); });
+  std::vector<int32_t> node_of(C, -1);
+  double L = 0.0;
+  auto append = [&](int u) {
+    node_of[u] = (int)out->parent.size();
+    out->parent.push_back(u == 0 ? -1 : node_of[cpar[u]]);
+    out->token.push_back(a.cand_token[lo + u]);
+    out->cand.push_back(u);
+    out->pathprob.push_back(P[u]);
+    L = L + P[u];
+  };
+  append(0);
+  for (int u : generated) append(u);
+  out->L = L;
+  out->R = L / a.cost[out->parent.size()];
+}
+
+}  // namespace
+
+extern "C" int32_t smart_baseline_tree(
+    int32_t batch, const int32_t* h_cand_cu, const int32_t* h_cand_parent, const double* h_cand_prob,
+    const int32_t* h_cand_token, const double* h_cost, int32_t k, int32_t max_depth, int32_t g,
+    int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token, int32_t* h_out_cand_index,
+    double* h_out_pathprob, int64_t out_cap, double* h_out_L, double* h_out_R) {
+  if (batch < 0 || !h_cand_cu || !h_cost || !h_out_cu) return SMART_EINVAL;
+  if (batch > 0 && (!h_cand_parent || !h_cand_prob || !h_cand_token || !h_out_parent || !h_out_token ||
+                    !h_out_cand_index || !h_out_pathprob || !h_out_L || !h_out_R))
+    return SMART_EINVAL;
+  if (k < 1 || max_depth < 0 || g < 0 || g > SMART_MAX_NODES - 1 || out_cap < 0) return SMART_EINVAL;
+  if (h_cand_cu[0] != 0) return SMART_ETREE;
+  for (int b = 0; b < batch; ++b)
+    if (h_cand_cu[b + 1] <= h_cand_cu[b]) return SMART_ETREE;
+  const BaselineArgs a{h_cand_cu, h_cand_parent, h_cand_prob, h_cand_token, h_cost, k, max_depth, g};
+  static thread_local std::vector<SeqResult> res;
+  if ((int)res.size() < batch) res.resize(batch);
+  int64_t total = 0;
+  for (int b = 0; b < batch; ++b) {
+    baseline_one(a, b, &res[b]);
+    if (res[b].err != SMART_OK) return res[b].err;
+    total += (int64_t)res[b].parent.size();
+  }
+  if (total > out_cap) return SMART_ECAP;
+  int32_t off = 0;
+  h_out_cu[0] = 0;
+  for (int b = 0; b < batch; ++b) {
+    const SeqResult& r = res[b];
+    std::copy(r.parent.begin(), r.parent.end(), h_out_parent + off);
+    std::copy(r.token.begin(), r.token.end(), h_out_token + off);
+    std::copy(r.cand.begin(), r.cand.end(), h_out_cand_index + off);
+    std::copy(r.pathprob.begin(), r.pathprob.end(), h_out_pathprob + off);
+    off += (int32_t)r.parent.size();
+    h_out_cu[b + 1] = off;
+    h_out_L[b] = r.L;
+    h_out_R[b] = r.R;
+  }
+  return SMART_OK;
+}

@@ -59,7 +59,7 @@ constexpr int kLargeSlot = kLargeRows * kD + 2 * kLargeRows;
 __host__ __device__ inline int class_rows(int cls) { return cls == 0 ? kSmallRows : (cls == 1 ? kMediumRows : kLargeRows); }
 __host__ __device__ inline int class_slot(int cls) { return cls == 0 ? kSmallSlot : (cls == 1 ? kMediumSlot : kLargeSlot); }
 constexpr int kCombineRows = 8;       // rows per combine wavefront (8 lanes per row)
-constexpr int kMinTilesPerWorker[kClasses] = {16, 32, 8};  // workers are 8-wave workgroups
+constexpr int kMinTilesPerWorker[kClasses] = {16, 16, 8};  // workers are 8-wave workgroups
 constexpr int kChunkTiles = 64;       // tiles whose block ids one pair of registers holds
 constexpr float kLog2e = 1.4426950408889634f;
 

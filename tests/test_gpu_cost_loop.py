@@ -15,3 +15,7 @@ def test_cost_loop_small():
     assert all(math.isfinite(r[k]) and r[k] > 0 for k in ("gamma", "delta", "rho", "c_T_us"))
     lo, med, hi = r["tree_nodes_min_median_max"]
     assert 1 <= lo <= med <= hi <= 64
+    # the fixed policy keeps its 59 draft nodes whatever they cost; the rule's modelled speedup is never the smaller one
+    # by much (alpha < 1 makes it conservative), and both policies' trees were really run through the kernel
+    assert r["baseline_nodes"] == 60 and r["smart_us"] > 0 and r["baseline_us"] > 0
+    assert r["smart_measured_R"] > 0 and r["baseline_measured_R"] > 0

@@ -331,3 +331,55 @@ def test_device_layer_entry_points_validate_on_the_host_first():
     assert lib.smart_select_begin(None, one, one) == B.SMART_EINVAL
     bad = B.LayerStateStruct(batch=1, budget=129)
     assert lib.smart_select_begin(ctypes.byref(bad), one, one) == B.SMART_EINVAL
+
+
+# ---------------------------------------------------------------------------
+# The likelihood-maximising baseline policy
+# ---------------------------------------------------------------------------
+def test_baseline_policy_hand_worked_example_library():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "baseline_hand_worked.json")) as f:
+        g = json.load(f)
+    fo = g["forest"]
+    cost = np.array([1.0 + n / 8.0 for n in range(70)])
+    for case in g["cases"]:
+        r = B.smart_baseline_tree([0, len(fo["parent"])], fo["parent"], fo["prob"], fo["token"], cost, k=case["k"],
+                                  max_depth=case.get("max_depth", g["max_depth"]), g=case["g"])
+        assert r["cand_index"].tolist() == case["cand_index"] and r["parent"].tolist() == case["parent"], case["name"]
+        assert r["L"][0] == case["L"] and r["R"][0] == case["R"], case["name"]
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_baseline_policy_bit_exact_on_workload_forests(name):
+    w = W.WORKLOADS[name].scaled(batch=6)
+    f = W.make_forest(w)
+    cost = np.array([1.0 + 0.004 * n for n in range(130)])
+    for k, d, g in ((10, 6, 60), (3, 3, 8), (5, 7, 127), (7, 4, 0), (1, 8, 30)):
+        r = B.smart_baseline_tree(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, k=k, max_depth=d, g=g)
+        for b in range(w.batch):
+            lo, hi = int(f.cand_cu[b]), int(f.cand_cu[b + 1])
+            t = S.baseline_tree(f.cand_parent[lo:hi].tolist(), f.cand_prob[lo:hi].tolist(),
+                                f.cand_token[lo:hi].tolist(), cost.tolist(), k=k, max_depth=d, g=g)
+            a, e = int(r["cu_nodes"][b]), int(r["cu_nodes"][b + 1])
+            assert r["cand_index"][a:e].tolist() == t.cand_index and r["parent"][a:e].tolist() == t.parent
+            assert r["token"][a:e].tolist() == t.token and r["pathprob"][a:e].tolist() == t.pathprob
+            assert r["L"][b] == t.L and r["R"][b] == t.R
+
+
+def test_baseline_policy_error_paths():
+    cost = np.ones(130)
+    ok = dict(cand_cu=[0, 3], cand_parent=[-1, 0, 0], cand_prob=[1.0, 0.5, 0.25], cand_token=[1, 2, 3], cost=cost)
+    assert B.smart_baseline_tree(**ok, k=2, max_depth=2, g=5)["cu_nodes"].tolist() == [0, 3]
+    for bad, code in ((dict(k=0), B.SMART_EINVAL), (dict(max_depth=-1), B.SMART_EINVAL), (dict(g=128), None),
+                      (dict(cand_parent=[-1, 0, 2]), B.SMART_ETREE), (dict(cand_prob=[1.0, 1.5, 0.2]), B.SMART_ETREE),
+                      (dict(cand_cu=[1, 3]), B.SMART_ETREE)):
+        kw = dict(ok, k=2, max_depth=2, g=5)
+        kw.update(bad)
+        if code is None:
+            with pytest.raises((B.SmartError, ValueError)):
+                B.smart_baseline_tree(**kw)
+            continue
+        with pytest.raises(B.SmartError) as e:
+            B.smart_baseline_tree(**kw)
+        assert e.value.code == code, bad
