@@ -21,6 +21,8 @@
  *                          attention sub-step of that forward pass)
  *   tree_accept            greedy longest accepted path ("accepted" prefix by
  *                          prefix, Sec. 3.1 below Eq. "cum_prob")
+ *   tree_rope              rotates the tree's queries and keys by their position
+ *                          ids (for rotary-embedding target models)
  *   kv_cache_write         writes token K/V rows into the paged cache in the
  *                          layout tree_verify_attention streams fastest
  *   tree_commit            appends the accepted path's K/V rows to the cache and
@@ -82,6 +84,9 @@ enum { SMART_KV_PLAIN = 0, SMART_KV_INTERLEAVED = 1 };
 /* smart_select_tree modes */
 enum { SMART_BEST_FIRST = 0, SMART_LAYERWISE = 1 };
 enum { SMART_DILUTION_NONE = 0, SMART_DILUTION_PATH_MEAN = 1 };
+
+/* tree_rope pairings */
+enum { SMART_ROPE_HALF_SPLIT = 0, SMART_ROPE_INTERLEAVED = 1 };
 
 /* smart_set_option keys */
 enum {
@@ -376,6 +381,31 @@ int32_t tree_pack(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nod
                   const int32_t* d_cu_nodes, const int32_t* d_parent, const int32_t* d_prefix_len,
                   int32_t* d_depth, int32_t* d_position, int32_t* d_node_seq,
                   uint64_t* d_anc_mask, int32_t* d_status);
+
+/* ---------------------------------------------------------------------------
+ * tree_rope (device)
+ *
+ * Rotary position embedding of the tree's queries and keys, in place, by the
+ * position ids tree_pack wrote (a node at depth d of sequence b is verified at
+ * position prefix_len[b] + d: the whole tree passes through the target model
+ * at once, Sec. 1).  Pair i (i = 0 .. rotary_dim/2 - 1) of every head of node
+ * t is turned by the angle d_position[t] * base^(-2 i / rotary_dim):
+ *   (x, y) -> (x cos - y sin, x sin + y cos),
+ *   SMART_ROPE_HALF_SPLIT:  (x, y) = (v[i], v[i + rotary_dim/2])
+ *   SMART_ROPE_INTERLEAVED: (x, y) = (v[2i], v[2i + 1])
+ * Elements from rotary_dim on are left alone.  Angles are formed in binary64,
+ * the rotation in binary32; bf16 results are rounded to nearest even.
+ * d_q [total_nodes][num_q_heads][head_dim], d_k_tree [total_nodes][num_kv_heads]
+ * [head_dim] (either may be NULL if its head count is 0).  Call it before
+ * tree_verify_attention and tree_commit, so that the cache only ever holds
+ * rotated keys.  total_nodes may be a capacity (rows past the trees are
+ * rotated by whatever d_position holds there; nothing reads them).
+ * Host errors: SMART_EINVAL (null pointers, head_dim > 128, rotary_dim odd or
+ * outside 2 .. head_dim, unknown dtype / pairing, base not positive).
+ * ------------------------------------------------------------------------- */
+int32_t tree_rope(smart_ctx* ctx, void* stream, int32_t dtype, int32_t total_nodes,
+                  int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim, int32_t rotary_dim,
+                  int32_t pairing, double base, const int32_t* d_position, void* d_q, void* d_k_tree);
 
 /* ---------------------------------------------------------------------------
  * kv_cache_write (device)

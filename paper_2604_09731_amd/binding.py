@@ -22,12 +22,13 @@ SMART_BEST_FIRST, SMART_LAYERWISE = 0, 1
 SMART_DILUTION_NONE, SMART_DILUTION_PATH_MEAN = 0, 1
 SMART_OPT_TVA_WORKERS, SMART_OPT_TVA_FORCE_GENERAL, SMART_OPT_TVA_PROFILE = 1, 2, 3
 SMART_OPT_TVA_PROFILE_STRIDE = 4
+SMART_ROPE_HALF_SPLIT, SMART_ROPE_INTERLEAVED = 0, 1
 SMART_MAX_NODES = 128
 SMART_MAX_LAYER_CAND = 2048
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
-           "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
+           "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
 
@@ -109,6 +110,8 @@ def _lib():
         lib.smart_select_layer_device.argtypes = [vp, vp, sp, vp, vp, vp, vp, i64, vp, vp, f64, i32, vp, vp]
         lib.tree_compact_pack.restype = i32
         lib.tree_compact_pack.argtypes = [vp, vp, sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.tree_rope.restype = i32
+        lib.tree_rope.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, f64, vp, vp, vp]
         lib.smart_cost_tables.restype = i32
         lib.smart_cost_tables.argtypes = [f64, f64, f64, f64, f64, f64, i32, vp, vp]
         lib.smart_fit_cost_models.restype = i32
@@ -437,6 +440,16 @@ class SmartTree:
                                       _ptr(anc_mask), _ptr(status))
         _check(rc, "tree_compact_pack")
         return cu, par[:N], tok[:N], depth[:N], position[:N], node_seq[:N], anc_mask[:N], status[:B]
+
+    # -- tree_rope ---------------------------------------------------------
+    def tree_rope(self, position, q, k_tree, base=10000.0, rotary_dim=None, pairing=SMART_ROPE_HALF_SPLIT):
+        """Rotates q [N, Hq, D] and k_tree [N, Hkv, D] in place by the nodes' position ids."""
+        N, Hq, D = q.shape
+        Hkv = k_tree.shape[1]
+        rc = _lib().tree_rope(self._h, _stream_ptr(), _dtype_code(q), N, Hq, Hkv, D,
+                              int(D if rotary_dim is None else rotary_dim), int(pairing), float(base),
+                              _ptr(position), _ptr(q), _ptr(k_tree))
+        _check(rc, "tree_rope")
 
     # -- tree_pack ---------------------------------------------------------
     def tree_pack(self, cu_nodes, parent, prefix_len):
