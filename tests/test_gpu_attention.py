@@ -371,3 +371,28 @@ def test_medium_trees_every_tail_of_the_two_tile_iteration(lib, oracle_attention
             check_full(lib, oracle_attention, case)
         finally:
             lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
+
+
+# ----- seeded random shapes: batch sizes around the 64-sequence plan window, group sizes 1..16, ------
+# ----- all three row classes mixed in one call, chains / stars / random trees, ragged and empty prefixes
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_shapes(lib, oracle_attention, seed):
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    for case in range(40):
+        batch = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 65, 70]))
+        Hkv, G = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 7, 8, 16]))
+        kind = str(rng.choice(["small", "mixed", "big"]))
+        lo, hi = {"small": (1, 9), "mixed": (1, 129), "big": (40, 129)}[kind]
+        sizes = rng.integers(lo, hi, batch)
+        if batch * int(sizes.max()) * Hkv * G > 40000:
+            sizes = np.minimum(sizes, 24)
+        trees = [W.random_tree(int(n), rng, str(rng.choice(["random", "chain", "star"]))) for n in sizes]
+        cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        parent = np.concatenate(trees).astype(np.int32)
+        lens = rng.integers(0, int(rng.choice([40, 300, 1500])), batch).astype(np.int32)
+        lens[rng.integers(0, batch)] = int(rng.choice([0, 1, 31, 32, 33, 64]))
+        w = W.Workload("random_shapes", "bf16", batch, Hkv * G, Hkv, 128, 0, 0, seed=1000 * seed + case)
+        c = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=lens, trees=(cu, parent), seed=1000 * seed + case)
+        worst = max(worst, check_full(lib, oracle_attention, c))
+    assert worst <= H.TOL["bf16"]
