@@ -19,9 +19,10 @@
 //    their rows per kv head (<= 32, <= 64, more); ONE kernel launch serves all
 //    three, its workgroups dealt to the classes in proportion to their work:
 //    class 0 streams K/V from HBM straight into operand registers (eight
-//    wavefronts share a worker's tiles), class 1 does the same with two row
-//    tiles per wavefront, class 2 stages tiles in LDS (HBM -> LDS without
-//    passing through registers) for eight wavefronts of 32 rows each.
+//    wavefronts share a worker's tiles); classes 1 and 2 stage tiles in LDS
+//    (HBM -> LDS without passing through registers) for the eight wavefronts
+//    of a workgroup: two row tiles x two key groups in class 1, eight row
+//    tiles of 32 rows each in class 2.
 //
 //  * the tree part (a node sees only itself and its ancestors: a handful of
 //    keys selected by a 128-bit mask) is sparse and tiny.  It is evaluated in
@@ -64,13 +65,14 @@ constexpr int kChunkTiles = 64;       // tiles whose block ids one pair of regis
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------
-// launch plan (device memory, written by tva_plan_kernel)
+// launch plan (device memory; written by tva_plan_kernel, or for batches of at most 64
+// sequences by workgroup 0 of the prefix kernel)
 //
 // A "unit" is one 32-key tile of one (sequence, kv head, row group) segment.
-// Sequences fall in three classes with separate unit spaces and kernels:
+// Sequences fall in three classes with separate unit spaces:
 //   class 0  n * G <= 32 rows: one row group, eight wavefronts share a worker's tiles
 //   class 1  33 .. 64 rows: one row group, tiles staged in LDS, two key groups of wavefronts
-//   class 2  more rows: row groups of 256 rows, four wavefronts x 64 rows per worker
+//   class 2  more rows: row groups of 256 rows, eight wavefronts x 32 rows per worker
 // ---------------------------------------------------------------------------
 struct SeqInfo {
   int32_t len;    // prefix length, clamped
@@ -724,11 +726,11 @@ __device__ inline void follow(ClassPlan& cp, const PlanView& pv, const int32_t* 
 }
 
 // One workgroup of eight wavefronts per worker (two per SIMD).  Worker w owns
-// units [w U / W, (w+1) U / W) of class 1; every piece of that range (its
+// units [w U / W, (w+1) U / W) of class 0; every piece of that range (its
 // intersection with one (sequence, kv head) segment) is cut into eight
 // contiguous sub-ranges, one per wavefront, and the eight running states are
-// folded together through LDS in three rounds, so that a piece leaves ONE
-// partial in memory however many wavefronts streamed it.
+// folded together through LDS after one barrier (fold_and_store), so that a
+// piece leaves ONE partial in memory however many wavefronts streamed it.
 constexpr int kSmallWaves = kWgWaves;
 
 __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 132 KB: eight states */) {
@@ -1609,7 +1611,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   for (int c = 1; c < kClasses; ++c)
     ws[c] = ws[c - 1] + class_slots(ctx, c - 1, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads) * class_slot(c - 1);
 
-  if (p.batch > kWave) {  // smaller batches: every wavefront derives the plan for itself
+  if (p.batch > kWave) {  // smaller batches: the prefix kernel derives the plan itself
     hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
                        p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
                        p.d_cu_nodes);
