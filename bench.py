@@ -37,7 +37,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs scaled by a plain copy of known size (see profiles/); bytes.
-MEASURED_TRAFFIC = {"cfg3a": 481.9e6}   # profiles/tva_prefix_kernel_cfg3a.md
+MEASURED_TRAFFIC = {"cfg3a": 482.0e6}   # profiles/tva_prefix_kernel_cfg3a.md
 
 
 def log(*a):
@@ -107,25 +107,16 @@ def main():
                     raise B.SmartError(rc, "smart_select_tree")
             return run
         if w.tree == "topn":
-            # per-sequence budgets: one call per sequence, outputs appended
-            one_cu = np.zeros(2, np.int32)
-            cc = [np.array([0, forest.cand_cu[b + 1] - forest.cand_cu[b]], np.int32) for b in range(Bsz)]
+            h_budgets = np.ascontiguousarray(budgets, np.int32)
+            argv = (Bsz, p(forest.cand_cu), p(forest.cand_parent), p(forest.cand_prob),
+                    p(forest.cand_token), p(cost), None, float(w.alpha), w.max_depth, int(h_budgets.max()),
+                    p(h_budgets), B.SMART_BEST_FIRST, B.SMART_DILUTION_NONE, p(cu), p(par), p(tok), p(h_cand),
+                    p(h_pp), cap, p(h_L), p(h_R))
 
             def run():
-                off = 0
-                cu[0] = 0
-                for b in range(Bsz):
-                    lo = int(forest.cand_cu[b])
-                    rc = L.smart_select_tree(
-                        1, p(cc[b]), p(forest.cand_parent[lo:]), p(forest.cand_prob[lo:]),
-                        p(forest.cand_token[lo:]), p(cost), None, float(w.alpha), w.max_depth,
-                        int(budgets[b]), B.SMART_BEST_FIRST, B.SMART_DILUTION_NONE, p(one_cu),
-                        p(par[off:]), p(tok[off:]), p(h_cand[off:]), p(h_pp[off:]), cap - off,
-                        p(h_L[b:]), p(h_R[b:]))
-                    if rc:
-                        raise B.SmartError(rc, "smart_select_tree")
-                    off += int(one_cu[1])
-                    cu[b + 1] = off
+                rc = L.smart_select_tree_budgets(*argv)
+                if rc:
+                    raise B.SmartError(rc, "smart_select_tree_budgets")
             return run
 
         fcu, fpar, ftok = W.fixed_tree(w)

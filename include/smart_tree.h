@@ -170,6 +170,22 @@ int32_t smart_select_tree(
     int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
     double* h_out_L, double* h_out_R);
 
+/* The same with a budget of its own for every sequence (Sec. 3.2 derives one
+ * per-sequence budget B = B_verify / b from the batch; a scheduler that hands
+ * sequences unequal shares of B_verify passes them here): h_budgets[batch],
+ * each in 1 .. max_budget; the cost tables are sized by max_budget
+ * (h_cost[max_budget+2], h_dcost[max_budget+1]).  Errors as above, plus
+ * SMART_EINVAL for a missing or out-of-range budget. */
+int32_t smart_select_tree_budgets(
+    int32_t batch, const int32_t* h_cand_cu, const int32_t* h_cand_parent,
+    const double* h_cand_prob, const int32_t* h_cand_token,
+    const double* h_cost, const double* h_dcost,
+    double alpha, int32_t max_depth, int32_t max_budget, const int32_t* h_budgets,
+    int32_t schedule, int32_t dilution,
+    int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
+    int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
+    double* h_out_L, double* h_out_R);
+
 /* ---------------------------------------------------------------------------
  * smart_baseline_tree (host, batched over sequences)
  *

@@ -27,7 +27,7 @@ SMART_MAX_NODES = 128
 SMART_MAX_LAYER_CAND = 2048
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
-           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
+           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
            "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
            "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
@@ -97,6 +97,9 @@ def _lib():
         lib.smart_select_tree.restype = i32
         lib.smart_select_tree.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, i32, i32,
                                           vp, vp, vp, vp, vp, i64, vp, vp]
+        lib.smart_select_tree_budgets.restype = i32
+        lib.smart_select_tree_budgets.argtypes = [i32, vp, vp, vp, vp, vp, vp, f64, i32, i32, vp, i32, i32,
+                                                  vp, vp, vp, vp, vp, i64, vp, vp]
         lib.smart_baseline_tree.restype = i32
         lib.smart_baseline_tree.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp]
         sp = ctypes.POINTER(LayerStateStruct)
@@ -150,8 +153,9 @@ def _check(code: int, what: str):
 # ---------------------------------------------------------------------------
 def smart_select_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, dcost=None, alpha=0.8,
                       max_depth=8, budget=64, schedule=SMART_BEST_FIRST,
-                      dilution=SMART_DILUTION_NONE, out_cap: Optional[int] = None):
-    """Returns dict(cu_nodes, parent, token, cand_index, pathprob, L, R) of numpy arrays."""
+                      dilution=SMART_DILUTION_NONE, out_cap: Optional[int] = None, budgets=None):
+    """Returns dict(cu_nodes, parent, token, cand_index, pathprob, L, R) of numpy arrays.
+    ``budgets``: optional per-sequence budgets (each at most ``budget``, which sizes the tables)."""
     cand_cu = np.ascontiguousarray(cand_cu, np.int32)
     cand_parent = np.ascontiguousarray(cand_parent, np.int32)
     cand_prob = np.ascontiguousarray(cand_prob, np.float64)
@@ -173,10 +177,19 @@ def smart_select_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, dcost=N
     o_L = np.zeros(max(batch, 1), np.float64)
     o_R = np.zeros(max(batch, 1), np.float64)
     p = lambda a: ctypes.c_void_p(a.ctypes.data) if a is not None else None
-    rc = _lib().smart_select_tree(batch, p(cand_cu), p(cand_parent), p(cand_prob), p(cand_token),
-                                  p(cost), p(dcost), float(alpha), int(max_depth), int(budget),
-                                  int(schedule), int(dilution), p(o_cu), p(o_parent), p(o_token),
-                                  p(o_cand), p(o_pp), cap, p(o_L), p(o_R))
+    if budgets is None:
+        rc = _lib().smart_select_tree(batch, p(cand_cu), p(cand_parent), p(cand_prob), p(cand_token),
+                                      p(cost), p(dcost), float(alpha), int(max_depth), int(budget),
+                                      int(schedule), int(dilution), p(o_cu), p(o_parent), p(o_token),
+                                      p(o_cand), p(o_pp), cap, p(o_L), p(o_R))
+    else:
+        budgets = np.ascontiguousarray(budgets, np.int32)
+        if budgets.shape[0] != batch:
+            raise ValueError("one budget per sequence")
+        rc = _lib().smart_select_tree_budgets(batch, p(cand_cu), p(cand_parent), p(cand_prob), p(cand_token),
+                                              p(cost), p(dcost), float(alpha), int(max_depth), int(budget),
+                                              p(budgets), int(schedule), int(dilution), p(o_cu), p(o_parent),
+                                              p(o_token), p(o_cand), p(o_pp), cap, p(o_L), p(o_R))
     _check(rc, "smart_select_tree")
     n = int(o_cu[-1])
     return dict(cu_nodes=o_cu, parent=o_parent[:n], token=o_token[:n], cand_index=o_cand[:n],

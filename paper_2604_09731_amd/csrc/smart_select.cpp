@@ -46,6 +46,7 @@ struct Args {
   const double* dcost;
   double alpha;
   int32_t max_depth, budget, schedule, dilution;
+  const int32_t* budgets;  // per sequence, or nullptr: `budget` for all
 };
 
 // Per-thread scratch reused across sequences and calls (no allocation in steady state).
@@ -117,6 +118,7 @@ inline bool keep(double alpha, double benefit, double dC, double L, double cost_
 }
 
 void select_one(const Args& a, int b, SeqResult* out, Scratch& sc) {
+  const int budget = a.budgets ? a.budgets[b] : a.budget;
   const int lo = a.cand_cu[b], hi = a.cand_cu[b + 1];
   const int C = hi - lo;
   const int32_t* cpar = a.cand_parent + lo;
@@ -195,7 +197,7 @@ void select_one(const Args& a, int b, SeqResult* out, Scratch& sc) {
     push_children(0);
     while (!heap.empty()) {
       const int n = (int)out->parent.size();
-      if (n >= a.budget) break;
+      if (n >= budget) break;
       const int u = heap.front();
       double L, paths;
       st.current(&L, &paths);
@@ -211,7 +213,7 @@ void select_one(const Args& a, int b, SeqResult* out, Scratch& sc) {
     active.assign(1, 0);
     for (int layer = 1; layer <= a.max_depth; ++layer) {
       const int n = (int)out->parent.size();
-      if (n >= a.budget) break;
+      if (n >= budget) break;
       double L, paths;
       st.current(&L, &paths);
       const double dC = dC_of(n), cost_n = a.cost[n];
@@ -224,7 +226,7 @@ void select_one(const Args& a, int b, SeqResult* out, Scratch& sc) {
           const double benefit = a.dilution == SMART_DILUTION_NONE ? P[u] : P[u] / paths;
           if (keep(a.alpha, benefit, dC, L, cost_n)) survivors.push_back(u);
         }
-      const int room = a.budget - n;
+      const int room = budget - n;
       if ((int)survivors.size() > room) {
         std::sort(survivors.begin(), survivors.end(),
                   [&](int x, int y) { return P[x] > P[y] || (P[x] == P[y] && x < y); });
@@ -323,11 +325,11 @@ class Pool {
 
 }  // namespace
 
-extern "C" int32_t smart_select_tree(
+static int32_t select_batch(
     int32_t batch, const int32_t* h_cand_cu, const int32_t* h_cand_parent,
     const double* h_cand_prob, const int32_t* h_cand_token,
     const double* h_cost, const double* h_dcost,
-    double alpha, int32_t max_depth, int32_t budget, int32_t schedule, int32_t dilution,
+    double alpha, int32_t max_depth, int32_t budget, const int32_t* h_budgets, int32_t schedule, int32_t dilution,
     int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
     int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
     double* h_out_L, double* h_out_R) {
@@ -340,12 +342,15 @@ extern "C" int32_t smart_select_tree(
   if (schedule != SMART_BEST_FIRST && schedule != SMART_LAYERWISE) return SMART_EINVAL;
   if (dilution != SMART_DILUTION_NONE && dilution != SMART_DILUTION_PATH_MEAN) return SMART_EINVAL;
   if (out_cap < 0) return SMART_EINVAL;
+  if (h_budgets)
+    for (int b = 0; b < batch; ++b)
+      if (h_budgets[b] < 1 || h_budgets[b] > budget) return SMART_EINVAL;
   if (h_cand_cu[0] != 0) return SMART_ETREE;
   for (int b = 0; b < batch; ++b)
     if (h_cand_cu[b + 1] <= h_cand_cu[b]) return SMART_ETREE;
 
   const Args a{h_cand_cu, h_cand_parent, h_cand_prob, h_cand_token, h_cost, h_dcost,
-               alpha, max_depth, budget, schedule, dilution};
+               alpha, max_depth, budget, schedule, dilution, h_budgets};
   static thread_local std::vector<SeqResult> res;
   if ((int)res.size() < batch) res.resize(batch);
   if (batch < 8) {
@@ -375,6 +380,33 @@ extern "C" int32_t smart_select_tree(
     h_out_R[b] = r.R;
   }
   return SMART_OK;
+}
+
+extern "C" int32_t smart_select_tree(
+    int32_t batch, const int32_t* h_cand_cu, const int32_t* h_cand_parent,
+    const double* h_cand_prob, const int32_t* h_cand_token,
+    const double* h_cost, const double* h_dcost,
+    double alpha, int32_t max_depth, int32_t budget, int32_t schedule, int32_t dilution,
+    int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
+    int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
+    double* h_out_L, double* h_out_R) {
+  return select_batch(batch, h_cand_cu, h_cand_parent, h_cand_prob, h_cand_token, h_cost, h_dcost, alpha, max_depth,
+                      budget, nullptr, schedule, dilution, h_out_cu, h_out_parent, h_out_token, h_out_cand_index,
+                      h_out_pathprob, out_cap, h_out_L, h_out_R);
+}
+
+extern "C" int32_t smart_select_tree_budgets(
+    int32_t batch, const int32_t* h_cand_cu, const int32_t* h_cand_parent,
+    const double* h_cand_prob, const int32_t* h_cand_token,
+    const double* h_cost, const double* h_dcost,
+    double alpha, int32_t max_depth, int32_t max_budget, const int32_t* h_budgets, int32_t schedule,
+    int32_t dilution, int32_t* h_out_cu, int32_t* h_out_parent, int32_t* h_out_token,
+    int32_t* h_out_cand_index, double* h_out_pathprob, int64_t out_cap,
+    double* h_out_L, double* h_out_R) {
+  if (batch > 0 && !h_budgets) return SMART_EINVAL;
+  return select_batch(batch, h_cand_cu, h_cand_parent, h_cand_prob, h_cand_token, h_cost, h_dcost, alpha, max_depth,
+                      max_budget, h_budgets, schedule, dilution, h_out_cu, h_out_parent, h_out_token,
+                      h_out_cand_index, h_out_pathprob, out_cap, h_out_L, h_out_R);
 }
 
 // ---------------------------------------------------------------------------

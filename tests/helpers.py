@@ -43,18 +43,9 @@ def trees_from_library(w: W.Workload, forest=None):
                                 budget=w.budget)
         return r["cu_nodes"], r["parent"], r["token"], r["cand_index"]
     budgets = W.topn_budgets(w)
-    cu, parent, token, cand = [0], [], [], []
-    for b in range(w.batch):
-        lo, hi = int(forest.cand_cu[b]), int(forest.cand_cu[b + 1])
-        r = B.smart_select_tree(np.array([0, hi - lo], np.int32), forest.cand_parent[lo:hi],
-                                forest.cand_prob[lo:hi], forest.cand_token[lo:hi], cost,
-                                alpha=w.alpha, max_depth=w.max_depth, budget=int(budgets[b]))
-        parent += r["parent"].tolist()
-        token += r["token"].tolist()
-        cand += r["cand_index"].tolist()
-        cu.append(len(parent))
-    return (np.array(cu, np.int32), np.array(parent, np.int32), np.array(token, np.int32),
-            np.array(cand, np.int32))
+    r = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost,
+                            alpha=w.alpha, max_depth=w.max_depth, budget=int(budgets.max()), budgets=budgets)
+    return r["cu_nodes"], r["parent"], r["token"], r["cand_index"]
 
 
 def torch_elems(arr: np.ndarray, dtype: str, device):

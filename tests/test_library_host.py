@@ -383,3 +383,26 @@ def test_baseline_policy_error_paths():
         with pytest.raises(B.SmartError) as e:
             B.smart_baseline_tree(**kw)
         assert e.value.code == code, bad
+
+
+def test_per_sequence_budgets_equal_one_call_per_sequence():
+    w = W.WORKLOADS["cfg3b"].scaled(batch=12)
+    f = W.make_forest(w)
+    cost = W.cost_table(w)
+    budgets = W.topn_budgets(w)
+    assert len(set(budgets.tolist())) > 3
+    for schedule in (B.SMART_BEST_FIRST, B.SMART_LAYERWISE):
+        r = B.smart_select_tree(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, alpha=w.alpha,
+                                max_depth=w.max_depth, budget=int(budgets.max()), budgets=budgets, schedule=schedule)
+        for b in range(w.batch):
+            lo, hi = int(f.cand_cu[b]), int(f.cand_cu[b + 1])
+            t = S.select_tree(f.cand_parent[lo:hi].tolist(), f.cand_prob[lo:hi].tolist(), f.cand_token[lo:hi].tolist(),
+                              cost, alpha=w.alpha, max_depth=w.max_depth, budget=int(budgets[b]), schedule=schedule)
+            a, e = int(r["cu_nodes"][b]), int(r["cu_nodes"][b + 1])
+            assert r["cand_index"][a:e].tolist() == t.cand_index and r["parent"][a:e].tolist() == t.parent
+            assert r["L"][b] == t.L and r["R"][b] == t.R
+    for bad in ([0] + [4] * 11, [4] * 11 + [int(budgets.max()) + 1]):
+        with pytest.raises(B.SmartError) as e:
+            B.smart_select_tree(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, budget=int(budgets.max()),
+                                budgets=bad)
+        assert e.value.code == B.SMART_EINVAL
