@@ -23,6 +23,8 @@
  *                          prefix, Sec. 3.1 below Eq. "cum_prob")
  *   tree_rope              rotates the tree's queries and keys by their position
  *                          ids (for rotary-embedding target models)
+ *   tree_accept_sample     temperature-1 (sampling) verification, lossless for
+ *                          deterministic proposals
  *   kv_cache_write         writes token K/V rows into the paged cache in the
  *                          layout tree_verify_attention streams fastest
  *   tree_commit            appends the accepted path's K/V rows to the cache and
@@ -511,6 +513,43 @@ int32_t tree_accept(smart_ctx* ctx, void* stream, int32_t batch, int32_t max_dep
                     const int32_t* d_cu_nodes, const int32_t* d_parent, const int32_t* d_token,
                     const int32_t* d_target_next,
                     int32_t* d_accept_len, int32_t* d_accept_path, int32_t* d_bonus_token);
+
+/* ---------------------------------------------------------------------------
+ * tree_accept_sample (device)
+ *
+ * Temperature-1 verification (the paper evaluates at temperatures 0 and 1 and
+ * relies on verification being lossless, Sec. 4) for trees whose children are
+ * deterministic proposals, as the tree drafters the paper builds on produce
+ * them.  d_target_prob[i][0..vocab) is the distribution the target model
+ * assigns after node i (binary32, row stride prob_row_stride elements).  Per
+ * sequence, from the root: the current node's children are visited in node
+ * order; a child proposing token x is accepted with probability
+ * p(x) / (mass not yet rejected at this node), a rejected token's mass is
+ * removed (a later sibling with the same token, or a token outside the
+ * vocabulary, is skipped); the walk descends into an accepted child and stops
+ * when no child is accepted or max_depth drafts are.  The bonus token is drawn
+ * from what is left of the last node's distribution; every emitted token is
+ * then distributed exactly as the target's.
+ * Arithmetic is on integers: w(x) = floor(p(x) 2^32) (NaN and negatives count
+ * 0, values above 1 count 1), with a 64-bit draw r and remaining weight R a
+ * child is accepted iff floor(r R / 2^64) < w(x), and the bonus token is the
+ * first index whose running weight sum exceeds floor(r R / 2^64).  Draws are
+ * Philox-4x32-10 with counter (draw index within the sequence's step, step
+ * low, step high, sequence index) and key (seed low, seed high); a draw is the
+ * first two output words, low word first.  Results therefore depend only on
+ * (seed, step, sequence index) and the inputs, bit for bit.
+ * Outputs as tree_accept; d_bonus_token[b] = -1 if no weight is left.
+ * Sequences with no node, more than SMART_MAX_NODES nodes or offsets outside
+ * [0, total_nodes] get accept_len -1.
+ * Host errors: SMART_EINVAL (null pointers, negative sizes, vocab < 1,
+ * prob_row_stride < vocab, max_depth > SMART_MAX_NODES).
+ * ------------------------------------------------------------------------- */
+int32_t tree_accept_sample(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nodes,
+                           int32_t max_depth, int32_t vocab,
+                           const int32_t* d_cu_nodes, const int32_t* d_parent, const int32_t* d_token,
+                           const float* d_target_prob, int64_t prob_row_stride,
+                           uint64_t seed, uint64_t step,
+                           int32_t* d_accept_len, int32_t* d_accept_path, int32_t* d_bonus_token);
 
 /* ---------------------------------------------------------------------------
  * tree_commit (device)

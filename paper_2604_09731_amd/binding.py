@@ -30,7 +30,7 @@ EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_dest
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
            "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
-           "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_commit"]
+           "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_accept_sample", "tree_commit"]
 
 
 class SmartError(RuntimeError):
@@ -133,6 +133,9 @@ def _lib():
         lib.tree_commit.restype = i32
         lib.tree_commit.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp,
                                     vp, vp, i64, i64, i64, vp, vp]
+        lib.tree_accept_sample.restype = i32
+        lib.tree_accept_sample.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, i64, ctypes.c_uint64,
+                                           ctypes.c_uint64, vp, vp, vp]
         lib.tree_accept.restype = i32
         lib.tree_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         _libh = lib
@@ -547,6 +550,23 @@ class SmartTree:
                                 _ptr(token), _ptr(target_next), _ptr(accept_len), _ptr(accept_path),
                                 _ptr(bonus))
         _check(rc, "tree_accept")
+        return accept_len, accept_path, bonus
+
+    # -- tree_accept_sample ------------------------------------------------
+    def tree_accept_sample(self, cu_nodes, parent, token, target_prob, max_depth, seed, step):
+        """Temperature-1 verification; target_prob [N, V] float32 (rows may be strided)."""
+        torch = _torch()
+        B = cu_nodes.shape[0] - 1
+        dev = cu_nodes.device
+        N, V = target_prob.shape
+        assert target_prob.dtype == torch.float32 and target_prob.stride(1) == 1
+        accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+        accept_path = torch.empty((B, max_depth + 1), dtype=torch.int32, device=dev)
+        bonus = torch.empty(B, dtype=torch.int32, device=dev)
+        rc = _lib().tree_accept_sample(self._h, _stream_ptr(), B, N, max_depth, V, _ptr(cu_nodes), _ptr(parent),
+                                       _ptr(token), _ptr(target_prob), target_prob.stride(0), int(seed), int(step),
+                                       _ptr(accept_len), _ptr(accept_path), _ptr(bonus))
+        _check(rc, "tree_accept_sample")
         return accept_len, accept_path, bonus
 
     # -- tree_commit -------------------------------------------------------
