@@ -51,6 +51,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg3a")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--accept", choices=["greedy", "sample"], default="greedy",
+                    help="greedy: the longest-accepted-path walk (the headline step); sample: temperature-1 "
+                         "verification over synthetic target distributions of --vocab tokens")
+    ap.add_argument("--vocab", type=int, default=128256)
     ap.add_argument("--workers", type=int, default=0, help="override the number of split-KV workers (0 = automatic)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -162,6 +166,14 @@ def main():
     accept_len = torch.empty(Bsz, dtype=torch.int32, device=dev)
     accept_path = torch.empty((Bsz, w.max_depth + 1), dtype=torch.int32, device=dev)
     bonus = torch.empty(Bsz, dtype=torch.int32, device=dev)
+    target_prob = None
+    if args.accept == "sample":
+        # synthetic target distributions: half of the mass on the token the greedy target would pick, the
+        # rest a softmax of N(0, 3^2) logits over the vocabulary
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed + 2)
+        target_prob = torch.softmax(torch.randn((N, args.vocab), device=dev, generator=gen) * 3.0, dim=1) * 0.5
+        target_prob[torch.arange(N, device=dev), target_next.long() % args.vocab] += 0.5
     if args.workers:
         lib.set_option(B.SMART_OPT_TVA_WORKERS, args.workers)
     lib.reserve(Bsz, cap, w.num_q_heads, w.num_kv_heads)
@@ -197,8 +209,12 @@ def main():
         P.h_cu_nodes = stage_np[ds_index][:Bsz + 1].ctypes.data   # selection wrote it on the host
         acc_args = (ctx, stream, Bsz, w.max_depth, vp(d_cu), vp(d_par), vp(d_tok), vp(target_next),
                     vp(accept_len), vp(accept_path), vp(bonus))
+        if target_prob is not None:
+            acc_args = (ctx, stream, Bsz, N, w.max_depth, args.vocab, vp(d_cu), vp(d_par), vp(d_tok),
+                        vp(target_prob), target_prob.stride(0), w.seed, 0, vp(accept_len), vp(accept_path), vp(bonus))
         return pack_args, P, acc_args
 
+    accept_call = L.tree_accept if target_prob is None else L.tree_accept_sample
     calls = [device_calls(d_stage[0], 0), device_calls(d_stage[1], 1)]
     hp = lambda t, off: ctypes.c_void_p(t.data_ptr() + 4 * off)
     upload_pack_args = [(ctx, stream, Bsz, N, hp(stage[i], 0), hp(stage[i], Bsz + 1), hp(stage[i], Bsz + 1 + cap),
@@ -211,7 +227,7 @@ def main():
         _, P, acc_args = calls[s]
         rc = L.tree_upload_pack(*upload_pack_args[s])            # tree CSR to the GPU + a2, one launch
         rc = rc or L.tree_verify_attention(ctx, stream, ctypes.byref(P))   # a3 + a4
-        rc = rc or L.tree_accept(*acc_args)                      # a5
+        rc = rc or accept_call(*acc_args)                        # a5
         if rc:
             raise B.SmartError(rc, "verify step")
 
@@ -266,7 +282,7 @@ def main():
     pack_args, P, acc_args = calls[0]
     att_us = time_device(lambda: L.tree_verify_attention(ctx, stream, ctypes.byref(P)))
     pack_us = time_device(lambda: L.tree_upload_pack(*upload_pack_args[0]))
-    acc_us = time_device(lambda: L.tree_accept(*acc_args))
+    acc_us = time_device(lambda: accept_call(*acc_args))
     th0 = time.perf_counter()
     for _ in range(50):
         select[0]()
@@ -307,9 +323,10 @@ def main():
                    "tree_nodes_min_median_max": [int(sizes.min()), int(np.median(sizes)), int(sizes.max())],
                    "prefix_len_min_max": [int(inp.prefix_len.min()), int(inp.prefix_len.max())],
                    "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
-                   "block_size": 16, "kv_layout": "interleaved"},
+                   "block_size": 16, "kv_layout": "interleaved", "accept": args.accept,
+                   **({"vocab": args.vocab} if args.accept == "sample" else {})},
         "breakdown_us": {"select_host": round(sel_us, 1), "tree_upload_pack": round(pack_us, 2),
-                         "tree_verify_attention": round(att_us, 2), "tree_accept": round(acc_us, 2)},
+                         "tree_verify_attention": round(att_us, 2), ("tree_accept" if args.accept == "greedy" else "tree_accept_sample"): round(acc_us, 2)},
         "attended_tokens_per_s": round(work["attended_tokens"] / (att_us * 1e-6), 1),
         "attention_tflops": round(tflops, 2),
         "attention_mfma_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),

@@ -14,18 +14,20 @@
 // sum exceeds mulhi(r, R).  Draws are Philox-4x32-10 (Salmon et al., SC 2011) with counter
 // (draw index, step low, step high, sequence) and key (seed low, seed high).
 //
-// One workgroup of 16 wavefronts per sequence.  Per visited node the workgroup streams that
-// node's row of the target distribution once (wavefront k owns a contiguous range of the
-// vocabulary and sums its weights); one thread then walks the children (a handful of gathers
-// from the row just read); the bonus draw picks the wavefront whose range holds the target
-// weight, and that wavefront rescans its range with a lane scan per 64 tokens.
+// Two launches.  A single compute unit pulls only a few tens of GB/s by itself, so the rows of
+// the target distribution are not streamed by the workgroup that walks a sequence: first
+// every row of the batch is summed by many small workgroups at once (64 contiguous ranges per
+// row, the weight sum of each kept in the context's workspace: 512 bytes a row); then one
+// wavefront per sequence walks its tree with nothing but gathers -- a node's total is the sum of
+// its 64 range sums (one per lane), the weights of all its children's tokens arrive in the same
+// round trip -- and finds the bonus token by a lane scan over the range sums followed by a
+// rescan of the single range (1/64 of a row) that holds the target weight.
 #include "common.h"
 
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kWaves = 16;
-constexpr int kThreads = kWave * kWaves;
+constexpr int kRanges = 64;  // ranges a row is cut into: one per lane of the walking wavefront
 
 __device__ inline uint64_t weight_of(float p) {
   if (!(p > 0.f)) return 0;  // NaN, zero, negative
@@ -59,55 +61,48 @@ __device__ inline uint64_t wave_sum(uint64_t v) {
   return v;
 }
 
-__global__ __launch_bounds__(kThreads) void tree_accept_sample_kernel(
-    int batch, int total_nodes, int max_depth, int V, int64_t stride, const int32_t* __restrict__ cu_nodes,
-    const int32_t* __restrict__ parent, const int32_t* __restrict__ token, const float* __restrict__ prob,
-    uint64_t seed, uint64_t step, int32_t* __restrict__ accept_len, int32_t* __restrict__ accept_path,
-    int32_t* __restrict__ bonus_token) {
-  __shared__ int32_t sPar[SMART_MAX_NODES], sTok[SMART_MAX_NODES], sRej[SMART_MAX_NODES];
-  __shared__ uint64_t sWave[kWaves];
-  __shared__ uint64_t sRem, sTarget;
-  __shared__ int32_t sNext, sNRej, sTargetWave;
-  const int b = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
-  if (b >= batch) return;
-  const int base = cu_nodes[b];
-  const int n = cu_nodes[b + 1] - base;
-  int32_t* path = accept_path + (size_t)b * (max_depth + 1);
-  for (int d = tid; d <= max_depth; d += kThreads) path[d] = d == 0 ? 0 : -1;
-  if (base < 0 || n < 1 || n > SMART_MAX_NODES || base + n > total_nodes) {
-    if (tid == 0) {
-      path[0] = -1;
-      accept_len[b] = -1;
-      bonus_token[b] = -1;
-    }
-    return;
+__device__ inline uint64_t wave_incl_scan(uint64_t v, int lane) {
+  for (int sh = 1; sh < kWave; sh <<= 1) {
+    const uint64_t up = __shfl_up(v, sh);
+    if (lane >= sh) v += up;
   }
-  for (int i = tid; i < n; i += kThreads) {
-    sPar[i] = parent[base + i];
-    sTok[i] = token[base + i];
-  }
-  // wavefront k owns tokens [k range, (k + 1) range) of the vocabulary
-  const int range = ((V + kWaves - 1) / kWaves + 4 * kWave - 1) / (4 * kWave) * (4 * kWave);
-  // 16-byte loads when every row starts on a 16-byte boundary
+  return v;
+}
+
+// Tokens per range: a 64th of the vocabulary, rounded up to whole 16-byte vectors.
+__host__ __device__ inline int range_of(int V) { return ((V + kRanges - 1) / kRanges + 3) / 4 * 4; }
+
+// Weight sums of the 64 ranges of every row.  Workgroup (row, quarter): four wavefronts, each
+// sums four consecutive ranges, one after the other, with all of a range's loads in flight.
+__global__ __launch_bounds__(4 * kWave) void range_sums_kernel(int total_nodes, int V, int64_t stride,
+                                                               const float* __restrict__ prob,
+                                                               uint64_t* __restrict__ sums) {
+  const int node = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+  if (node >= total_nodes) return;
+  const int range = range_of(V);
   const bool vec = (stride % 4 == 0) && (((uintptr_t)prob & 15u) == 0);
-  const int v_begin = wv * range < V ? wv * range : V;
-  const int v_end = (wv + 1) * range < V ? (wv + 1) * range : V;
-  int cur = 0, len = 0;
-  uint32_t draw = 0;  // (only thread 0's copy is used)
-  const float* row = prob;
-  __syncthreads();
-  for (;;) {
-    row = prob + (size_t)(base + cur) * stride;
+  const float* row = prob + (size_t)node * stride;
+  for (int k = 0; k < 4; ++k) {
+    const int rg = blockIdx.y * 16 + wv * 4 + k;
+    const int v_begin = rg * range < V ? rg * range : V;
+    const int v_end = (rg + 1) * range < V ? (rg + 1) * range : V;
     uint64_t acc = 0;
     if (vec) {
-#pragma unroll 4
-      for (int v = v_begin + 4 * lane; v < v_end; v += 4 * kWave) {
-        if (v + 3 < v_end) {
-          const float4 x = *reinterpret_cast<const float4*>(row + v);
-          acc += weight_of(x.x) + weight_of(x.y) + weight_of(x.z) + weight_of(x.w);
-        } else {
-          for (int i = 0; v + i < v_end; ++i) acc += weight_of(row[v + i]);
+      constexpr int kInFlight = 8;
+      for (int v0 = v_begin + 4 * lane; v0 < v_end; v0 += 4 * kWave * kInFlight) {
+        float4 x[kInFlight];
+#pragma unroll
+        for (int i = 0; i < kInFlight; ++i) {
+          const int v = v0 + i * 4 * kWave;
+          x[i] = v + 3 < v_end ? *reinterpret_cast<const float4*>(row + v) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < kInFlight; ++i) {
+          const int v = v0 + i * 4 * kWave;
+          acc += weight_of(x[i].x) + weight_of(x[i].y) + weight_of(x[i].z) + weight_of(x[i].w);
+          if (v < v_end && v + 3 >= v_end)  // the ragged end of the vocabulary
+            for (int e = 0; v + e < v_end; ++e) acc += weight_of(row[v + e]);
         }
       }
     } else {
@@ -115,100 +110,161 @@ __global__ __launch_bounds__(kThreads) void tree_accept_sample_kernel(
       for (int v = v_begin + lane; v < v_end; v += kWave) acc += weight_of(row[v]);
     }
     acc = wave_sum(acc);
-    if (lane == 0) sWave[wv] = acc;
-    __syncthreads();
-    if (tid == 0) {
-      uint64_t R = 0;
-      for (int k = 0; k < kWaves; ++k) R += sWave[k];
-      int nrej = 0, nxt = -1;
-      if (len < max_depth) {
-        for (int c = cur + 1; c < n; ++c) {
-          if (sPar[c] != cur) continue;
-          const int x = sTok[c];
-          if (x < 0 || x >= V) continue;
-          bool gone = false;  // an earlier sibling proposed the same token and was rejected
-          for (int i = 0; i < nrej; ++i) gone = gone || sRej[i] == x;
-          if (gone) continue;
-          const uint64_t wx = weight_of(row[x]);
-          const uint64_t r = rand64(seed, step, (uint32_t)b, draw++);
-          if (R > 0 && __umul64hi(r, R) < wx) {
-            nxt = c;
-            break;
-          }
-          R -= wx;
-          sWave[x / range] -= wx;
-          sRej[nrej++] = x;
-        }
-      }
-      sNext = nxt;
-      if (nxt < 0) {
-        // the step ends here: place the bonus draw in the wavefront ranges
-        sNRej = nrej;
-        sRem = R;
-        uint64_t T = R > 0 ? __umul64hi(rand64(seed, step, (uint32_t)b, draw++), R) : 0;
-        int k = 0;
-        while (k < kWaves - 1 && T >= sWave[k]) T -= sWave[k++];
-        sTargetWave = k;
-        sTarget = T;
-      }
-    }
-    __syncthreads();
-    const int nxt = sNext;
-    if (nxt < 0) break;
-    cur = nxt;
-    ++len;
-    if (tid == 0) path[len] = cur;
-    __syncthreads();  // everyone has read this round's decision before the next one is written
+    if (lane == 0) sums[(size_t)node * kRanges + rg] = acc;
   }
-  if (sRem == 0) {
-    if (tid == 0) {
-      accept_len[b] = len;
+}
+
+// The walk: one wavefront per sequence, lane l owns range l of the current row.
+__global__ __launch_bounds__(kWave) void tree_accept_sample_kernel(
+    int batch, int total_nodes, int max_depth, int V, int64_t stride, const int32_t* __restrict__ cu_nodes,
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ token, const float* __restrict__ prob,
+    const uint64_t* __restrict__ sums, uint64_t seed, uint64_t step, int32_t* __restrict__ accept_len,
+    int32_t* __restrict__ accept_path, int32_t* __restrict__ bonus_token) {
+  __shared__ int32_t sRej[SMART_MAX_NODES];
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (b >= batch) return;
+  const int base = cu_nodes[b];
+  const int n = cu_nodes[b + 1] - base;
+  int32_t* path = accept_path + (size_t)b * (max_depth + 1);
+  for (int d = lane; d <= max_depth; d += kWave) path[d] = d == 0 ? 0 : -1;
+  if (base < 0 || n < 1 || n > SMART_MAX_NODES || base + n > total_nodes) {
+    if (lane == 0) {
+      path[0] = -1;
+      accept_len[b] = -1;
       bonus_token[b] = -1;
     }
     return;
   }
-  if (wv != sTargetWave) return;
-  // first token of this wavefront's range whose running weight sum exceeds the target
-  const uint64_t T = sTarget;
-  const int nrej = sNRej;
-  uint64_t running = 0;
-  int found = -1;
-  for (int v0 = v_begin; v0 < v_end && found < 0; v0 += kWave) {
-    const int v = v0 + lane;
-    uint64_t w = v < v_end ? weight_of(row[v]) : 0;
-    if (w != 0)
-      for (int i = 0; i < nrej; ++i)
-        if (sRej[i] == v) w = 0;
-    uint64_t incl = w;
-    for (int sh = 1; sh < kWave; sh <<= 1) {
-      const uint64_t up = __shfl_up(incl, sh);
-      if (lane >= sh) incl += up;
+  // this lane's two nodes
+  const int c0 = lane, c1 = lane + kWave;
+  const int p0 = c0 < n ? parent[base + c0] : -2, x0 = c0 < n ? token[base + c0] : -1;
+  const int p1 = c1 < n ? parent[base + c1] : -2, x1 = c1 < n ? token[base + c1] : -1;
+  const int range = range_of(V);
+  int cur = 0, len = 0, nrej = 0;
+  uint32_t draw = 0;
+  const float* row;
+  uint64_t mine, R;  // this lane's range sum (less what was rejected in it), and the row's remaining weight
+  for (;;) {
+    row = prob + (size_t)(base + cur) * stride;
+    mine = sums[(size_t)(base + cur) * kRanges + lane];
+    // candidates: children of `cur` whose token lies in the vocabulary; their weights come with the same trip
+    const bool cand0 = p0 == cur && c0 > cur && x0 >= 0 && x0 < V && len < max_depth;
+    const bool cand1 = p1 == cur && c1 > cur && x1 >= 0 && x1 < V && len < max_depth;
+    const uint64_t w0 = cand0 ? weight_of(row[x0]) : 0;
+    const uint64_t w1 = cand1 ? weight_of(row[x1]) : 0;
+    R = wave_sum(mine);
+    nrej = 0;
+    int nxt = -1;
+    for (int half = 0; half < 2 && nxt < 0; ++half) {
+      uint64_t m = __ballot(half ? cand1 : cand0);
+      while (m) {  // children in node order; everything in here is wave-uniform
+        const int l = __ffsll((unsigned long long)m) - 1;
+        m &= m - 1;
+        const int xc = __shfl(half ? x1 : x0, l);
+        const uint64_t wc = __shfl(half ? w1 : w0, l);
+        bool gone = false;  // an earlier sibling proposed the same token and was rejected
+        for (int i = 0; i < nrej; ++i) gone = gone || sRej[i] == xc;
+        if (gone) continue;
+        const uint64_t r = rand64(seed, step, (uint32_t)b, draw++);
+        if (R > 0 && __umul64hi(r, R) < wc) {
+          nxt = l + kWave * half;
+          break;
+        }
+        R -= wc;
+        if (lane == xc / range) mine -= wc;
+        if (lane == 0) sRej[nrej] = xc;
+        ++nrej;
+      }
     }
-    const uint64_t hit = __ballot(running + incl > T);
-    if (hit) found = v0 + __ffsll((unsigned long long)hit) - 1;
-    running += __shfl(incl, kWave - 1);
+    if (nxt < 0) break;
+    cur = nxt;
+    ++len;
+    if (lane == 0) path[len] = cur;
   }
-  if (lane == 0) {
-    accept_len[b] = len;
-    bonus_token[b] = found;  // (always found: the target is below this range's remaining weight)
+  if (lane == 0) accept_len[b] = len;
+  if (R == 0) {
+    if (lane == 0) bonus_token[b] = -1;
+    return;
   }
+  // bonus: first token whose running weight sum (rejected tokens left out) exceeds the target
+  uint64_t T = __umul64hi(rand64(seed, step, (uint32_t)b, draw++), R);
+  const uint64_t incl = wave_incl_scan(mine, lane);
+  const uint64_t hit = __ballot(incl > T);  // never empty: T < R = the last lane's inclusive sum
+  const int rg = __ffsll((unsigned long long)hit) - 1;
+  T -= __shfl(incl - mine, rg);  // the target inside range rg
+  // Range rg is gone through in pieces of 64 x 32 tokens: a lane takes 32 consecutive tokens (one
+  // 128-byte line, all of its loads in flight at once), sums them, a lane scan finds the lane whose
+  // run holds the target, and that lane goes through its run once more, out of registers.
+  const int v_begin = rg * range, v_end = (rg + 1) * range < V ? (rg + 1) * range : V;
+  constexpr int kRun = 32;
+  int found = -1;
+  for (int vb = v_begin; vb < v_end && found < 0; vb += kWave * kRun) {
+    const int my_begin = vb + lane * kRun;
+    float x[kRun];
+#pragma unroll
+    for (int k = 0; k < kRun; ++k) x[k] = my_begin + k < v_end ? row[my_begin + k] : 0.f;
+    uint64_t w[kRun], run_sum = 0;
+#pragma unroll
+    for (int k = 0; k < kRun; ++k) {
+      w[k] = weight_of(x[k]);
+      if (w[k] != 0)
+        for (int i = 0; i < nrej; ++i)
+          if (sRej[i] == my_begin + k) w[k] = 0;
+      run_sum += w[k];
+    }
+    const uint64_t run_incl = wave_incl_scan(run_sum, lane);
+    const uint64_t piece = __shfl(run_incl, kWave - 1);
+    if (piece <= T) {  // the target lies further on
+      T -= piece;
+      continue;
+    }
+    const uint64_t run_hit = __ballot(run_incl > T);
+    const int owner = __ffsll((unsigned long long)run_hit) - 1;
+    const uint64_t t_run = T - __shfl(run_incl - run_sum, owner);
+    uint64_t acc = 0;
+    int mine_found = -1;  // (only the owner's is meaningful)
+#pragma unroll
+    for (int k = 0; k < kRun; ++k) {
+      acc += w[k];
+      if (mine_found < 0 && acc > t_run) mine_found = my_begin + k;
+    }
+    found = __shfl(mine_found, owner);
+  }
+  if (lane == 0) bonus_token[b] = found;
 }
 
 }  // namespace
 
 extern "C" int32_t tree_accept_sample(smart_ctx* ctx, void* stream, int32_t batch, int32_t total_nodes,
-                                      int32_t max_depth, int32_t vocab, const int32_t* d_cu_nodes, const int32_t* d_parent,
-                                      const int32_t* d_token, const float* d_target_prob, int64_t prob_row_stride,
-                                      uint64_t seed, uint64_t step, int32_t* d_accept_len,
+                                      int32_t max_depth, int32_t vocab, const int32_t* d_cu_nodes,
+                                      const int32_t* d_parent, const int32_t* d_token, const float* d_target_prob,
+                                      int64_t prob_row_stride, uint64_t seed, uint64_t step, int32_t* d_accept_len,
                                       int32_t* d_accept_path, int32_t* d_bonus_token) {
   if (!ctx || batch < 0 || total_nodes < 0 || max_depth < 0 || max_depth > SMART_MAX_NODES) return SMART_EINVAL;
   if (vocab < 1 || prob_row_stride < vocab) return SMART_EINVAL;
   if (!d_cu_nodes || !d_parent || !d_token || !d_target_prob || !d_accept_len || !d_accept_path || !d_bonus_token)
     return SMART_EINVAL;
   if (batch == 0) return SMART_OK;
-  hipLaunchKernelGGL(tree_accept_sample_kernel, dim3(batch), dim3(kThreads), 0, (hipStream_t)stream, batch, total_nodes,
-                     max_depth, vocab, prob_row_stride, d_cu_nodes, d_parent, d_token, d_target_prob, seed, step, d_accept_len,
-                     d_accept_path, d_bonus_token);
-  SMART_HIP_CHECK(hipGetLastError());
-  return SMART_OK;
+  int prev = 0;
+  SMART_HIP_CHECK(hipGetDevice(&prev));
+  if (prev != ctx->device) SMART_HIP_CHECK(hipSetDevice(ctx->device));
+  const size_t need = (size_t)(total_nodes > 0 ? total_nodes : 1) * kRanges * sizeof(uint64_t);
+  int32_t rc = smart::ensure_workspace(ctx, (hipStream_t)stream, need, 0);
+  if (rc == SMART_OK) {
+    uint64_t* sums = (uint64_t*)ctx->ws;
+    if (total_nodes > 0)
+      hipLaunchKernelGGL(range_sums_kernel, dim3(total_nodes, 4), dim3(4 * kWave), 0, (hipStream_t)stream, total_nodes,
+                         vocab, prob_row_stride, d_target_prob, sums);
+    hipLaunchKernelGGL(tree_accept_sample_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch, total_nodes,
+                       max_depth, vocab, prob_row_stride, d_cu_nodes, d_parent, d_token, d_target_prob, sums, seed,
+                       step, d_accept_len, d_accept_path, d_bonus_token);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+      smart::set_last_hip_error(e);
+      rc = SMART_EHIP;
+    }
+  }
+  if (prev != ctx->device) (void)hipSetDevice(prev);
+  return rc;
 }
