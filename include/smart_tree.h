@@ -70,6 +70,9 @@ enum {
 };
 
 enum { SMART_F32 = 0, SMART_BF16 = 1 };
+/* Element type of an fp8 KV cache (cache only; q, tree k / v and outputs stay SMART_F32 / SMART_BF16):
+ * E4M3 of the OCP 8-bit floating point specification (bias 7, no infinities, largest value 448). */
+enum { SMART_FP8_E4M3 = 2 };
 
 /* Paged KV-cache layouts.  A page is the block_size x head_dim elements of one
  * (physical block, kv head); pages are addressed by block_stride / head_stride
@@ -443,6 +446,27 @@ int32_t kv_cache_write(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_l
                        int64_t cache_token_stride /* PLAIN only */);
 
 /* ---------------------------------------------------------------------------
+ * kv_cache_write_fp8 (device)
+ *
+ * kv_cache_write into an fp8 cache (SMART_FP8_E4M3, one byte per element, same
+ * two layouts, strides in elements): every source element x (src_dtype
+ * SMART_F32 or SMART_BF16) is stored as the E4M3 value nearest to x / k_scale
+ * (keys) or x / v_scale (values): binary32 division, round to nearest with
+ * ties to the even mantissa, saturation at +-448, NaN kept.  Halving the bytes
+ * tree_verify_attention streams is the point: the prefix kernel is bound by
+ * HBM bandwidth.
+ * Errors as kv_cache_write, plus SMART_EINVAL for scales that are not positive
+ * and finite.
+ * ------------------------------------------------------------------------- */
+int32_t kv_cache_write_fp8(smart_ctx* ctx, void* stream, int32_t src_dtype, int32_t kv_layout,
+                           int32_t n_tokens, int32_t num_kv_heads, int32_t head_dim,
+                           int32_t block_size, int32_t num_blocks,
+                           const void* d_k_src, const void* d_v_src, const int64_t* d_slot_mapping,
+                           void* d_k_cache, void* d_v_cache,
+                           int64_t cache_block_stride, int64_t cache_head_stride,
+                           int64_t cache_token_stride /* PLAIN only */, float k_scale, float v_scale);
+
+/* ---------------------------------------------------------------------------
  * tree_verify_attention (device)
  *
  * For every sequence b, node i of its tree, query head h (kv head g = h / G,
@@ -455,7 +479,9 @@ int32_t kv_cache_write(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_l
  *   lse[i,h]   = log sum_keys exp(score)                      (optional)
  * Scores, softmax and accumulation are fp32 (bf16 inputs are multiplied on
  * the matrix cores with fp32 accumulation; softmax weights are rounded to
- * bf16 before the second product).
+ * bf16 before the second product).  With an fp8 cache (kv_cache_dtype =
+ * SMART_FP8_E4M3) the cached keys and values are k_scale / v_scale times the
+ * stored E4M3 values (exact in bf16); everything else is as above.
  *
  * Shapes: q, out [total_nodes][Hq][D]; k_tree, v_tree [total_nodes][Hkv][D]
  * (tree K/V are not in the cache yet); block_table [batch][max_blocks_per_seq]
@@ -475,7 +501,9 @@ typedef struct {
   int32_t batch, total_nodes, num_q_heads, num_kv_heads, head_dim;
   int32_t block_size, max_blocks_per_seq, num_blocks;
   float softmax_scale;
-  int32_t reserved0;
+  int32_t kv_cache_dtype; /* 0: the cache holds `dtype` elements; SMART_FP8_E4M3: one byte per element,
+                             key = k_scale * stored value, value = v_scale * stored value (strides still
+                             count elements) */
   const void* d_q;
   const void* d_k_tree;
   const void* d_v_tree;
@@ -492,6 +520,7 @@ typedef struct {
    * A hint only: results never depend on it and the present kernels plan on the device
    * without it.  If given it must agree with d_cu_nodes. */
   const int32_t* h_cu_nodes;
+  float k_scale, v_scale; /* fp8 cache only: positive, finite */
 } tva_params;
 
 int32_t tree_verify_attention(smart_ctx* ctx, void* stream, const tva_params* params);

@@ -17,6 +17,7 @@ LIB_PATH = os.environ.get("SMART_TREE_LIB") or os.path.join(_HERE, "libsmart_tre
 
 SMART_OK, SMART_EINVAL, SMART_ETREE, SMART_ECAP, SMART_EHIP, SMART_ENOMEM = 0, -1, -2, -3, -4, -5
 SMART_F32, SMART_BF16 = 0, 1
+SMART_FP8_E4M3 = 2
 SMART_KV_PLAIN, SMART_KV_INTERLEAVED = 0, 1
 SMART_BEST_FIRST, SMART_LAYERWISE = 0, 1
 SMART_DILUTION_NONE, SMART_DILUTION_PATH_MEAN = 0, 1
@@ -30,7 +31,7 @@ EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_dest
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
            "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
-           "kv_cache_write", "tree_verify_attention", "tree_accept", "tree_accept_sample", "tree_commit"]
+           "kv_cache_write", "kv_cache_write_fp8", "tree_verify_attention", "tree_accept", "tree_accept_sample", "tree_commit"]
 
 
 class SmartError(RuntimeError):
@@ -47,7 +48,7 @@ class TvaParams(ctypes.Structure):
         ("head_dim", ctypes.c_int32),
         ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
         ("num_blocks", ctypes.c_int32),
-        ("softmax_scale", ctypes.c_float), ("reserved0", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("kv_cache_dtype", ctypes.c_int32),
         ("d_q", ctypes.c_void_p), ("d_k_tree", ctypes.c_void_p), ("d_v_tree", ctypes.c_void_p),
         ("d_k_cache", ctypes.c_void_p), ("d_v_cache", ctypes.c_void_p),
         ("cache_block_stride", ctypes.c_int64), ("cache_head_stride", ctypes.c_int64),
@@ -56,6 +57,7 @@ class TvaParams(ctypes.Structure):
         ("d_cu_nodes", ctypes.c_void_p), ("d_anc_mask", ctypes.c_void_p),
         ("d_out", ctypes.c_void_p), ("d_lse", ctypes.c_void_p),
         ("h_cu_nodes", ctypes.c_void_p),
+        ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float),
     ]
 
 
@@ -128,6 +130,9 @@ def _lib():
         lib.kv_cache_write.restype = i32
         lib.kv_cache_write.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp,
                                        i64, i64, i64]
+        lib.kv_cache_write_fp8.restype = i32
+        lib.kv_cache_write_fp8.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp,
+                                           i64, i64, i64, ctypes.c_float, ctypes.c_float]
         lib.tree_verify_attention.restype = i32
         lib.tree_verify_attention.argtypes = [vp, vp, ctypes.POINTER(TvaParams)]
         lib.tree_commit.restype = i32
@@ -494,10 +499,20 @@ class SmartTree:
                                    block_stride, head_stride, token_stride)
         _check(rc, "kv_cache_write")
 
+    def kv_cache_write_fp8(self, k_src, v_src, slot_mapping, k_cache, v_cache, layout, block_size,
+                           num_blocks, block_stride, head_stride, k_scale, v_scale, token_stride=0):
+        """k_cache / v_cache: uint8 tensors (E4M3); strides in elements."""
+        n, Hkv, D = k_src.shape
+        rc = _lib().kv_cache_write_fp8(self._h, _stream_ptr(), _dtype_code(k_src), layout, n, Hkv, D,
+                                       block_size, num_blocks, _ptr(k_src), _ptr(v_src), _ptr(slot_mapping),
+                                       _ptr(k_cache), _ptr(v_cache), block_stride, head_stride, token_stride,
+                                       float(k_scale), float(v_scale))
+        _check(rc, "kv_cache_write_fp8")
+
     # -- tree_verify_attention ---------------------------------------------
     def tree_verify_attention(self, q, k_tree, v_tree, k_cache, v_cache, block_table, prefix_len,
                               cu_nodes, anc_mask, softmax_scale, kv_layout, block_size=16,
-                              out=None, lse=None, want_lse=False, h_cu_nodes=None):
+                              out=None, lse=None, want_lse=False, h_cu_nodes=None, k_scale=None, v_scale=None):
         """k_cache / v_cache: [num_blocks, Hkv, ...] with one contiguous page of
         block_size * D elements per (block, head) (any of the two layouts)."""
         torch = _torch()
@@ -526,6 +541,9 @@ class SmartTree:
         else:
             p.cache_block_stride = p.cache_head_stride = block_size * D
             p.cache_token_stride = D
+        if k_cache is not None and k_cache.dtype == torch.uint8:      # an fp8 (E4M3) cache
+            p.kv_cache_dtype = SMART_FP8_E4M3
+            p.k_scale, p.v_scale = float(k_scale), float(v_scale)
         p.d_prefix_len, p.d_cu_nodes = prefix_len.data_ptr(), cu_nodes.data_ptr()
         p.d_anc_mask = anc_mask.data_ptr()
         p.d_out = out.data_ptr()

@@ -10,6 +10,10 @@ extern "C" int32_t tree_verify_attention(smart_ctx* ctx, void* stream, const tva
   if (p.batch < 0 || p.total_nodes < 0 || p.num_q_heads <= 0 || p.num_kv_heads <= 0 ||
       p.num_q_heads % p.num_kv_heads != 0)
     return SMART_EINVAL;
+  if (p.kv_cache_dtype != 0 && p.kv_cache_dtype != SMART_FP8_E4M3) return SMART_EINVAL;
+  if (p.kv_cache_dtype == SMART_FP8_E4M3 &&
+      (!(p.k_scale > 0.f) || !(p.k_scale < 3e38f) || !(p.v_scale > 0.f) || !(p.v_scale < 3e38f)))
+    return SMART_EINVAL;
   if (p.head_dim != 64 && p.head_dim != 128) return SMART_EINVAL;
   if (p.block_size <= 0 || p.block_size > 64 || p.block_size % 8 != 0) return SMART_EINVAL;
   if (p.max_blocks_per_seq < 0 || p.num_blocks < 0) return SMART_EINVAL;

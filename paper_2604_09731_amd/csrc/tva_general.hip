@@ -11,6 +11,7 @@
 #include <math.h>
 
 #include "common.h"
+#include "fp8.h"
 
 namespace {
 
@@ -18,6 +19,7 @@ constexpr int kWave = 64;
 
 __device__ inline float to_float(float x) { return x; }
 __device__ inline float to_float(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+__device__ inline float to_float(uint8_t x) { return smart::fp8_e4m3_to_float(x); }  // fp8 cache element
 __device__ inline void from_float(float v, float* o) { *o = v; }
 __device__ inline void from_float(float v, uint16_t* o) {
   uint32_t u = __float_as_uint(v);
@@ -50,11 +52,14 @@ struct Layout {
   }
 };
 
-template <typename T>
+// T: element type of q, tree k / v and out; C: element type of the cache (T, or uint8_t = E4M3 whose
+// values are multiplied by k_scale / v_scale).
+template <typename T, typename C>
 __global__ __launch_bounds__(kWave) void tva_general_kernel(
     int batch, int total_nodes, int Hq, int Hkv, int D, int max_blocks, int num_blocks, float scale,
+    float k_scale, float v_scale,
     Layout lay, const T* __restrict__ q, const T* __restrict__ k_tree, const T* __restrict__ v_tree,
-    const T* __restrict__ k_cache, const T* __restrict__ v_cache,
+    const C* __restrict__ k_cache, const C* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ prefix_len,
     const int32_t* __restrict__ cu_nodes, const uint64_t* __restrict__ anc_mask,
     T* __restrict__ out, float* __restrict__ lse) {
@@ -114,6 +119,7 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
       float dot = 0.f;
       if (!tree) {
         for (int d = 0; d < D; ++d) dot += s_q[d] * to_float(k_cache[lay.k(blk, g, slot, d)]);
+        dot *= k_scale;
       } else {
         const T* kr = k_tree + ((size_t)(base + j) * Hkv + g) * D;
         for (int d = 0; d < D; ++d) dot += s_q[d] * to_float(kr[d]);
@@ -139,8 +145,8 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
         int64_t vb = block_table[(size_t)b * max_blocks + t / lay.block_size];
         vb = vb < 0 ? 0 : (vb >= num_blocks ? num_blocks - 1 : vb);
         const int vs = t % lay.block_size;
-        if (lane < D) acc0 += pk * to_float(v_cache[lay.v(vb, g, vs, lane)]);
-        if (lane + kWave < D) acc1 += pk * to_float(v_cache[lay.v(vb, g, vs, lane + kWave)]);
+        if (lane < D) acc0 += pk * (v_scale * to_float(v_cache[lay.v(vb, g, vs, lane)]));
+        if (lane + kWave < D) acc1 += pk * (v_scale * to_float(v_cache[lay.v(vb, g, vs, lane + kWave)]));
       } else {
         const int jj = (c - n_prefix_chunks) * kWave + kk;
         const T* vr = v_tree + ((size_t)(base + jj) * Hkv + g) * D;
@@ -168,21 +174,20 @@ int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params&
              p.cache_token_stride};
   int32_t rc = profile_begin(ctx, stream);
   if (rc != SMART_OK) return rc;
-  if (p.dtype == SMART_F32)
-    hipLaunchKernelGGL(tva_general_kernel<float>, dim3((unsigned)rows), dim3(kWave), 0, stream,
-                       p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, p.head_dim,
-                       p.max_blocks_per_seq, p.num_blocks, p.softmax_scale, lay,
-                       (const float*)p.d_q, (const float*)p.d_k_tree, (const float*)p.d_v_tree,
-                       (const float*)p.d_k_cache, (const float*)p.d_v_cache, p.d_block_table,
-                       p.d_prefix_len, p.d_cu_nodes, p.d_anc_mask, (float*)p.d_out, p.d_lse);
-  else
-    hipLaunchKernelGGL(tva_general_kernel<uint16_t>, dim3((unsigned)rows), dim3(kWave), 0, stream,
-                       p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, p.head_dim,
-                       p.max_blocks_per_seq, p.num_blocks, p.softmax_scale, lay,
-                       (const uint16_t*)p.d_q, (const uint16_t*)p.d_k_tree,
-                       (const uint16_t*)p.d_v_tree, (const uint16_t*)p.d_k_cache,
-                       (const uint16_t*)p.d_v_cache, p.d_block_table, p.d_prefix_len, p.d_cu_nodes,
-                       p.d_anc_mask, (uint16_t*)p.d_out, p.d_lse);
+  const bool fp8 = p.kv_cache_dtype == SMART_FP8_E4M3;
+  const float ks = fp8 ? p.k_scale : 1.f, vs = fp8 ? p.v_scale : 1.f;
+#define SMART_LAUNCH_GENERAL(T, C)                                                                            \
+  hipLaunchKernelGGL((tva_general_kernel<T, C>), dim3((unsigned)rows), dim3(kWave), 0, stream, p.batch,      \
+                     p.total_nodes, p.num_q_heads, p.num_kv_heads, p.head_dim, p.max_blocks_per_seq,         \
+                     p.num_blocks, p.softmax_scale, ks, vs, lay, (const T*)p.d_q, (const T*)p.d_k_tree,      \
+                     (const T*)p.d_v_tree, (const C*)p.d_k_cache, (const C*)p.d_v_cache, p.d_block_table,    \
+                     p.d_prefix_len, p.d_cu_nodes, p.d_anc_mask, (T*)p.d_out, p.d_lse)
+  if (p.dtype == SMART_F32) {
+    if (fp8) SMART_LAUNCH_GENERAL(float, uint8_t); else SMART_LAUNCH_GENERAL(float, float);
+  } else {
+    if (fp8) SMART_LAUNCH_GENERAL(uint16_t, uint8_t); else SMART_LAUNCH_GENERAL(uint16_t, uint16_t);
+  }
+#undef SMART_LAUNCH_GENERAL
   SMART_HIP_CHECK(hipGetLastError());
   return profile_end(ctx, stream);
 }

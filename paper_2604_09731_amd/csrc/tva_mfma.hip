@@ -1592,7 +1592,7 @@ void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes
 
 bool tva_mfma_supported(const tva_params& p) {
   auto aligned16 = [](const void* x) { return ((uintptr_t)x & 15u) == 0; };
-  return p.dtype == SMART_BF16 && p.kv_layout == SMART_KV_INTERLEAVED && p.head_dim == kD &&
+  return p.dtype == SMART_BF16 && p.kv_cache_dtype == 0 && p.kv_layout == SMART_KV_INTERLEAVED && p.head_dim == kD &&
          p.block_size == kBlock && p.cache_block_stride % 8 == 0 && p.cache_head_stride % 8 == 0 &&
          aligned16(p.d_q) && aligned16(p.d_k_cache) && aligned16(p.d_v_cache) &&
          aligned16(p.d_k_tree) && aligned16(p.d_v_tree) && aligned16(p.d_out) && p.num_blocks > 0;

@@ -1,0 +1,142 @@
+"""GPU parity of the fp8 (E4M3) KV-cache variant against the CPU oracle, through the C ABI: the cache writer
+is bit-exact, attention over an fp8 cache meets the same tolerance as over a bf16 cache (the oracle is fed
+the decoded cache, so the comparison measures kernel arithmetic, not the quantisation)."""
+import numpy as np
+import pytest
+
+from oracle import fp8 as F
+from oracle import kv_layout as KL
+from paper_2604_09731_amd import binding as B
+from paper_2604_09731_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return B.SmartTree(0)
+
+
+def _dev(a, dtype=None):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype)).to("cuda")
+
+
+def _f32(raw, dtype):
+    return W.bf16_bits_to_f32(raw) if dtype == "bf16" else raw.astype(np.float32)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("k_scale,v_scale", [(1.0, 1.0), (0.37, 2.0 ** -3), (3.0, 0.011)])
+def test_kv_cache_write_fp8_bit_exact(lib, dtype, k_scale, v_scale):
+    import torch
+    rng = np.random.default_rng(4)
+    nb, Hkv, bs, D, n = 7, 3, 16, 128, 60
+    k_src = W._normal(2, 1, (n, Hkv, D), 1.0, dtype)
+    v_src = W._normal(2, 2, (n, Hkv, D), 1.0, dtype)
+    # special values: zeros of both signs, ties, values beyond the range, tiny values
+    special = np.array([0.0, -0.0, 1.0625, 1.1875, 500.0, -1e6, 2.0 ** -10, 3 * 2.0 ** -10, 447.9, 17.0], np.float32)
+    if dtype == "bf16":
+        k_src[0, 0, :10] = W.f32_to_bf16_bits(special * np.float32(k_scale))
+    else:
+        k_src[0, 0, :10] = special * np.float32(k_scale)
+    slots = rng.permutation(nb * bs)[:n].astype(np.int64)
+    slots[7] = -1
+    want_k = np.zeros((nb, Hkv, bs, D), np.uint8)
+    want_v = np.zeros((nb, Hkv, bs, D), np.uint8)
+    ek = F.encode(_f32(k_src, dtype) / np.float32(k_scale))             # binary32 division, as the kernel does
+    ev = F.encode(_f32(v_src, dtype) / np.float32(v_scale))
+    for t in range(n):
+        if slots[t] >= 0:
+            want_k[slots[t] // bs, :, slots[t] % bs] = ek[t]
+            want_v[slots[t] // bs, :, slots[t] % bs] = ev[t]
+    tk, tv = H.torch_elems(k_src, dtype, "cuda"), H.torch_elems(v_src, dtype, "cuda")
+    for layout in (B.SMART_KV_PLAIN, B.SMART_KV_INTERLEAVED):
+        kc = torch.zeros((nb, Hkv, bs * D), dtype=torch.uint8, device="cuda")
+        vc = torch.zeros_like(kc)
+        lib.kv_cache_write_fp8(tk, tv, _dev(slots), kc, vc, layout, bs, nb, Hkv * bs * D, bs * D, k_scale, v_scale,
+                               token_stride=D)
+        torch.cuda.synchronize()
+        if layout == B.SMART_KV_PLAIN:
+            assert np.array_equal(kc.cpu().numpy().reshape(want_k.shape), want_k)
+            assert np.array_equal(vc.cpu().numpy().reshape(want_v.shape), want_v)
+        else:
+            assert np.array_equal(kc.cpu().numpy(), KL.interleave_plain_cache(want_k, "k"))
+            assert np.array_equal(vc.cpu().numpy(), KL.interleave_plain_cache(want_v, "v"))
+
+
+def _fp8_case(lib, w, cu, parent, lens, k_scale, v_scale, layout, seed):
+    """Builds an fp8 cache with the library's writer from the workload's bf16 / f32 cache contents; returns the
+    device tensors and the decoded cache (float64, scales applied) for the oracle."""
+    import torch
+    inp = W.make_attention_inputs(w, cu, seed=seed, prefix_len=lens, poison_unused=False)
+    nb, Hkv, bs, D = inp.k_cache.shape
+    # every slot of the cache as one "token": the writer quantises the whole cache
+    slots = np.arange(nb * bs, dtype=np.int64)
+    k_rows = np.ascontiguousarray(inp.k_cache.transpose(0, 2, 1, 3)).reshape(nb * bs, Hkv, D)
+    v_rows = np.ascontiguousarray(inp.v_cache.transpose(0, 2, 1, 3)).reshape(nb * bs, Hkv, D)
+    kc = torch.zeros((nb, Hkv, bs * D), dtype=torch.uint8, device="cuda")
+    vc = torch.zeros_like(kc)
+    lib.kv_cache_write_fp8(H.torch_elems(k_rows, w.dtype, "cuda"), H.torch_elems(v_rows, w.dtype, "cuda"), _dev(slots),
+                           kc, vc, layout, bs, nb, Hkv * bs * D, bs * D, k_scale, v_scale, token_stride=D)
+    torch.cuda.synchronize()
+    kq = F.decode(F.encode(_f32(inp.k_cache, w.dtype) / np.float32(k_scale))) * float(np.float32(k_scale))
+    vq = F.decode(F.encode(_f32(inp.v_cache, w.dtype) / np.float32(v_scale))) * float(np.float32(v_scale))
+    return inp, kc, vc, kq, vq
+
+
+@pytest.mark.parametrize("dtype,layout,D", [("bf16", B.SMART_KV_INTERLEAVED, 128), ("bf16", B.SMART_KV_PLAIN, 64),
+                                            ("f32", B.SMART_KV_INTERLEAVED, 64)])
+def test_attention_over_an_fp8_cache(lib, oracle_attention, dtype, layout, D):
+    import torch
+    rng = np.random.default_rng(8)
+    sizes = [1, 3, 9, 17, 40, 2]
+    trees = [W.random_tree(n, rng, s) for n, s in zip(sizes, ["random", "chain", "random", "star", "random", "random"])]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate(trees).astype(np.int32)
+    lens = np.array([0, 1, 31, 32, 33, 517], np.int32)
+    w = W.Workload("fp8", dtype, len(sizes), 8, 2, D, 0, 0, seed=31)
+    k_scale, v_scale = 0.05, 0.02                                    # unit-variance inputs use most of the range
+    inp, kc, vc, kq, vq = _fp8_case(lib, w, cu, parent, lens, k_scale, v_scale, layout, 31)
+    f64 = (lambda x: W.bf16_bits_to_f32(x).astype(np.float64)) if dtype == "bf16" else (lambda x: x.astype(np.float64))
+    d_cu, d_par, d_len = _dev(cu), _dev(parent), _dev(lens)
+    _, _, _, mask, _ = lib.tree_pack(d_cu, d_par, d_len)
+    nb, Hkv, bs, _ = inp.k_cache.shape
+    kc4 = kc.view(nb, Hkv, bs, D) if layout == B.SMART_KV_PLAIN else kc.view(nb, Hkv, D // 8, bs, 8)
+    vc4 = vc.view(nb, Hkv, bs, D) if layout == B.SMART_KV_PLAIN else vc.view(nb, Hkv, bs // 8, D, 8)
+    out, lse = lib.tree_verify_attention(H.torch_elems(inp.q, dtype, "cuda"), H.torch_elems(inp.k_tree, dtype, "cuda"),
+                                         H.torch_elems(inp.v_tree, dtype, "cuda"), kc4, vc4,
+                                         _dev(inp.block_table), d_len, d_cu, mask, inp.scale, layout, block_size=bs,
+                                         want_lse=True, k_scale=k_scale, v_scale=v_scale)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle_attention.tree_attention(f64(inp.q), f64(inp.k_tree), f64(inp.v_tree), kq, vq,
+                                                   inp.block_table, lens, cu, parent, inp.scale)
+    got = H.out_to_f64(out, dtype)
+    assert np.isfinite(got).all()
+    assert H.rel_err(got, ref) <= H.TOL[dtype], H.rel_err(got, ref)
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() <= (1e-4 if dtype == "f32" else 2e-2)
+    # the quantisation itself is visible: against the unquantised cache the error is well above the tolerance
+    ref0, _ = oracle_attention.tree_attention(f64(inp.q), f64(inp.k_tree), f64(inp.v_tree), f64(inp.k_cache),
+                                              f64(inp.v_cache), inp.block_table, lens, cu, parent, inp.scale)
+    assert H.rel_err(ref, ref0) > 1e-3
+
+
+def test_fp8_argument_checks(lib):
+    import ctypes
+    import torch
+    x = torch.zeros(16 * 128, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(16 * 128, dtype=torch.uint8, device="cuda")
+    sm = torch.zeros(1, dtype=torch.int64, device="cuda")
+    L = B._lib()
+    vp = lambda t: ctypes.c_void_p(t.data_ptr())
+    call = lambda ks, vs, dt=B.SMART_BF16: L.kv_cache_write_fp8(lib._h, None, dt, B.SMART_KV_INTERLEAVED, 1, 1, 128, 16, 1,
+                                                                vp(x), vp(x), vp(sm), vp(c), vp(c), 2048, 2048, 128,
+                                                                ctypes.c_float(ks), ctypes.c_float(vs))
+    assert call(1.0, 1.0) == B.SMART_OK
+    for ks, vs in ((0.0, 1.0), (1.0, -1.0), (float("nan"), 1.0), (1.0, float("inf"))):
+        assert call(ks, vs) == B.SMART_EINVAL
+    assert call(1.0, 1.0, dt=B.SMART_FP8_E4M3) == B.SMART_EINVAL
+    torch.cuda.synchronize()
