@@ -60,5 +60,16 @@ def encode_one(x: float) -> int:
 
 
 def encode(x) -> np.ndarray:
-    flat = np.asarray(x, np.float64).ravel()
-    return np.array([encode_one(v) for v in flat], np.uint8).reshape(np.shape(x))
+    """encode_one over an array: the nearest of the 127 non-negative grid values (their codes are
+    their ranks), ties to the even code, the sign bit on top.  Same results as encode_one (pinned)."""
+    x = np.asarray(x, np.float64)
+    grid = TABLE[:0x7F]                                  # codes 0x00 .. 0x7E: ascending, 0 .. 448
+    a = np.minimum(np.abs(x), MAX)
+    a = np.where(np.isnan(a), 0.0, a)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 1, 0x7E)
+    lo = hi - 1
+    d_lo, d_hi = a - grid[lo], grid[hi] - a
+    code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(a == grid[hi], hi, code)
+    out = (code | np.where(np.signbit(x), 0x80, 0)).astype(np.uint8)
+    return np.where(np.isnan(x), np.uint8(0x7F), out).astype(np.uint8)

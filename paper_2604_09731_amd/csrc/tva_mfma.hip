@@ -177,8 +177,12 @@ __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_n
 // to the class with the most work, so the classes never need more workgroups than were
 // launched.  Returns the workers per class and the first workgroup of each class (entry
 // kClasses: one past the last).
-__device__ inline void apportion(const int64_t (&tot_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
+// kOnlySmall: the fp8-cache kernel streams class 0 only (the other classes go through the general
+// kernel), so class 0 gets every workgroup.
+template <bool kOnlySmall = false>
+__device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
                                  int64_t (&first_wg)[kClasses + 1]) {
+  const int64_t tot_u[kClasses] = {all_u[0], kOnlySmall ? 0 : all_u[1], kOnlySmall ? 0 : all_u[2]};
   const int64_t weight[kClasses] = {2, 2, 3};
   const int64_t launched = workgroups > kClasses ? workgroups : kClasses;
   int64_t cost[kClasses], total = 0;
@@ -217,6 +221,7 @@ __device__ inline void apportion(const int64_t (&tot_u)[kClasses], int workgroup
   first_wg[kClasses] = first;
 }
 
+template <bool kOnlySmall>
 __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int workgroups,
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ cu_nodes) {
@@ -242,7 +247,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   int64_t ch = wave_excl_scan(chunks, t, &tot_c);
   if (t == 0) {
     int64_t workers[kClasses], first_wg[kClasses + 1];
-    apportion(tot_u, workgroups, workers, first_wg);
+    apportion<kOnlySmall>(tot_u, workgroups, workers, first_wg);
     for (int c = 0; c < kClasses; ++c) {
       pv.cum_units[c][batch] = tot_u[c];
       pv.cum_segs[c][batch] = (int32_t)tot_s[c];
@@ -284,6 +289,7 @@ struct LanePlan {
   int32_t chunks;
 };
 
+template <bool kOnlySmall = false>
 __device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const int32_t* cu_nodes, int batch,
                                  int total_nodes, int G, int Hkv, int max_blocks, int workgroups, int lane) {
   const int b = min(lane, batch - 1);
@@ -305,7 +311,7 @@ __device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const i
   }
   p.cum_chunks = (int32_t)wave_excl_scan((int64_t)Hkv * ((rows + kCombineRows - 1) / kCombineRows), lane, &tot_c);
   p.chunks = (int32_t)tot_c;
-  apportion(p.units, workgroups, p.workers, p.first_wg);
+  apportion<kOnlySmall>(p.units, workgroups, p.workers, p.first_wg);
 }
 
 // ---------------------------------------------------------------------------
@@ -323,6 +329,9 @@ struct MainArgs {
   int64_t block_stride, head_stride;
   int32_t batch, total_nodes, Hq, Hkv, G, max_blocks, num_blocks, workgroups;
   float scale_log2e;
+  // fp8 cache only: k_cache / v_cache then point at bytes (E4M3), scale_log2e already includes k_scale,
+  // a partial's row maxima are multiplied by m_scale (= k_scale) and its O by o_scale (= v_scale)
+  float m_scale, o_scale;
 };
 
 // Wave-uniform data (block table, plan) is read through the constant address
@@ -403,9 +412,50 @@ __device__ inline void load_v(bf16x8 (&v)[2][4], const MainArgs& a, const TilePa
   }
 }
 
+// The same two tiles out of an fp8 cache: the pages have the same element order, one byte per
+// element, so a lane's operand vector is 8 bytes; it becomes bf16 (exactly) just before its MFMA.
+typedef __attribute__((ext_vector_type(2))) uint32_t fp8x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+__device__ inline void load_k(fp8x8 (&k)[8], const MainArgs& a, const TilePages& tp, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  const int64_t mask = -(int64_t)(j >> 4);
+  const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
+  const uint8_t* kp = (const uint8_t*)a.k_cache + page + (h * 16 + sigma(j & 15)) * 8;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k[ks] = *(const fp8x8*)(kp + ks * 256);
+}
+
+__device__ inline void load_v(fp8x8 (&v)[2][4], const MainArgs& a, const TilePages& tp, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  const uint8_t* vp0 = (const uint8_t*)a.v_cache + tp.page0 + (h * kD + j) * 8;
+  const uint8_t* vp1 = (const uint8_t*)a.v_cache + tp.page1 + (h * kD + j) * 8;
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    v[0][jt] = *(const fp8x8*)(vp0 + jt * 256);
+    v[1][jt] = *(const fp8x8*)(vp1 + jt * 256);
+  }
+}
+
+__device__ inline bf16x8 operand(const bf16x8& x) { return x; }
+__device__ inline bf16x8 operand(const fp8x8& x) {
+  const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x[0], 1.0f, false);
+  const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x[0], 1.0f, true);
+  const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x[1], 1.0f, false);
+  const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x[1], 1.0f, true);
+  bf16x8 r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+  r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+  return r;
+}
+
+__device__ inline void zero_token(bf16x8& v, int e) { v[e] = (__bf16)0.f; }
+__device__ inline void zero_token(fp8x8& v, int e) { v[e >> 2] &= ~(0xFFu << (8 * (e & 3))); }  // byte 0x00 = +0
+
 // Masks the ragged end of a prefix: scores of tokens >= n_valid become -inf and
 // their V entries zero (unused cache slots may hold anything, NaN included).
-__device__ inline void mask_tail(floatx16& s, bf16x8 (&v)[2][4], int n_valid, int h) {
+template <typename Raw>
+__device__ inline void mask_tail(floatx16& s, Raw (&v)[2][4], int n_valid, int h) {
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int i = 8 * (r >> 2) + 4 * h + (r & 3);  // score-tile row of this register
@@ -418,7 +468,7 @@ __device__ inline void mask_tail(floatx16& s, bf16x8 (&v)[2][4], int n_valid, in
     for (int e = 0; e < 8; ++e)
       if (kk * 16 + h * 8 + e >= n_valid) {
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) v[kk][jt][e] = (__bf16)0.f;
+        for (int jt = 0; jt < 4; ++jt) zero_token(v[kk][jt], e);
       }
 }
 
@@ -516,25 +566,26 @@ __device__ inline TilePages pages_from_ids(const MainArgs& a, const BlockIds& id
   return tp;
 }
 
-template <bool kMasked>
-__device__ inline void small_tile(SmallState& S, bf16x8 (&k)[8], bf16x8 (&v)[2][4], const bf16x8 (&q)[8],
+template <bool kMasked, typename Raw>
+__device__ inline void small_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4], const bf16x8 (&q)[8],
                                   int lane, float c, int n_valid, const MainArgs& a,
                                   const TilePages& next) {
   floatx16 s = (floatx16)(0.f);
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[ks], q[ks], s, 0, 0, 0);
+  for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(k[ks]), q[ks], s, 0, 0, 0);
   load_k(k, a, next, lane);
   if (kMasked) mask_tail(s, v, n_valid, lane >> 5);
   bf16x8 pb0, pb1;
   softmax_tile(s, S.m, S.l, S.o, pb0, pb1, c);
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt) {
-    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[0][jt], pb0, S.o[jt], 0, 0, 0);
-    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[1][jt], pb1, S.o[jt], 0, 0, 0);
+    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(v[0][jt]), pb0, S.o[jt], 0, 0, 0);
+    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(v[1][jt]), pb1, S.o[jt], 0, 0, 0);
   }
   load_v(v, a, next, lane);
 }
 
+template <typename Raw = bf16x8>
 __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, int g, int base, int t0,
                                      int t1, const SeqInfo si, int lane) {
   const int h = lane >> 5, j = lane & 31;
@@ -566,7 +617,7 @@ __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, in
     asm volatile("" ::"v"(ids.lo), "v"(ids.hi));
     // complete tiles (32 valid keys) end here; at most the sequence's last tile is ragged
     const int full_end = min(te, si.len / kTile);
-    bf16x8 k[8], v[2][4];
+    Raw k[8], v[2][4];
     {
       const TilePages first = pages_from_ids(a, ids, 0, g);
       load_k(k, a, first, lane);
@@ -601,7 +652,10 @@ __device__ inline void state_to_lds(const SmallState& S, float* region, int lane
 // LDS, and after one barrier wavefront w merges accumulator registers 8 w .. 8 w + 7 of the
 // eight states (always in wavefront order, so the result does not depend on timing) and
 // stores that slice of the partial; wavefront 0 also stores the row maxima and sums.
-__device__ inline void fold_and_store(const SmallState& S, float* lds, float* slot, int wv, int lane, float c) {
+// kScaled (fp8 cache): the partial leaves in true units, row maxima times m_scale, O times o_scale.
+template <bool kScaled = false>
+__device__ inline void fold_and_store(const SmallState& S, float* lds, float* slot, int wv, int lane, float c,
+                                      float m_scale = 1.f, float o_scale = 1.f) {
   const int h = lane >> 5, j = lane & 31;
   state_to_lds(S, lds + wv * kStateFloats, lane);
   __syncthreads();
@@ -630,6 +684,11 @@ __device__ inline void fold_and_store(const SmallState& S, float* lds, float* sl
     l_new += lk[k] * sc;
     x[0] += part[k][0] * sc;
     x[1] += part[k][1] * sc;
+  }
+  if (kScaled) {
+    x[0] *= o_scale;
+    x[1] *= o_scale;
+    m_new *= m_scale;  // (-inf stays -inf)
   }
   // accumulator register 16 jt + 4 r4 + i of lane (h, j) is row j, head dims 4 (8 jt + 2 r4 + h) + i
   const int jt = wv >> 1, r4 = 2 * (wv & 1);
@@ -733,6 +792,7 @@ __device__ inline void follow(ClassPlan& cp, const PlanView& pv, const int32_t* 
 // piece leaves ONE partial in memory however many wavefronts streamed it.
 constexpr int kSmallWaves = kWgWaves;
 
+template <bool kFp8 = false>
 __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 132 KB: eight states */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = cp.U, W = cp.W;
@@ -761,8 +821,14 @@ __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
     const int s0 = t0 + (int)(((int64_t)nt * wv) / kSmallWaves);
     const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kSmallWaves);
     SmallState S;
-    small_segment(S, a, b, g, base, s0, s1, si, lane);
-    fold_and_store(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e);
+    if (kFp8) {
+      small_segment<fp8x8>(S, a, b, g, base, s0, s1, si, lane);
+      fold_and_store<true>(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e,
+                           a.m_scale, a.o_scale);
+    } else {
+      small_segment(S, a, b, g, base, s0, s1, si, lane);
+      fold_and_store(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e);
+    }
     u0 += nt;
   }
 }
@@ -1275,6 +1341,9 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
 }
 
 // ---- the prefix kernel: one launch, workgroups apportioned to the classes by the plan ------
+// kFp8: the cache holds E4M3 bytes; only class 0 is streamed here (every workgroup goes to it),
+// the sequences of the other classes are left to the general kernel.
+template <bool kFp8>
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
   __shared__ float4 lds_raw[8448];  // 132 KB, carved up per class (class 0: eight states of 16.5 KB)
@@ -1289,7 +1358,7 @@ void tva_prefix_kernel(MainArgs a) {
     __shared__ PlanShare share;
     if (wv == 0) {
       LanePlan lp;
-      lane_plan(lp, a.prefix_len, a.cu_nodes, a.batch, a.total_nodes, a.G, a.Hkv, a.max_blocks, a.workgroups, lane);
+      lane_plan<kFp8>(lp, a.prefix_len, a.cu_nodes, a.batch, a.total_nodes, a.G, a.Hkv, a.max_blocks, a.workgroups, lane);
 #pragma unroll
       for (int c = 0; c < kClasses; ++c) {
         share.cum_units[c][lane] = lp.cum_units[c];
@@ -1361,6 +1430,10 @@ void tva_prefix_kernel(MainArgs a) {
     cp.resident = false;
   }
   if (wg >= end) return;
+  if (kFp8) {
+    if (wg < first1) small_worker<true>(a, wg, cp, (float*)lds_raw);
+    return;
+  }
   if (wg < first1) {
     small_worker(a, wg, cp, (float*)lds_raw);
   } else if (wg < first2) {
@@ -1385,6 +1458,7 @@ struct CombineArgs {
   float* lse;
   int32_t batch, Hq, Hkv, G;
   float scale, scale_log2e;
+  int32_t only_small;  // fp8 cache: rows of sequences outside class 0 belong to the general kernel
 };
 
 __device__ inline float bf16_to_f32(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
@@ -1424,6 +1498,7 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   }
   const SeqInfo si = sload(pv.info + b);
   const int cls = seq_class(si.n * a.G);
+  if (a.only_small && cls != 0) return;
   const int chunk_base = sload(pv.cum_chunks + b);
   const int base = sload(a.cu_nodes + b);
   const int64_t U = sload(pv.header + 2 * cls), W = sload(pv.header + 2 * cls + 1);
@@ -1592,7 +1667,7 @@ void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes
 
 bool tva_mfma_supported(const tva_params& p) {
   auto aligned16 = [](const void* x) { return ((uintptr_t)x & 15u) == 0; };
-  return p.dtype == SMART_BF16 && p.kv_cache_dtype == 0 && p.kv_layout == SMART_KV_INTERLEAVED && p.head_dim == kD &&
+  return p.dtype == SMART_BF16 && p.kv_layout == SMART_KV_INTERLEAVED && p.head_dim == kD &&
          p.block_size == kBlock && p.cache_block_stride % 8 == 0 && p.cache_head_stride % 8 == 0 &&
          aligned16(p.d_q) && aligned16(p.d_k_cache) && aligned16(p.d_v_cache) &&
          aligned16(p.d_k_tree) && aligned16(p.d_v_tree) && aligned16(p.d_out) && p.num_blocks > 0;
@@ -1611,10 +1686,16 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   for (int c = 1; c < kClasses; ++c)
     ws[c] = ws[c - 1] + class_slots(ctx, c - 1, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads) * class_slot(c - 1);
 
+  const bool fp8 = p.kv_cache_dtype == SMART_FP8_E4M3;
   if (p.batch > kWave) {  // smaller batches: the prefix kernel derives the plan itself
-    hipLaunchKernelGGL(tva_plan_kernel, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
-                       p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
-                       p.d_cu_nodes);
+    if (fp8)
+      hipLaunchKernelGGL(tva_plan_kernel<true>, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
+                         p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
+                         p.d_cu_nodes);
+    else
+      hipLaunchKernelGGL(tva_plan_kernel<false>, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
+                         p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
+                         p.d_cu_nodes);
     SMART_HIP_CHECK(hipGetLastError());
   }
 
@@ -1637,15 +1718,25 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.G = G;
   ma.max_blocks = p.max_blocks_per_seq;
   ma.num_blocks = p.num_blocks;
-  ma.scale_log2e = p.softmax_scale * kLog2e;
+  ma.scale_log2e = p.softmax_scale * kLog2e * (fp8 ? p.k_scale : 1.f);
+  ma.m_scale = fp8 ? p.k_scale : 1.f;
+  ma.o_scale = fp8 ? p.v_scale : 1.f;
   rc = profile_begin(ctx, stream);
   if (rc != SMART_OK) return rc;
   // (every class with work needs a workgroup, however few were asked for)
-  hipLaunchKernelGGL(tva_prefix_kernel, dim3(workgroups > kClasses ? workgroups : kClasses), dim3(kWgWaves * kWave), 0,
-                     stream, ma);
+  const dim3 grid(workgroups > kClasses ? workgroups : kClasses);
+  if (fp8)
+    hipLaunchKernelGGL(tva_prefix_kernel<true>, grid, dim3(kWgWaves * kWave), 0, stream, ma);
+  else
+    hipLaunchKernelGGL(tva_prefix_kernel<false>, grid, dim3(kWgWaves * kWave), 0, stream, ma);
   SMART_HIP_CHECK(hipGetLastError());
   rc = profile_end(ctx, stream);
   if (rc != SMART_OK) return rc;
+  if (fp8) {
+    // sequences with more than 32 rows per kv head: whole rows (prefix and tree part) by the general kernel
+    rc = tva_launch_general_rows(ctx, stream, p, kSmallRows);
+    if (rc != SMART_OK) return rc;
+  }
 
   CombineArgs ca;
   ca.q = (const uint16_t*)p.d_q;
@@ -1663,6 +1754,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ca.G = G;
   ca.scale = p.softmax_scale;
   ca.scale_log2e = p.softmax_scale * kLog2e;
+  ca.only_small = fp8 ? 1 : 0;
   const int64_t max_chunks =
       (int64_t)p.num_kv_heads * (((int64_t)p.total_nodes * G + kCombineRows - 1) / kCombineRows + p.batch);
   if (max_chunks > 0x7FFFFFFF) return SMART_EINVAL;

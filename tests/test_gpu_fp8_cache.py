@@ -140,3 +140,63 @@ def test_fp8_argument_checks(lib):
         assert call(ks, vs) == B.SMART_EINVAL
     assert call(1.0, 1.0, dt=B.SMART_FP8_E4M3) == B.SMART_EINVAL
     torch.cuda.synchronize()
+
+
+def _run_fp8(lib, oracle_attention, w, cu, parent, lens, seed, k_scale=0.05, v_scale=0.02):
+    import torch
+    inp, kc, vc, kq, vq = _fp8_case(lib, w, cu, parent, lens, k_scale, v_scale, B.SMART_KV_INTERLEAVED, seed)
+    f64 = lambda x: W.bf16_bits_to_f32(x).astype(np.float64)
+    d_cu, d_par, d_len = _dev(cu), _dev(parent), _dev(lens)
+    _, _, _, mask, _ = lib.tree_pack(d_cu, d_par, d_len)
+    nb, Hkv, bs, D = inp.k_cache.shape
+    out, lse = lib.tree_verify_attention(H.torch_elems(inp.q, "bf16", "cuda"), H.torch_elems(inp.k_tree, "bf16", "cuda"),
+                                         H.torch_elems(inp.v_tree, "bf16", "cuda"), kc.view(nb, Hkv, D // 8, bs, 8),
+                                         vc.view(nb, Hkv, bs // 8, D, 8), _dev(inp.block_table), d_len, d_cu, mask,
+                                         inp.scale, B.SMART_KV_INTERLEAVED, block_size=bs, want_lse=True,
+                                         k_scale=k_scale, v_scale=v_scale)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle_attention.tree_attention(f64(inp.q), f64(inp.k_tree), f64(inp.v_tree), kq, vq,
+                                                   inp.block_table, lens, cu, parent, inp.scale)
+    got = H.out_to_f64(out, "bf16")
+    assert np.isfinite(got).all()
+    err = H.rel_err(got, ref)
+    assert err <= H.TOL["bf16"], err
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() <= 2e-2
+    return got
+
+
+@pytest.mark.parametrize("batch,G,Hkv,maxlen", [(32, 4, 8, 1200), (5, 8, 2, 3000), (70, 4, 2, 400), (1, 1, 4, 2500)])
+def test_fp8_small_trees_on_the_matrix_cores(lib, oracle_attention, batch, G, Hkv, maxlen):
+    """Every sequence has at most 32 rows per kv head: all of them go through the fp8 streaming kernel
+    (ragged prefixes, empty prefixes, several workers per segment, more than 64 sequences)."""
+    rng = np.random.default_rng(batch + G)
+    sizes = rng.integers(1, 32 // G + 1, batch)
+    trees = [W.random_tree(int(n), rng, "random") for n in sizes]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate(trees).astype(np.int32)
+    lens = rng.integers(0, maxlen, batch).astype(np.int32)
+    lens[0] = maxlen
+    if batch > 3:
+        lens[1], lens[2], lens[3] = 0, 33, 31
+    w = W.Workload("fp8_small", "bf16", batch, Hkv * G, Hkv, 128, 0, 0, seed=77)
+    a = _run_fp8(lib, oracle_attention, w, cu, parent, lens, 77)
+    # the general kernel over the same fp8 cache agrees (two implementations of one definition)
+    lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 1)
+    try:
+        g = _run_fp8(lib, oracle_attention, w, cu, parent, lens, 77)
+    finally:
+        lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 0)
+    assert H.rel_err(a, g) <= H.TOL["bf16"]
+
+
+def test_fp8_scales_are_applied(lib, oracle_attention):
+    """Large and small scales, keys and values scaled apart: the result follows the decoded cache."""
+    rng = np.random.default_rng(2)
+    sizes = [4, 6, 2]
+    trees = [W.random_tree(n, rng, "random") for n in sizes]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate(trees).astype(np.int32)
+    lens = np.array([700, 64, 129], np.int32)
+    w = W.Workload("fp8_scales", "bf16", 3, 8, 2, 128, 0, 0, seed=5)
+    for ks, vs in ((0.01, 0.3), (0.2, 0.01), (1.0, 1.0)):
+        _run_fp8(lib, oracle_attention, w, cu, parent, lens, 5, k_scale=ks, v_scale=vs)

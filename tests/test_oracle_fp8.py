@@ -36,3 +36,13 @@ def test_encode_is_the_nearest_grid_point_by_brute_force():
     for xi, gi in zip(x, got):
         best = np.abs(grid - np.clip(xi, -448, 448)).min()
         assert abs(gi - np.clip(xi, -448, 448)) == best
+
+
+def test_array_form_equals_the_scalar_definition():
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.standard_normal(4000) * 3, rng.uniform(-500, 500, 2000), rng.standard_normal(2000) * 0.01,
+                        F.TABLE[np.isfinite(F.TABLE)], [0.0, -0.0, np.inf, -np.inf, np.nan, 1.0625, 1.1875, 2.0 ** -10,
+                                                         3 * 2.0 ** -10, 464.0, 447.99, 448.0, -448.0]])
+    mid = (F.TABLE[:0x7E] + F.TABLE[1:0x7F]) / 2             # every half-way point of the grid, both signs
+    x = np.concatenate([x, mid, -mid])
+    assert F.encode(x).tolist() == [F.encode_one(v) for v in x]
