@@ -55,6 +55,9 @@ def main():
                     help="greedy: the longest-accepted-path walk (the headline step); sample: temperature-1 "
                          "verification over synthetic target distributions of --vocab tokens")
     ap.add_argument("--vocab", type=int, default=128256)
+    ap.add_argument("--kv", choices=["bf16", "fp8"], default="bf16",
+                    help="fp8: the same cache contents stored as E4M3 bytes (a bandwidth variant; the headline "
+                         "metric is the bf16 cache)")
     ap.add_argument("--workers", type=int, default=0, help="override the number of split-KV workers (0 = automatic)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -150,6 +153,16 @@ def main():
 
     q, k_tree, v_tree = elems(inp.q), elems(inp.k_tree), elems(inp.v_tree)
     kc, vc = B.interleave_kv_cache(elems(inp.k_cache), elems(inp.v_cache))
+    KV_SCALES = (2.0 ** -5, 2.0 ** -5)           # unit-variance K / V use the E4M3 range well at 1/32
+    if args.kv == "fp8":
+        nb_, Hkv_, bs_, D_ = inp.k_cache.shape
+        rows = lambda x: elems(np.ascontiguousarray(x.transpose(0, 2, 1, 3)).reshape(nb_ * bs_, Hkv_, D_))
+        kc8 = torch.zeros((nb_, Hkv_, D_ // 8, bs_, 8), dtype=torch.uint8, device=dev)
+        vc8 = torch.zeros((nb_, Hkv_, bs_ // 8, D_, 8), dtype=torch.uint8, device=dev)
+        lib.kv_cache_write_fp8(rows(inp.k_cache), rows(inp.v_cache), torch.arange(nb_ * bs_, device=dev),
+                               kc8, vc8, B.SMART_KV_INTERLEAVED, bs_, nb_, Hkv_ * bs_ * D_, bs_ * D_, *KV_SCALES)
+        torch.cuda.synchronize()
+        kc, vc = kc8, vc8
     block_table = torch.from_numpy(inp.block_table).to(dev)
     prefix_len = torch.from_numpy(inp.prefix_len).to(dev)
     if forest is not None:
@@ -206,6 +219,9 @@ def main():
         P.d_block_table, P.d_prefix_len = block_table.data_ptr(), prefix_len.data_ptr()
         P.d_cu_nodes, P.d_anc_mask = d_cu.data_ptr(), anc_mask.data_ptr()
         P.d_out, P.d_lse = out.data_ptr(), None
+        if args.kv == "fp8":
+            P.kv_cache_dtype = B.SMART_FP8_E4M3
+            P.k_scale, P.v_scale = KV_SCALES
         P.h_cu_nodes = stage_np[ds_index][:Bsz + 1].ctypes.data   # selection wrote it on the host
         acc_args = (ctx, stream, Bsz, w.max_depth, vp(d_cu), vp(d_par), vp(d_tok), vp(target_next),
                     vp(accept_len), vp(accept_path), vp(bonus))
@@ -301,7 +317,8 @@ def main():
     dep = depth.cpu().numpy()
     work = algorithmic_work(w, inp.prefix_len, cu_nodes, int((dep + 1).sum()))
     e = 2 if w.dtype == "bf16" else 4
-    dom_bytes = work["kv_bytes"] + N * w.num_q_heads * w.head_dim * e   # prefix K/V once + Q
+    kv_bytes = work["kv_bytes"] // (2 if args.kv == "fp8" and w.dtype == "bf16" else 1)
+    dom_bytes = kv_bytes + N * w.num_q_heads * w.head_dim * e   # prefix K/V once + Q
     achieved_gbs = dom_bytes / (dom_ms * 1e-3) / 1e9
     tflops = work["flops"] / (att_us * 1e-6) / 1e12
     result = {
@@ -323,7 +340,7 @@ def main():
                    "tree_nodes_min_median_max": [int(sizes.min()), int(np.median(sizes)), int(sizes.max())],
                    "prefix_len_min_max": [int(inp.prefix_len.min()), int(inp.prefix_len.max())],
                    "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
-                   "block_size": 16, "kv_layout": "interleaved", "accept": args.accept,
+                   "block_size": 16, "kv_layout": "interleaved", "kv_cache": args.kv, "accept": args.accept,
                    **({"vocab": args.vocab} if args.accept == "sample" else {})},
         "breakdown_us": {"select_host": round(sel_us, 1), "tree_upload_pack": round(pack_us, 2),
                          "tree_verify_attention": round(att_us, 2), ("tree_accept" if args.accept == "greedy" else "tree_accept_sample"): round(acc_us, 2)},
@@ -334,7 +351,7 @@ def main():
                      "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
                      "kernel_us": round(dom_ms * 1e3, 2), "algorithmic_bytes": int(dom_bytes),
-                     "traffic": MEASURED_TRAFFIC.get(w.name)},
+                     "traffic": MEASURED_TRAFFIC.get(w.name) if args.kv == "bf16" else None},
     }
 
     # ---------------- CPU baseline: the oracle, bounded sample ----------------

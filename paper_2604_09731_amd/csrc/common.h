@@ -53,9 +53,6 @@ int32_t profile_end(smart_ctx* ctx, hipStream_t stream);
 
 // Entry points of the two attention implementations (validated params).
 int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
-// The general kernel for the sequences with MORE than skip_rows_upto rows per kv head only (rows of the
-// other sequences are left untouched); no profiling events.
-int32_t tva_launch_general_rows(smart_ctx* ctx, hipStream_t stream, const tva_params& p, int32_t skip_rows_upto);
 int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
 bool tva_mfma_supported(const tva_params& p);
 // Workspace the matrix-core path needs for a problem of this size.

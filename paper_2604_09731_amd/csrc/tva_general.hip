@@ -57,7 +57,7 @@ struct Layout {
 template <typename T, typename C>
 __global__ __launch_bounds__(kWave) void tva_general_kernel(
     int batch, int total_nodes, int Hq, int Hkv, int D, int max_blocks, int num_blocks, float scale,
-    float k_scale, float v_scale, int skip_rows_upto,
+    float k_scale, float v_scale,
     Layout lay, const T* __restrict__ q, const T* __restrict__ k_tree, const T* __restrict__ v_tree,
     const C* __restrict__ k_cache, const C* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ prefix_len,
@@ -83,8 +83,6 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
   int len = prefix_len[b];
   const int cap = max_blocks * lay.block_size;
   len = len < 0 ? 0 : (len > cap ? cap : len);
-  // (another kernel computes the sequences with few rows per kv head)
-  if (skip_rows_upto > 0 && n_b * (Hq / Hkv) <= skip_rows_upto) return;
   if (node - base >= n_b) {  // a node no sequence owns (inconsistent offsets): defined output
     T* o = out + ((size_t)node * Hq + h) * D;
     for (int d = lane; d < D; d += kWave) from_float(0.f, &o[d]);
@@ -168,21 +166,20 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
 
 namespace smart {
 
-static int32_t launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p, int32_t skip_rows_upto,
-                              bool profile) {
+int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p) {
   const int64_t rows = (int64_t)p.total_nodes * p.num_q_heads;
   if (rows == 0) return SMART_OK;
   if (rows > 0x7FFFFFFF) return SMART_EINVAL;
   Layout lay{p.kv_layout, p.block_size, p.head_dim, p.cache_block_stride, p.cache_head_stride,
              p.cache_token_stride};
-  int32_t rc = profile ? profile_begin(ctx, stream) : SMART_OK;
+  int32_t rc = profile_begin(ctx, stream);
   if (rc != SMART_OK) return rc;
   const bool fp8 = p.kv_cache_dtype == SMART_FP8_E4M3;
   const float ks = fp8 ? p.k_scale : 1.f, vs = fp8 ? p.v_scale : 1.f;
 #define SMART_LAUNCH_GENERAL(T, C)                                                                            \
   hipLaunchKernelGGL((tva_general_kernel<T, C>), dim3((unsigned)rows), dim3(kWave), 0, stream, p.batch,      \
                      p.total_nodes, p.num_q_heads, p.num_kv_heads, p.head_dim, p.max_blocks_per_seq,         \
-                     p.num_blocks, p.softmax_scale, ks, vs, skip_rows_upto, lay, (const T*)p.d_q, (const T*)p.d_k_tree,      \
+                     p.num_blocks, p.softmax_scale, ks, vs, lay, (const T*)p.d_q, (const T*)p.d_k_tree,      \
                      (const T*)p.d_v_tree, (const C*)p.d_k_cache, (const C*)p.d_v_cache, p.d_block_table,    \
                      p.d_prefix_len, p.d_cu_nodes, p.d_anc_mask, (T*)p.d_out, p.d_lse)
   if (p.dtype == SMART_F32) {
@@ -192,14 +189,7 @@ static int32_t launch_general(smart_ctx* ctx, hipStream_t stream, const tva_para
   }
 #undef SMART_LAUNCH_GENERAL
   SMART_HIP_CHECK(hipGetLastError());
-  return profile ? profile_end(ctx, stream) : SMART_OK;
-}
-
-int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p) {
-  return launch_general(ctx, stream, p, 0, true);
-}
-int32_t tva_launch_general_rows(smart_ctx* ctx, hipStream_t stream, const tva_params& p, int32_t skip_rows_upto) {
-  return launch_general(ctx, stream, p, skip_rows_upto, false);
+  return profile_end(ctx, stream);
 }
 
 }  // namespace smart

@@ -155,6 +155,8 @@ __device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
 
 // What the plan records of one sequence (inputs clamped so that nothing downstream can leave
 // its arrays whatever the offsets say).
+// kAllSmall (fp8 cache): every sequence is streamed by the class-0 code, in row groups of 32 rows.
+template <bool kAllSmall = false>
 __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_nodes, int G, int max_blocks) {
   const int cap = max_blocks * kBlock;
   len = len < 0 ? 0 : (len > cap ? cap : len);
@@ -166,7 +168,10 @@ __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_n
   si.len = len;
   si.n = n;
   si.tiles = (len + kTile - 1) / kTile;
-  si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
+  if (kAllSmall)
+    si.rg = (rows + kSmallRows - 1) / kSmallRows;
+  else
+    si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
   return si;
 }
 
@@ -177,8 +182,8 @@ __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_n
 // to the class with the most work, so the classes never need more workgroups than were
 // launched.  Returns the workers per class and the first workgroup of each class (entry
 // kClasses: one past the last).
-// kOnlySmall: the fp8-cache kernel streams class 0 only (the other classes go through the general
-// kernel), so class 0 gets every workgroup.
+// kOnlySmall: the fp8-cache kernel puts every sequence in class 0 (row groups of 32 rows), so that
+// class gets every workgroup.
 template <bool kOnlySmall = false>
 __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
                                  int64_t (&first_wg)[kClasses + 1]) {
@@ -231,10 +236,10 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   const int b0 = min(batch, t * per), b1 = min(batch, b0 + per);
   int64_t units[kClasses] = {0, 0, 0}, segs[kClasses] = {0, 0, 0}, chunks = 0;
   for (int b = b0; b < b1; ++b) {
-    const SeqInfo si = sequence_info(prefix_len[b], cu_nodes[b], cu_nodes[b + 1], total_nodes, G, max_blocks);
+    const SeqInfo si = sequence_info<kOnlySmall>(prefix_len[b], cu_nodes[b], cu_nodes[b + 1], total_nodes, G, max_blocks);
     pv.info[b] = si;
     const int rows = si.n * G;
-    const int c = seq_class(rows);
+    const int c = kOnlySmall ? 0 : seq_class(rows);
     units[c] += (int64_t)si.tiles * Hkv * si.rg;
     segs[c] += Hkv * si.rg;
     chunks += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
@@ -261,7 +266,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   for (int b = b0; b < b1; ++b) {
     const SeqInfo si = pv.info[b];
     const int rows = si.n * G;
-    const int c = seq_class(rows);
+    const int c = kOnlySmall ? 0 : seq_class(rows);
     for (int k = 0; k < kClasses; ++k) {
       pv.cum_units[k][b] = u[k];
       pv.cum_segs[k][b] = (int32_t)s[k];
@@ -294,12 +299,12 @@ __device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const i
                                  int total_nodes, int G, int Hkv, int max_blocks, int workgroups, int lane) {
   const int b = min(lane, batch - 1);
   const int32_t len = prefix_len[b], base = cu_nodes[min(lane, batch)], next = cu_nodes[b + 1];
-  SeqInfo si = sequence_info(len, base, next, total_nodes, G, max_blocks);
+  SeqInfo si = sequence_info<kOnlySmall>(len, base, next, total_nodes, G, max_blocks);
   if (lane >= batch) si.len = si.n = si.tiles = si.rg = 0;
   p.si = si;
   p.cu = base;
   const int rows = si.n * G;
-  const int cls = seq_class(rows);
+  const int cls = kOnlySmall ? 0 : seq_class(rows);
   const int64_t my_units = (int64_t)si.tiles * Hkv * si.rg;
   const int64_t my_segs = Hkv * si.rg;
   int64_t tot_s, tot_c;
@@ -587,7 +592,7 @@ __device__ inline void small_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4], co
 
 template <typename Raw = bf16x8>
 __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, int g, int base, int t0,
-                                     int t1, const SeqInfo si, int lane) {
+                                     int t1, const SeqInfo si, int lane, int row0 = 0) {
   const int h = lane >> 5, j = lane & 31;
   const int M = si.n * a.G;
 #pragma unroll
@@ -597,7 +602,7 @@ __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, in
   if (t0 >= t1) return;  // this wavefront has no tile of the piece
   bf16x8 q[8];  // B operand of the score product: query row j, head dims 16 ks + 8 h ..
   {
-    const int rho = j < M ? j : M - 1;  // padding rows repeat the last real row; never read back
+    const int rho = row0 + j < M ? row0 + j : M - 1;  // padding rows repeat the last real row; never read back
     const int node = base + rho / a.G, head = g * a.G + rho % a.G;
     const __bf16* qp = a.q + ((int64_t)node * a.Hq + head) * kD + h * 8;
 #pragma unroll
@@ -811,18 +816,20 @@ __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
     if (u0 >= seq_end) { ++b; continue; }  // also skips sequences without units in this class
     const SeqInfo si = window_info(win, b);
     const int64_t local = u0 - seq_begin;
-    const int g = (int)(local / si.tiles);
+    const int seg_local = (int)(local / si.tiles);  // kv head, or (fp8) kv head x row group
+    const int g = kFp8 ? seg_local / si.rg : seg_local;
+    const int row0 = kFp8 ? (seg_local % si.rg) * kSmallRows : 0;
     const int t0 = (int)(local % si.tiles);
     const int64_t left = u1 - u0;
     const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
-    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + g;
+    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
     const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
     // this wavefront's share of the piece
     const int s0 = t0 + (int)(((int64_t)nt * wv) / kSmallWaves);
     const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kSmallWaves);
     SmallState S;
     if (kFp8) {
-      small_segment<fp8x8>(S, a, b, g, base, s0, s1, si, lane);
+      small_segment<fp8x8>(S, a, b, g, base, s0, s1, si, lane, row0);
       fold_and_store<true>(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e,
                            a.m_scale, a.o_scale);
     } else {
@@ -1341,8 +1348,8 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
 }
 
 // ---- the prefix kernel: one launch, workgroups apportioned to the classes by the plan ------
-// kFp8: the cache holds E4M3 bytes; only class 0 is streamed here (every workgroup goes to it),
-// the sequences of the other classes are left to the general kernel.
+// kFp8: the cache holds E4M3 bytes; every sequence is streamed by the class-0 code, in row groups of
+// 32 rows (a sequence with more rows re-reads its tiles once per row group).
 template <bool kFp8>
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
@@ -1458,7 +1465,7 @@ struct CombineArgs {
   float* lse;
   int32_t batch, Hq, Hkv, G;
   float scale, scale_log2e;
-  int32_t only_small;  // fp8 cache: rows of sequences outside class 0 belong to the general kernel
+  int32_t only_small;  // fp8 cache: every sequence was streamed as class 0, in row groups of 32 rows
 };
 
 __device__ inline float bf16_to_f32(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
@@ -1497,8 +1504,7 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
     b = lo;
   }
   const SeqInfo si = sload(pv.info + b);
-  const int cls = seq_class(si.n * a.G);
-  if (a.only_small && cls != 0) return;
+  const int cls = a.only_small ? 0 : seq_class(si.n * a.G);
   const int chunk_base = sload(pv.cum_chunks + b);
   const int base = sload(a.cu_nodes + b);
   const int64_t U = sload(pv.header + 2 * cls), W = sload(pv.header + 2 * cls + 1);
@@ -1652,6 +1658,8 @@ static size_t class_slots(const smart_ctx* ctx, int cls, int32_t batch, int32_t 
                           int32_t num_q_heads, int32_t num_kv_heads) {
   const int64_t G = num_q_heads / num_kv_heads;
   int64_t segs = (int64_t)num_kv_heads * batch;  // one row group per sequence in classes 0 and 1
+  // (with an fp8 cache every sequence is class 0, in row groups of 32 rows)
+  if (cls == 0) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kSmallRows - 1) / kSmallRows + batch);
   if (cls == 2) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
   return (size_t)class_workers(ctx, cls) + (size_t)segs + 1;
 }
@@ -1732,11 +1740,6 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   SMART_HIP_CHECK(hipGetLastError());
   rc = profile_end(ctx, stream);
   if (rc != SMART_OK) return rc;
-  if (fp8) {
-    // sequences with more than 32 rows per kv head: whole rows (prefix and tree part) by the general kernel
-    rc = tva_launch_general_rows(ctx, stream, p, kSmallRows);
-    if (rc != SMART_OK) return rc;
-  }
 
   CombineArgs ca;
   ca.q = (const uint16_t*)p.d_q;
