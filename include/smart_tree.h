@@ -612,6 +612,20 @@ int32_t tree_commit(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layo
                     int64_t cache_token_stride /* PLAIN only */,
                     int32_t* d_new_prefix_len, int32_t* d_status);
 
+/* tree_commit into an fp8 cache (SMART_FP8_E4M3): rows are quantised as kv_cache_write_fp8 does
+ * (E4M3 of row / scale).  src_dtype is the type of d_k_tree / d_v_tree.  Everything else, errors
+ * included, as tree_commit; SMART_EINVAL also for scales that are not positive and finite. */
+int32_t tree_commit_fp8(smart_ctx* ctx, void* stream, int32_t src_dtype, int32_t kv_layout,
+                        int32_t batch, int32_t max_depth, int32_t num_kv_heads, int32_t head_dim,
+                        int32_t block_size, int32_t max_blocks_per_seq, int32_t num_blocks,
+                        const int32_t* d_cu_nodes, const int32_t* d_accept_len, const int32_t* d_accept_path,
+                        const void* d_k_tree, const void* d_v_tree,
+                        const int32_t* d_block_table, const int32_t* d_prefix_len,
+                        void* d_k_cache, void* d_v_cache,
+                        int64_t cache_block_stride, int64_t cache_head_stride,
+                        int64_t cache_token_stride /* PLAIN only */,
+                        int32_t* d_new_prefix_len, int32_t* d_status, float k_scale, float v_scale);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,7 @@ EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_dest
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
            "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
-           "kv_cache_write", "kv_cache_write_fp8", "tree_verify_attention", "tree_accept", "tree_accept_sample", "tree_commit"]
+           "kv_cache_write", "kv_cache_write_fp8", "tree_verify_attention", "tree_accept", "tree_accept_sample", "tree_commit", "tree_commit_fp8"]
 
 
 class SmartError(RuntimeError):
@@ -141,6 +141,9 @@ def _lib():
         lib.tree_accept_sample.restype = i32
         lib.tree_accept_sample.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, i64, ctypes.c_uint64,
                                            ctypes.c_uint64, vp, vp, vp]
+        lib.tree_commit_fp8.restype = i32
+        lib.tree_commit_fp8.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
+                                        vp, vp, vp, i64, i64, i64, vp, vp, ctypes.c_float, ctypes.c_float]
         lib.tree_accept.restype = i32
         lib.tree_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         _libh = lib
@@ -589,7 +592,8 @@ class SmartTree:
 
     # -- tree_commit -------------------------------------------------------
     def tree_commit(self, cu_nodes, accept_len, accept_path, k_tree, v_tree, k_cache, v_cache, block_table,
-                    prefix_len, layout, block_size, num_blocks, block_stride, head_stride, token_stride=0):
+                    prefix_len, layout, block_size, num_blocks, block_stride, head_stride, token_stride=0,
+                    k_scale=None, v_scale=None):
         """Appends the accepted path's K/V rows to the paged cache (in place); returns
         (new_prefix_len, status)."""
         torch = _torch()
@@ -597,10 +601,14 @@ class SmartTree:
         _, Hkv, D = k_tree.shape
         new_len = torch.empty(B, dtype=torch.int32, device=cu_nodes.device)
         status = torch.empty(B, dtype=torch.int32, device=cu_nodes.device)
-        rc = _lib().tree_commit(self._h, _stream_ptr(), _dtype_code(k_tree), layout, B, accept_path.shape[1] - 1,
-                                Hkv, D, block_size, block_table.shape[1], num_blocks, _ptr(cu_nodes),
-                                _ptr(accept_len), _ptr(accept_path), _ptr(k_tree), _ptr(v_tree), _ptr(block_table),
-                                _ptr(prefix_len), _ptr(k_cache), _ptr(v_cache), block_stride, head_stride,
-                                token_stride, _ptr(new_len), _ptr(status))
+        args = (self._h, _stream_ptr(), _dtype_code(k_tree), layout, B, accept_path.shape[1] - 1,
+                Hkv, D, block_size, block_table.shape[1], num_blocks, _ptr(cu_nodes),
+                _ptr(accept_len), _ptr(accept_path), _ptr(k_tree), _ptr(v_tree), _ptr(block_table),
+                _ptr(prefix_len), _ptr(k_cache), _ptr(v_cache), block_stride, head_stride,
+                token_stride, _ptr(new_len), _ptr(status))
+        if k_cache.dtype == torch.uint8:                          # an fp8 (E4M3) cache
+            rc = _lib().tree_commit_fp8(*args, float(k_scale), float(v_scale))
+        else:
+            rc = _lib().tree_commit(*args)
         _check(rc, "tree_commit")
         return new_len, status

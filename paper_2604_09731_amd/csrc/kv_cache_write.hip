@@ -68,14 +68,22 @@ __global__ __launch_bounds__(256) void kv_cache_write_fp8_kernel(
 
 // One workgroup per (path index i, sequence b).  Every workgroup of a sequence takes the same
 // accept / refuse decision from the same inputs; workgroup i = 0 reports it.
-template <typename T>
+// C: element type of the cache (T, or uint8_t = E4M3 of source / scale).
+template <typename C, typename T>
+__device__ inline C cache_elem(T x, float scale) {
+  if constexpr (sizeof(C) == 1) return smart::float_to_fp8_e4m3(src_to_float(x) / scale);
+  else return x;
+}
+
+template <typename T, typename C>
 __global__ __launch_bounds__(256) void tree_commit_kernel(
     int layout, int batch, int max_depth, int Hkv, int D, int block_size, int max_blocks, int num_blocks,
     const int32_t* __restrict__ cu_nodes, const int32_t* __restrict__ accept_len,
     const int32_t* __restrict__ accept_path, const T* __restrict__ k_tree, const T* __restrict__ v_tree,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ prefix_len,
-    T* __restrict__ k_cache, T* __restrict__ v_cache, int64_t block_stride, int64_t head_stride,
-    int64_t token_stride, int32_t* __restrict__ new_prefix_len, int32_t* __restrict__ status) {
+    C* __restrict__ k_cache, C* __restrict__ v_cache, int64_t block_stride, int64_t head_stride,
+    int64_t token_stride, int32_t* __restrict__ new_prefix_len, int32_t* __restrict__ status,
+    float k_scale, float v_scale) {
   const int i = blockIdx.x, b = blockIdx.y;
   const int base = cu_nodes[b];
   const int n = cu_nodes[b + 1] - base;
@@ -113,22 +121,22 @@ __global__ __launch_bounds__(256) void tree_commit_kernel(
       ko = page + ((int64_t)(d / 8) * block_size + slot) * 8 + d % 8;
       vo = page + ((int64_t)(slot / 8) * D + d) * 8 + slot % 8;
     }
-    k_cache[ko] = k_tree[src + e];
-    v_cache[vo] = v_tree[src + e];
+    k_cache[ko] = cache_elem<C>(k_tree[src + e], k_scale);
+    v_cache[vo] = cache_elem<C>(v_tree[src + e], v_scale);
   }
 }
 
 }  // namespace
 
-extern "C" int32_t tree_commit(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layout,
-                               int32_t batch, int32_t max_depth, int32_t num_kv_heads, int32_t head_dim,
-                               int32_t block_size, int32_t max_blocks_per_seq, int32_t num_blocks,
-                               const int32_t* d_cu_nodes, const int32_t* d_accept_len,
-                               const int32_t* d_accept_path, const void* d_k_tree, const void* d_v_tree,
-                               const int32_t* d_block_table, const int32_t* d_prefix_len,
-                               void* d_k_cache, void* d_v_cache, int64_t cache_block_stride,
-                               int64_t cache_head_stride, int64_t cache_token_stride,
-                               int32_t* d_new_prefix_len, int32_t* d_status) {
+static int32_t commit_impl(smart_ctx* ctx, void* stream, int32_t dtype, bool fp8, int32_t kv_layout,
+                           int32_t batch, int32_t max_depth, int32_t num_kv_heads, int32_t head_dim,
+                           int32_t block_size, int32_t max_blocks_per_seq, int32_t num_blocks,
+                           const int32_t* d_cu_nodes, const int32_t* d_accept_len,
+                           const int32_t* d_accept_path, const void* d_k_tree, const void* d_v_tree,
+                           const int32_t* d_block_table, const int32_t* d_prefix_len,
+                           void* d_k_cache, void* d_v_cache, int64_t cache_block_stride,
+                           int64_t cache_head_stride, int64_t cache_token_stride,
+                           int32_t* d_new_prefix_len, int32_t* d_status, float k_scale, float v_scale) {
   if (!ctx || batch < 0 || max_depth < 0 || max_depth > SMART_MAX_NODES || num_kv_heads <= 0 ||
       head_dim <= 0 || block_size <= 0 || max_blocks_per_seq < 0 || num_blocks < 0)
     return SMART_EINVAL;
@@ -136,6 +144,7 @@ extern "C" int32_t tree_commit(smart_ctx* ctx, void* stream, int32_t dtype, int3
   if (kv_layout != SMART_KV_PLAIN && kv_layout != SMART_KV_INTERLEAVED) return SMART_EINVAL;
   if (kv_layout == SMART_KV_INTERLEAVED && (block_size % 8 != 0 || head_dim % 8 != 0))
     return SMART_EINVAL;
+  if (fp8 && (!(k_scale > 0.f) || !(k_scale < 3e38f) || !(v_scale > 0.f) || !(v_scale < 3e38f))) return SMART_EINVAL;
   const int64_t page = (int64_t)block_size * head_dim;
   if (kv_layout == SMART_KV_PLAIN && cache_token_stride < head_dim) return SMART_EINVAL;
   if (cache_head_stride < (kv_layout == SMART_KV_PLAIN ? (block_size - 1) * cache_token_stride + head_dim : page))
@@ -149,20 +158,50 @@ extern "C" int32_t tree_commit(smart_ctx* ctx, void* stream, int32_t dtype, int3
     return SMART_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   const dim3 grid(max_depth + 1, batch);
-  if (dtype == SMART_F32)
-    hipLaunchKernelGGL(tree_commit_kernel<float>, grid, dim3(256), 0, s, kv_layout, batch, max_depth,
-                       num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks, d_cu_nodes,
-                       d_accept_len, d_accept_path, (const float*)d_k_tree, (const float*)d_v_tree,
-                       d_block_table, d_prefix_len, (float*)d_k_cache, (float*)d_v_cache,
-                       cache_block_stride, cache_head_stride, cache_token_stride, d_new_prefix_len, d_status);
-  else
-    hipLaunchKernelGGL(tree_commit_kernel<uint16_t>, grid, dim3(256), 0, s, kv_layout, batch, max_depth,
-                       num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks, d_cu_nodes,
-                       d_accept_len, d_accept_path, (const uint16_t*)d_k_tree, (const uint16_t*)d_v_tree,
-                       d_block_table, d_prefix_len, (uint16_t*)d_k_cache, (uint16_t*)d_v_cache,
-                       cache_block_stride, cache_head_stride, cache_token_stride, d_new_prefix_len, d_status);
+#define SMART_LAUNCH_COMMIT(T, C)                                                                               \
+  hipLaunchKernelGGL((tree_commit_kernel<T, C>), grid, dim3(256), 0, s, kv_layout, batch, max_depth,           \
+                     num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks, d_cu_nodes,           \
+                     d_accept_len, d_accept_path, (const T*)d_k_tree, (const T*)d_v_tree, d_block_table,       \
+                     d_prefix_len, (C*)d_k_cache, (C*)d_v_cache, cache_block_stride, cache_head_stride,        \
+                     cache_token_stride, d_new_prefix_len, d_status, k_scale, v_scale)
+  if (dtype == SMART_F32) {
+    if (fp8) SMART_LAUNCH_COMMIT(float, uint8_t); else SMART_LAUNCH_COMMIT(float, float);
+  } else {
+    if (fp8) SMART_LAUNCH_COMMIT(uint16_t, uint8_t); else SMART_LAUNCH_COMMIT(uint16_t, uint16_t);
+  }
+#undef SMART_LAUNCH_COMMIT
   SMART_HIP_CHECK(hipGetLastError());
   return SMART_OK;
+}
+
+extern "C" int32_t tree_commit(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layout,
+                               int32_t batch, int32_t max_depth, int32_t num_kv_heads, int32_t head_dim,
+                               int32_t block_size, int32_t max_blocks_per_seq, int32_t num_blocks,
+                               const int32_t* d_cu_nodes, const int32_t* d_accept_len,
+                               const int32_t* d_accept_path, const void* d_k_tree, const void* d_v_tree,
+                               const int32_t* d_block_table, const int32_t* d_prefix_len,
+                               void* d_k_cache, void* d_v_cache, int64_t cache_block_stride,
+                               int64_t cache_head_stride, int64_t cache_token_stride,
+                               int32_t* d_new_prefix_len, int32_t* d_status) {
+  return commit_impl(ctx, stream, dtype, false, kv_layout, batch, max_depth, num_kv_heads, head_dim, block_size,
+                     max_blocks_per_seq, num_blocks, d_cu_nodes, d_accept_len, d_accept_path, d_k_tree, d_v_tree,
+                     d_block_table, d_prefix_len, d_k_cache, d_v_cache, cache_block_stride, cache_head_stride,
+                     cache_token_stride, d_new_prefix_len, d_status, 1.f, 1.f);
+}
+
+extern "C" int32_t tree_commit_fp8(smart_ctx* ctx, void* stream, int32_t src_dtype, int32_t kv_layout,
+                                   int32_t batch, int32_t max_depth, int32_t num_kv_heads, int32_t head_dim,
+                                   int32_t block_size, int32_t max_blocks_per_seq, int32_t num_blocks,
+                                   const int32_t* d_cu_nodes, const int32_t* d_accept_len,
+                                   const int32_t* d_accept_path, const void* d_k_tree, const void* d_v_tree,
+                                   const int32_t* d_block_table, const int32_t* d_prefix_len,
+                                   void* d_k_cache, void* d_v_cache, int64_t cache_block_stride,
+                                   int64_t cache_head_stride, int64_t cache_token_stride,
+                                   int32_t* d_new_prefix_len, int32_t* d_status, float k_scale, float v_scale) {
+  return commit_impl(ctx, stream, src_dtype, true, kv_layout, batch, max_depth, num_kv_heads, head_dim, block_size,
+                     max_blocks_per_seq, num_blocks, d_cu_nodes, d_accept_len, d_accept_path, d_k_tree, d_v_tree,
+                     d_block_table, d_prefix_len, d_k_cache, d_v_cache, cache_block_stride, cache_head_stride,
+                     cache_token_stride, d_new_prefix_len, d_status, k_scale, v_scale);
 }
 
 extern "C" int32_t kv_cache_write(smart_ctx* ctx, void* stream, int32_t dtype, int32_t kv_layout,

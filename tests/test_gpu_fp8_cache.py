@@ -200,3 +200,54 @@ def test_fp8_scales_are_applied(lib, oracle_attention):
     w = W.Workload("fp8_scales", "bf16", 3, 8, 2, 128, 0, 0, seed=5)
     for ks, vs in ((0.01, 0.3), (0.2, 0.01), (1.0, 1.0)):
         _run_fp8(lib, oracle_attention, w, cu, parent, lens, 5, k_scale=ks, v_scale=vs)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tree_commit_into_an_fp8_cache(lib, dtype):
+    """The accepted path's rows go into the fp8 cache as the writer would quantise them; the oracle commits the
+    oracle-encoded rows into a byte cache.  Lengths, status and every cache byte agree."""
+    import torch
+    from oracle import pack_accept as PA
+    rng = np.random.default_rng(12)
+    Bsz, Hkv, bs, D, max_depth, max_blocks = 6, 2, 16, 128, 5, 4
+    sizes = [int(x) for x in rng.integers(2, 30, size=Bsz)]
+    trees = [W.random_tree(n, rng, "random") for n in sizes]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate(trees).astype(np.int32)
+    N = int(cu[-1])
+    token = rng.integers(0, 4, size=N).astype(np.int32)
+    target = rng.integers(0, 4, size=N).astype(np.int32)
+    prefix_len = rng.integers(0, (max_blocks - 1) * bs, size=Bsz).astype(np.int32)
+    nb = Bsz * max_blocks + 2
+    block_table = rng.permutation(nb)[:Bsz * max_blocks].reshape(Bsz, max_blocks).astype(np.int32)
+    k_tree = W._normal(12, 1, (N, Hkv, D), 1.0, dtype)
+    v_tree = W._normal(12, 2, (N, Hkv, D), 1.0, dtype)
+    k_scale, v_scale = 0.04, 0.25
+    acc_len, acc_path, _ = lib.tree_accept(_dev(cu), _dev(parent), _dev(token), _dev(target), max_depth)
+    h_len, h_path = acc_len.cpu().numpy().copy(), acc_path.cpu().numpy().copy()
+    assert h_len.max() >= 1
+    prefix_len[1] = max_blocks * bs - int(h_len[1])           # one token too many for sequence 1
+    ref_k = rng.integers(0, 255, (nb, Hkv, bs, D)).astype(np.uint8)
+    ref_v = rng.integers(0, 255, (nb, Hkv, bs, D)).astype(np.uint8)
+    start_k, start_v = ref_k.copy(), ref_v.copy()
+    ek = F.encode(_f32(k_tree, dtype) / np.float32(k_scale))
+    ev = F.encode(_f32(v_tree, dtype) / np.float32(v_scale))
+    ref_len, ref_status = PA.commit(cu, h_len, h_path, ek, ev, ref_k, ref_v, block_table, prefix_len, max_depth)
+    assert ref_status[1] == B.SMART_ECAP
+    tk, tv = H.torch_elems(k_tree, dtype, "cuda"), H.torch_elems(v_tree, dtype, "cuda")
+    for layout in (B.SMART_KV_PLAIN, B.SMART_KV_INTERLEAVED):
+        if layout == B.SMART_KV_PLAIN:
+            kc, vc = _dev(start_k.reshape(nb, Hkv, bs * D)), _dev(start_v.reshape(nb, Hkv, bs * D))
+        else:
+            kc, vc = _dev(KL.interleave_plain_cache(start_k, "k")), _dev(KL.interleave_plain_cache(start_v, "v"))
+        new_len, status = lib.tree_commit(_dev(cu), _dev(h_len), _dev(h_path), tk, tv, kc, vc, _dev(block_table),
+                                          _dev(prefix_len), layout, bs, nb, Hkv * bs * D, bs * D, D,
+                                          k_scale=k_scale, v_scale=v_scale)
+        torch.cuda.synchronize()
+        assert status.cpu().numpy().tolist() == ref_status and new_len.cpu().numpy().tolist() == ref_len
+        if layout == B.SMART_KV_PLAIN:
+            assert np.array_equal(kc.cpu().numpy().reshape(ref_k.shape), ref_k)
+            assert np.array_equal(vc.cpu().numpy().reshape(ref_v.shape), ref_v)
+        else:
+            assert np.array_equal(kc.cpu().numpy(), KL.interleave_plain_cache(ref_k, "k"))
+            assert np.array_equal(vc.cpu().numpy(), KL.interleave_plain_cache(ref_v, "v"))
