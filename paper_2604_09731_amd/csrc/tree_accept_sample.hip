@@ -72,8 +72,8 @@ __device__ inline uint64_t wave_incl_scan(uint64_t v, int lane) {
 // Tokens per range: a 64th of the vocabulary, rounded up to whole 16-byte vectors.
 __host__ __device__ inline int range_of(int V) { return ((V + kRanges - 1) / kRanges + 3) / 4 * 4; }
 
-// Weight sums of the 64 ranges of every row.  Workgroup (row, quarter): four wavefronts, each
-// sums four consecutive ranges, one after the other, with all of a range's loads in flight.
+// Weight sums of the 64 ranges of every row.  Workgroup (row, sixteenth): four wavefronts, one
+// range each, all of the range's loads in flight at once (one memory round trip per wavefront).
 __global__ __launch_bounds__(4 * kWave) void range_sums_kernel(int total_nodes, int V, int64_t stride,
                                                                const float* __restrict__ prob,
                                                                uint64_t* __restrict__ sums) {
@@ -83,8 +83,8 @@ __global__ __launch_bounds__(4 * kWave) void range_sums_kernel(int total_nodes, 
   const int range = range_of(V);
   const bool vec = (stride % 4 == 0) && (((uintptr_t)prob & 15u) == 0);
   const float* row = prob + (size_t)node * stride;
-  for (int k = 0; k < 4; ++k) {
-    const int rg = blockIdx.y * 16 + wv * 4 + k;
+  {
+    const int rg = blockIdx.y * 4 + wv;
     const int v_begin = rg * range < V ? rg * range : V;
     const int v_end = (rg + 1) * range < V ? (rg + 1) * range : V;
     uint64_t acc = 0;
@@ -254,7 +254,7 @@ extern "C" int32_t tree_accept_sample(smart_ctx* ctx, void* stream, int32_t batc
   if (rc == SMART_OK) {
     uint64_t* sums = (uint64_t*)ctx->ws;
     if (total_nodes > 0)
-      hipLaunchKernelGGL(range_sums_kernel, dim3(total_nodes, 4), dim3(4 * kWave), 0, (hipStream_t)stream, total_nodes,
+      hipLaunchKernelGGL(range_sums_kernel, dim3(total_nodes, kRanges / 4), dim3(4 * kWave), 0, (hipStream_t)stream, total_nodes,
                          vocab, prob_row_stride, d_target_prob, sums);
     hipLaunchKernelGGL(tree_accept_sample_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch, total_nodes,
                        max_depth, vocab, prob_row_stride, d_cu_nodes, d_parent, d_token, d_target_prob, sums, seed,
