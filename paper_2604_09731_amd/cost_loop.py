@@ -37,6 +37,10 @@ def main(argv=None):
     ap.add_argument("--baseline-k", type=int, default=8)
     ap.add_argument("--baseline-depth", type=int, default=6)
     ap.add_argument("--baseline-g", type=int, default=59)
+    ap.add_argument("--with-dense", action="store_true",
+                    help="add the time of the layer's dense products at the same token count (library GEMMs through "
+                         "torch.matmul: query/key/value/output projections and a gated MLP of an 8B-class layer), so "
+                         "that the cost is that of a whole transformer layer and turns compute-bound with the batch")
     args = ap.parse_args(argv)
     assert torch.cuda.is_available(), "needs the MI355X"
     lib = B.SmartTree(0)
@@ -66,6 +70,38 @@ def main(argv=None):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / args.reps
 
+    dense_weights = None
+
+    def dense_us(tokens):
+        """Microseconds of the dense products of one 8B-class layer for `tokens` rows (not part of the library:
+        the stand-in for what surrounds the attention in a verification pass)."""
+        nonlocal dense_weights
+        if not args.with_dense:
+            return 0.0
+        hid, qkv, mlp = 4096, 4096 + 2 * 1024, 14336
+        if dense_weights is None:
+            mk = lambda a, b: torch.randn((a, b), device="cuda", dtype=torch.bfloat16) * 0.02
+            dense_weights = (mk(hid, qkv), mk(hid, hid), mk(hid, 2 * mlp), mk(mlp, hid))
+        w_qkv, w_o, w_up, w_down = dense_weights
+        x = torch.randn((tokens, hid), device="cuda", dtype=torch.bfloat16)
+        h = torch.randn((tokens, mlp), device="cuda", dtype=torch.bfloat16)
+
+        def run():
+            x @ w_qkv
+            x @ w_o
+            x @ w_up
+            h @ w_down
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / args.reps
+
     def tiled(sel, batch):
         """The trees of a selection result, repeated until there are `batch` of them."""
         n_seq = sel["cu_nodes"].shape[0] - 1
@@ -82,7 +118,7 @@ def main(argv=None):
         times = []
         for n in args.sizes:
             cu = (np.arange(batch + 1) * n).astype(np.int32)
-            times.append(time_attention(w, cu, np.tile(big[:n], batch).astype(np.int32)))
+            times.append(time_attention(w, cu, np.tile(big[:n], batch).astype(np.int32)) + dense_us(batch * n))
         sizes = np.array(args.sizes, np.float64)
         times = np.array(times)
         c_T = times[0] if args.sizes[0] == 1 else float(np.interp(1.0, sizes, times))
@@ -97,7 +133,7 @@ def main(argv=None):
         sel = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost,
                                   alpha=base.alpha, max_depth=base.max_depth, budget=n_max)
         n_sel = np.diff(sel["cu_nodes"])
-        row = dict(batch=batch, sizes=args.sizes, us=[round(float(v), 2) for v in times], c_T_us=round(float(c_T), 2),
+        row = dict(batch=batch, with_dense=bool(args.with_dense), sizes=args.sizes, us=[round(float(v), 2) for v in times], c_T_us=round(float(c_T), 2),
                    gamma=fit["gamma"], delta=fit["delta"], rho=fit["rho"],
                    rms_us=round(float(np.sqrt(fit["sse"] / len(x))), 3),
                    tree_nodes_min_median_max=[int(n_sel.min()), int(np.median(n_sel)), int(n_sel.max())],
@@ -108,7 +144,7 @@ def main(argv=None):
                                       k=args.baseline_k, max_depth=args.baseline_depth, g=min(args.baseline_g, n_max - 1))
         for name, res in (("smart", sel), ("baseline", fixed)):
             cu, parent, L_mean = tiled(res, batch)
-            us = time_attention(w, cu, parent)
+            us = time_attention(w, cu, parent) + dense_us(int(cu[-1]))
             row[name + "_us"] = round(float(us), 2)
             row[name + "_measured_R"] = round(L_mean * float(c_T) / float(us), 3)
         row["baseline_nodes"] = int(np.median(np.diff(fixed["cu_nodes"])))

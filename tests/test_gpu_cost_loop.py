@@ -19,3 +19,13 @@ def test_cost_loop_small():
     # by much (alpha < 1 makes it conservative), and both policies' trees were really run through the kernel
     assert r["baseline_nodes"] == 60 and r["smart_us"] > 0 and r["baseline_us"] > 0
     assert r["smart_measured_R"] > 0 and r["baseline_measured_R"] > 0
+
+
+def test_cost_loop_with_the_layers_dense_products():
+    from paper_2604_09731_amd import cost_loop
+    rows = cost_loop.main(["--batches", "4", "--prefix", "256", "--sizes", "1", "4", "16", "32", "--reps", "3",
+                           "--with-dense"])
+    r = rows[0]
+    assert r["with_dense"] and len(r["us"]) == 4 and all(v > 0 for v in r["us"])
+    assert r["us"][-1] > r["us"][0]                        # 128 tokens of dense work cost more than 4
+    assert r["smart_measured_R"] > 0 and r["baseline_measured_R"] > 0
