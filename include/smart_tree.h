@@ -482,8 +482,8 @@ int32_t kv_cache_write_fp8(smart_ctx* ctx, void* stream, int32_t src_dtype, int3
  * bf16 before the second product).  With an fp8 cache (kv_cache_dtype =
  * SMART_FP8_E4M3) the cached keys and values are k_scale / v_scale times the
  * stored E4M3 values (exact in bf16); everything else is as above.  (The
- * matrix-core kernel then streams every sequence in row groups of 32 rows, so
- * trees with more than 32 rows per kv head re-read their prefix per group.)
+ * matrix-core kernel then streams every sequence in row groups of 64 rows, so
+ * trees with more than 64 rows per kv head re-read their prefix per group.)
  *
  * Shapes: q, out [total_nodes][Hq][D]; k_tree, v_tree [total_nodes][Hkv][D]
  * (tree K/V are not in the cache yet); block_table [batch][max_blocks_per_seq]

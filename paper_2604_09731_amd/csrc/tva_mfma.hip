@@ -155,8 +155,8 @@ __device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
 
 // What the plan records of one sequence (inputs clamped so that nothing downstream can leave
 // its arrays whatever the offsets say).
-// kAllSmall (fp8 cache): every sequence is streamed by the class-0 code, in row groups of 32 rows.
-template <bool kAllSmall = false>
+// kAllMedium (fp8 cache): every sequence is class 1, in row groups of 64 rows.
+template <bool kAllMedium = false>
 __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_nodes, int G, int max_blocks) {
   const int cap = max_blocks * kBlock;
   len = len < 0 ? 0 : (len > cap ? cap : len);
@@ -168,8 +168,8 @@ __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_n
   si.len = len;
   si.n = n;
   si.tiles = (len + kTile - 1) / kTile;
-  if (kAllSmall)
-    si.rg = (rows + kSmallRows - 1) / kSmallRows;
+  if (kAllMedium)
+    si.rg = (rows + kMediumRows - 1) / kMediumRows;
   else
     si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
   return si;
@@ -182,12 +182,12 @@ __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_n
 // to the class with the most work, so the classes never need more workgroups than were
 // launched.  Returns the workers per class and the first workgroup of each class (entry
 // kClasses: one past the last).
-// kOnlySmall: the fp8-cache kernel puts every sequence in class 0 (row groups of 32 rows), so that
+// kOnlySmall: the fp8-cache kernel puts every sequence in class 1 (row groups of 64 rows), so that
 // class gets every workgroup.
 template <bool kOnlySmall = false>
 __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
                                  int64_t (&first_wg)[kClasses + 1]) {
-  const int64_t tot_u[kClasses] = {all_u[0], kOnlySmall ? 0 : all_u[1], kOnlySmall ? 0 : all_u[2]};
+  const int64_t tot_u[kClasses] = {kOnlySmall ? 0 : all_u[0], all_u[1], kOnlySmall ? 0 : all_u[2]};
   const int64_t weight[kClasses] = {2, 2, 3};
   const int64_t launched = workgroups > kClasses ? workgroups : kClasses;
   int64_t cost[kClasses], total = 0;
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     const SeqInfo si = sequence_info<kOnlySmall>(prefix_len[b], cu_nodes[b], cu_nodes[b + 1], total_nodes, G, max_blocks);
     pv.info[b] = si;
     const int rows = si.n * G;
-    const int c = kOnlySmall ? 0 : seq_class(rows);
+    const int c = kOnlySmall ? 1 : seq_class(rows);
     units[c] += (int64_t)si.tiles * Hkv * si.rg;
     segs[c] += Hkv * si.rg;
     chunks += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
   for (int b = b0; b < b1; ++b) {
     const SeqInfo si = pv.info[b];
     const int rows = si.n * G;
-    const int c = kOnlySmall ? 0 : seq_class(rows);
+    const int c = kOnlySmall ? 1 : seq_class(rows);
     for (int k = 0; k < kClasses; ++k) {
       pv.cum_units[k][b] = u[k];
       pv.cum_segs[k][b] = (int32_t)s[k];
@@ -304,7 +304,7 @@ __device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const i
   p.si = si;
   p.cu = base;
   const int rows = si.n * G;
-  const int cls = kOnlySmall ? 0 : seq_class(rows);
+  const int cls = kOnlySmall ? 1 : seq_class(rows);
   const int64_t my_units = (int64_t)si.tiles * Hkv * si.rg;
   const int64_t my_segs = Hkv * si.rg;
   int64_t tot_s, tot_c;
@@ -658,9 +658,10 @@ __device__ inline void state_to_lds(const SmallState& S, float* region, int lane
 // eight states (always in wavefront order, so the result does not depend on timing) and
 // stores that slice of the partial; wavefront 0 also stores the row maxima and sums.
 // kScaled (fp8 cache): the partial leaves in true units, row maxima times m_scale, O times o_scale.
-template <bool kScaled = false>
+// kSlotRows / qt: the slot holds kSlotRows rows and this is its row tile qt.
+template <bool kScaled = false, int kSlotRows = kSmallRows>
 __device__ inline void fold_and_store(const SmallState& S, float* lds, float* slot, int wv, int lane, float c,
-                                      float m_scale = 1.f, float o_scale = 1.f) {
+                                      float m_scale = 1.f, float o_scale = 1.f, int qt = 0) {
   const int h = lane >> 5, j = lane & 31;
   state_to_lds(S, lds + wv * kStateFloats, lane);
   __syncthreads();
@@ -697,13 +698,13 @@ __device__ inline void fold_and_store(const SmallState& S, float* lds, float* sl
   }
   // accumulator register 16 jt + 4 r4 + i of lane (h, j) is row j, head dims 4 (8 jt + 2 r4 + h) + i
   const int jt = wv >> 1, r4 = 2 * (wv & 1);
-  *(floatx4*)(slot + ((size_t)(jt * 8 + 2 * r4 + h) * 32 + j) * 4) = x[0];
-  *(floatx4*)(slot + ((size_t)(jt * 8 + 2 * (r4 + 1) + h) * 32 + j) * 4) = x[1];
+  *(floatx4*)(slot + ((size_t)(qt * 32 + jt * 8 + 2 * r4 + h) * 32 + j) * 4) = x[0];
+  *(floatx4*)(slot + ((size_t)(qt * 32 + jt * 8 + 2 * (r4 + 1) + h) * 32 + j) * 4) = x[1];
   if (wv == 0) {
     const float lsum = sum_across_halves(l_new);
     if (h == 0) {
-      slot[kSmallRows * kD + j] = m_new;
-      slot[kSmallRows * kD + kSmallRows + j] = lsum;
+      slot[kSlotRows * kD + qt * 32 + j] = m_new;
+      slot[kSlotRows * kD + kSlotRows + qt * 32 + j] = lsum;
     }
   }
   __syncthreads();  // the next piece reuses the LDS regions
@@ -797,7 +798,6 @@ __device__ inline void follow(ClassPlan& cp, const PlanView& pv, const int32_t* 
 // piece leaves ONE partial in memory however many wavefronts streamed it.
 constexpr int kSmallWaves = kWgWaves;
 
-template <bool kFp8 = false>
 __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 132 KB: eight states */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = cp.U, W = cp.W;
@@ -816,25 +816,113 @@ __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
     if (u0 >= seq_end) { ++b; continue; }  // also skips sequences without units in this class
     const SeqInfo si = window_info(win, b);
     const int64_t local = u0 - seq_begin;
-    const int seg_local = (int)(local / si.tiles);  // kv head, or (fp8) kv head x row group
-    const int g = kFp8 ? seg_local / si.rg : seg_local;
-    const int row0 = kFp8 ? (seg_local % si.rg) * kSmallRows : 0;
+    const int g = (int)(local / si.tiles);
     const int t0 = (int)(local % si.tiles);
     const int64_t left = u1 - u0;
     const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
-    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
+    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + g;
     const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
     // this wavefront's share of the piece
     const int s0 = t0 + (int)(((int64_t)nt * wv) / kSmallWaves);
     const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kSmallWaves);
     SmallState S;
-    if (kFp8) {
+    small_segment(S, a, b, g, base, s0, s1, si, lane);
+    fold_and_store(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e);
+    u0 += nt;
+  }
+}
+
+// ---- fp8 cache: every sequence in row groups of up to 64 rows, streamed into registers ---------
+//
+// The same register-direct stream as class 0.  A row group with more than 32 rows has two row
+// tiles, one per half of the workgroup.
+
+// A row group of two row tiles: wavefronts 0..3 carry row tile 0, wavefronts 4..7 row tile 1, each
+// half cuts the piece's tiles four ways and both halves stream the SAME tiles (the second request
+// for a tile is served by the caches, HBM sees it once).  Their states meet in LDS like the eight
+// of a one-tile piece; wavefront w then merges accumulator registers 16 (w % 4) .. + 15 of the four
+// states of row tile w / 4 (always in wavefront order) and stores that slice of the 64-row slot.
+__device__ inline void fold_halves_and_store(const SmallState& S, float* lds, float* slot, int wv, int lane, float c,
+                                             float m_scale, float o_scale) {
+  const int h = lane >> 5, j = lane & 31;
+  state_to_lds(S, lds + wv * kStateFloats, lane);
+  __syncthreads();
+  const int rt = wv >> 2, part = wv & 3;
+  float mk[4], lk[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    mk[k] = lds[(4 * rt + k) * kStateFloats + 64 * kWave + lane];
+    lk[k] = lds[(4 * rt + k) * kStateFloats + 65 * kWave + lane];
+  }
+  float m_new = fmaxf(fmaxf(mk[0], mk[1]), fmaxf(mk[2], mk[3]));
+  float l_new = 0.f;
+  floatx4 x[4] = {(floatx4)(0.f), (floatx4)(0.f), (floatx4)(0.f), (floatx4)(0.f)};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    // an empty state has max -inf and contributes nothing
+    const float sc = mk[k] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mk[k] - m_new) * c);
+    l_new += lk[k] * sc;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      floatx4 r;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[i] = lds[(4 * rt + k) * kStateFloats + (16 * part + 4 * u + i) * kWave + lane];
+      x[u] += r * sc;
+    }
+  }
+  // accumulator register 16 jt + 4 r4 + i of lane (h, j) is row j, head dims 4 (8 jt + 2 r4 + h) + i; here jt = part, r4 = u
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    *(floatx4*)(slot + ((size_t)(rt * 32 + part * 8 + 2 * u + h) * 32 + j) * 4) = x[u] * o_scale;
+  if (part == 0) {
+    const float lsum = sum_across_halves(l_new);
+    if (h == 0) {
+      slot[kMediumRows * kD + rt * 32 + j] = m_new * m_scale;  // (-inf stays -inf)
+      slot[kMediumRows * kD + kMediumRows + rt * 32 + j] = lsum;
+    }
+  }
+  __syncthreads();  // the next piece reuses the LDS regions
+}
+
+__device__ inline void fp8_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 132 KB */) {
+  const PlanView pv = plan_view(a.plan, a.batch);
+  const int64_t U = cp.U, W = cp.W;
+  PlanWindow& win = cp.win;
+  if (w >= W || U <= 0) return;
+  int64_t u0 = (w * U) / W;
+  const int64_t u1 = ((w + 1) * U) / W;
+  if (u0 >= u1) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int b = locate(cp, pv, a.cu_nodes, 1, a.batch, u0, lane);
+  while (u0 < u1 && b < a.batch) {
+    follow(cp, pv, a.cu_nodes, 1, a.batch, b, lane);
+    const int64_t seq_begin = window_cum_units(win, b - win.first);
+    const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
+    if (u0 >= seq_end) { ++b; continue; }
+    const SeqInfo si = window_info(win, b);
+    const int64_t local = u0 - seq_begin;
+    const int seg_local = (int)(local / si.tiles);  // kv head x row group of 64 rows
+    const int g = seg_local / si.rg;
+    const int row0 = (seg_local % si.rg) * kMediumRows;
+    const int t0 = (int)(local % si.tiles);
+    const int64_t left = u1 - u0;
+    const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
+    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
+    const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
+    float* slot = a.ws[1] + (size_t)(w + seg) * kMediumSlot;
+    SmallState S;
+    if (si.n * a.G - row0 <= kSmallRows) {
+      const int s0 = t0 + (int)(((int64_t)nt * wv) / kWgWaves);
+      const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kWgWaves);
       small_segment<fp8x8>(S, a, b, g, base, s0, s1, si, lane, row0);
-      fold_and_store<true>(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e,
-                           a.m_scale, a.o_scale);
+      fold_and_store<true, kMediumRows>(S, merge_lds, slot, wv, lane, a.scale_log2e, a.m_scale, a.o_scale, 0);
     } else {
-      small_segment(S, a, b, g, base, s0, s1, si, lane);
-      fold_and_store(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e);
+      const int rt = wv >> 2, sub = wv & 3;
+      const int s0 = t0 + (int)(((int64_t)nt * sub) / 4);
+      const int s1 = t0 + (int)(((int64_t)nt * (sub + 1)) / 4);
+      small_segment<fp8x8>(S, a, b, g, base, s0, s1, si, lane, row0 + rt * kSmallRows);
+      fold_halves_and_store(S, merge_lds, slot, wv, lane, a.scale_log2e, a.m_scale, a.o_scale);
     }
     u0 += nt;
   }
@@ -1348,8 +1436,8 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
 }
 
 // ---- the prefix kernel: one launch, workgroups apportioned to the classes by the plan ------
-// kFp8: the cache holds E4M3 bytes; every sequence is streamed by the class-0 code, in row groups of
-// 32 rows (a sequence with more rows re-reads its tiles once per row group).
+// kFp8: the cache holds E4M3 bytes; every sequence is class 1 (row groups of 64 rows) and streamed
+// into registers by fp8_worker (a sequence with more rows re-reads its tiles once per row group).
 template <bool kFp8>
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
@@ -1438,7 +1526,7 @@ void tva_prefix_kernel(MainArgs a) {
   }
   if (wg >= end) return;
   if (kFp8) {
-    if (wg < first1) small_worker<true>(a, wg, cp, (float*)lds_raw);
+    if (wg >= first1 && wg < first2) fp8_worker(a, wg - first1, cp, (float*)lds_raw);
     return;
   }
   if (wg < first1) {
@@ -1465,7 +1553,7 @@ struct CombineArgs {
   float* lse;
   int32_t batch, Hq, Hkv, G;
   float scale, scale_log2e;
-  int32_t only_small;  // fp8 cache: every sequence was streamed as class 0, in row groups of 32 rows
+  int32_t only_small;  // fp8 cache: every sequence was streamed as class 1, in row groups of 64 rows
 };
 
 __device__ inline float bf16_to_f32(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
@@ -1504,7 +1592,7 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
     b = lo;
   }
   const SeqInfo si = sload(pv.info + b);
-  const int cls = a.only_small ? 0 : seq_class(si.n * a.G);
+  const int cls = a.only_small ? 1 : seq_class(si.n * a.G);
   const int chunk_base = sload(pv.cum_chunks + b);
   const int base = sload(a.cu_nodes + b);
   const int64_t U = sload(pv.header + 2 * cls), W = sload(pv.header + 2 * cls + 1);
@@ -1658,8 +1746,8 @@ static size_t class_slots(const smart_ctx* ctx, int cls, int32_t batch, int32_t 
                           int32_t num_q_heads, int32_t num_kv_heads) {
   const int64_t G = num_q_heads / num_kv_heads;
   int64_t segs = (int64_t)num_kv_heads * batch;  // one row group per sequence in classes 0 and 1
-  // (with an fp8 cache every sequence is class 0, in row groups of 32 rows)
-  if (cls == 0) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kSmallRows - 1) / kSmallRows + batch);
+  // (with an fp8 cache every sequence is class 1, in row groups of 64 rows)
+  if (cls == 1) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kMediumRows - 1) / kMediumRows + batch);
   if (cls == 2) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
   return (size_t)class_workers(ctx, cls) + (size_t)segs + 1;
 }
