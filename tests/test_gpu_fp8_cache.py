@@ -251,3 +251,24 @@ def test_tree_commit_into_an_fp8_cache(lib, dtype):
         else:
             assert np.array_equal(kc.cpu().numpy(), KL.interleave_plain_cache(ref_k, "k"))
             assert np.array_equal(vc.cpu().numpy(), KL.interleave_plain_cache(ref_v, "v"))
+
+
+def test_fp8_random_shapes(lib, oracle_attention):
+    """Seeded random shapes over an fp8 cache: batches around the 64-sequence plan window, group sizes 1..16,
+    one- and two-tile row groups and trees that need several groups, ragged and empty prefixes."""
+    rng = np.random.default_rng(31)
+    for case in range(30):
+        batch = int(rng.choice([1, 2, 5, 8, 17, 33, 64, 65, 70]))
+        Hkv, G = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 7, 8, 16]))
+        lo, hi = {"small": (1, 9), "mixed": (1, 129), "big": (40, 129)}[str(rng.choice(["small", "mixed", "big"]))]
+        sizes = rng.integers(lo, hi, batch)
+        if batch * int(sizes.max()) * Hkv * G > 30000:
+            sizes = np.minimum(sizes, 20)
+        trees = [W.random_tree(int(n), rng, str(rng.choice(["random", "chain", "star"]))) for n in sizes]
+        cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        parent = np.concatenate(trees).astype(np.int32)
+        lens = rng.integers(0, int(rng.choice([40, 300, 1200])), batch).astype(np.int32)
+        lens[rng.integers(0, batch)] = int(rng.choice([0, 1, 31, 32, 33, 64]))
+        w = W.Workload("fp8_random", "bf16", batch, Hkv * G, Hkv, 128, 0, 0, seed=4000 + case)
+        _run_fp8(lib, oracle_attention, w, cu, parent, lens, 4000 + case,
+                 k_scale=float(rng.choice([0.02, 0.05, 0.3])), v_scale=float(rng.choice([0.02, 0.05, 0.3])))
