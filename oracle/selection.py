@@ -367,3 +367,47 @@ def baseline_tree(cand_parent, cand_prob, cand_token, cost, k=10, max_depth=6, g
     out.L = L
     out.R = L / float(cost[len(out)])
     return out
+
+
+# ---------------------------------------------------------------------------
+# Candidate forest of a drafter whose positions are independent (Appendix
+# "Additional Experimental Results": the block-diffusion drafter proposes top-k
+# candidates per position in one pass; the tree is the Cartesian product of the
+# positions' candidates, kept to the most probable nodes).
+# ---------------------------------------------------------------------------
+def product_forest(pos_prob, pos_token, cap):
+    """pos_prob[l][j], pos_token[l][j]: probability and token of candidate j at
+    position l (l = 0 .. d-1, j = 0 .. k-1), the same whatever came before.
+    Every sequence (j_1, .., j_l), l <= d, is a node at depth l whose parent is
+    (j_1, .., j_{l-1}); its conditional probability is pos_prob[l-1][j_l], so
+    P = product along the path, multiplied root to leaf.  Kept: the `cap` nodes
+    with the largest P, the root among them (ties: smaller depth, then the
+    lexicographically smaller sequence), listed in that order -- a parent
+    precedes its children because P(child) <= P(parent) and it is shallower.
+    Returns (cand_parent, cand_prob, cand_token, P) in candidate-forest form
+    (root first, parent = -1, probability 1.0, token -1)."""
+    d = len(pos_prob)
+    nodes = [((), 1.0)]
+    layer = [((), 1.0)]
+    for l in range(d):
+        nxt = []
+        for path, P in layer:
+            for j in range(len(pos_prob[l])):
+                nxt.append((path + (j,), P * float(pos_prob[l][j])))
+        nodes += nxt
+        layer = nxt
+    nodes.sort(key=lambda e: (-e[1], len(e[0]), e[0]))
+    nodes = nodes[:max(int(cap), 1)]
+    index = {path: i for i, (path, _P) in enumerate(nodes)}
+    cand_parent, cand_prob, cand_token, cum = [], [], [], []
+    for path, P in nodes:
+        if not path:
+            cand_parent.append(-1)
+            cand_prob.append(1.0)
+            cand_token.append(-1)
+        else:
+            cand_parent.append(index[path[:-1]])
+            cand_prob.append(float(pos_prob[len(path) - 1][path[-1]]))
+            cand_token.append(int(pos_token[len(path) - 1][path[-1]]))
+        cum.append(P)
+    return cand_parent, cand_prob, cand_token, cum

@@ -411,3 +411,92 @@ def test_smart_never_loses_to_the_baseline_in_modelled_speedup_when_the_rule_is_
         for k, g in ((2, 8), (3, 20), (3, 60)):
             base = S.baseline_tree(parent, prob, token, cost, k=k, max_depth=4, g=g)
             assert smart.R >= base.R * (1 - 1e-12)
+
+
+# ---------------------------------------------------------------------------
+# Cartesian-product candidate forest (drafter with independent positions)
+# ---------------------------------------------------------------------------
+def _product_hand_worked():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "product_forest_hand_worked.json")) as f:
+        return json.load(f)
+
+
+def test_product_forest_hand_worked_example_oracle():
+    g = _product_hand_worked()
+    for cap in range(1, 8):
+        parent, prob, token, P = S.product_forest(g["pos_prob"], g["pos_token"], cap)
+        assert parent == g["parent"][:cap] and prob == g["prob"][:cap] and token == g["token"][:cap]
+        assert P == g["P"][:cap]
+    t = g["tie_case"]
+    parent, _prob, _token, _P = S.product_forest(t["pos_prob"], [[1, 2], [3, 4]], 7)
+    assert parent == t["parent"]
+
+
+def _dyadic_positions(rng, d, k):
+    """Probabilities that are multiples of 1/64: every product of up to five of them is exact in binary64."""
+    return [[float(v) / 64.0 for v in rng.integers(1, 33, size=k)] for _ in range(d)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_product_forest_against_closed_forms_and_direct_enumeration(seed):
+    rng = np.random.default_rng(seed)
+    d, k = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    pp = _dyadic_positions(rng, d, k)
+    tok = [[100 * l + j for j in range(k)] for l in range(d)]
+    total = sum(k ** l for l in range(d + 1))
+    parent, prob, token, P = S.product_forest(pp, tok, total + 5)
+    assert len(parent) == total                                               # the whole product, nothing twice
+    depth = [0] * total
+    for u in range(1, total):
+        assert 0 <= parent[u] < u
+        depth[u] = depth[parent[u]] + 1
+        assert P[u] == P[parent[u]] * prob[u]
+    # mass of a layer = product of the positions' masses (every factor and product is exact here)
+    for l in range(d + 1):
+        want = 1.0
+        for i in range(l):
+            want *= sum(pp[i])
+        assert abs(sum(P[u] for u in range(total) if depth[u] == l) - want) < 1e-12
+    # every index sequence occurs once, with the token and probability of its last position
+    seqs = {}
+    for u in range(total):
+        s, v = [], u
+        while v:
+            s.append(v)
+            v = parent[v]
+        path = tuple(int(round(token[x] % 100)) for x in reversed(s))
+        assert all(token[x] // 100 == i for i, x in enumerate(reversed(s)))
+        seqs[path] = u
+    assert len(seqs) == total
+    direct = {path: float(np.prod([pp[i][j] for i, j in enumerate(path)])) for l in range(d + 1)
+              for path in itertools.product(range(k), repeat=l)}
+    assert all(P[seqs[path]] == direct[path] for path in direct)              # dyadic: no rounding either way
+    # a smaller cap keeps exactly the head of the full list, and nothing left out beats anything kept
+    for cap in (1, 2, total // 2 + 1, total - 1):
+        if cap < 1:
+            continue
+        p2, q2, t2, P2 = S.product_forest(pp, tok, cap)
+        assert (p2, q2, t2, P2) == (parent[:cap], prob[:cap], token[:cap], P[:cap])
+    assert all(P[u] >= P[u + 1] for u in range(total - 1))
+    order = sorted(direct.items(), key=lambda e: (-e[1], len(e[0]), e[0]))
+    assert [seqs[path] for path, _ in order] == list(range(total))
+
+
+def test_product_forest_special_cases():
+    # one candidate per position: a chain of running products
+    parent, prob, token, P = S.product_forest([[0.5], [0.25], [0.5]], [[7], [8], [9]], 10)
+    assert parent == [-1, 0, 1, 2] and token == [-1, 7, 8, 9] and P == [1.0, 0.5, 0.125, 0.0625]
+    # one position: the candidates in order of probability
+    parent, prob, token, P = S.product_forest([[0.1, 0.4, 0.2, 0.3]], [[0, 1, 2, 3]], 10)
+    assert parent == [-1, 0, 0, 0, 0] and token == [-1, 1, 3, 2, 0] and prob[1:] == [0.4, 0.3, 0.2, 0.1]
+    # the rule on such a forest with a flat cost and a budget takes the head of the list: best-first
+    # selection only ever looks at the most probable remaining candidate
+    rng = np.random.default_rng(3)
+    pp = _dyadic_positions(rng, 3, 3)
+    parent, prob, token, P = S.product_forest(pp, [[1, 2, 3]] * 3, 40)
+    cost = [1.0 + 1e-9 * n for n in range(42)]
+    t = S.select_tree(parent, prob, token, cost, alpha=1.0, max_depth=3, budget=12)
+    if len(set(P[:13])) == 13:                                               # no ties at the cut
+        assert t.cand_index == list(range(12))
