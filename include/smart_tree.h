@@ -218,6 +218,35 @@ int32_t smart_baseline_tree(
     double* h_out_L, double* h_out_R);
 
 /* ---------------------------------------------------------------------------
+ * smart_product_forest (host, batched over sequences)
+ *
+ * Candidate forest of a drafter whose positions are independent (appendix,
+ * "Additional Experimental Results": a block-diffusion drafter yields top-k
+ * candidates for every position in one pass; the tree is the Cartesian product
+ * of the positions' candidates, pruned to the most probable nodes by
+ * cumulative probability).  Every index sequence (j_1 .. j_l), l <= depth, is a
+ * node whose parent is (j_1 .. j_{l-1}) and whose conditional probability is
+ * pos_prob[l-1][j_l]; P = product along the path, multiplied root to leaf in
+ * binary64.  Kept per sequence: the `cap` nodes with the largest P, root
+ * included (ties: smaller depth, then the lexicographically smaller index
+ * sequence), listed in that order, so a parent precedes its children.  The
+ * result has the layout smart_select_tree and smart_baseline_tree read; its
+ * first g + 1 candidates are the tree "pruned to the top g".
+ *
+ * Inputs (host): h_pos_prob, h_pos_token [batch][depth][k] (probabilities in
+ * [0,1], in any order).  Outputs (host): h_cand_cu[batch+1]; per candidate the
+ * local parent index (-1 for the root), conditional probability (1.0 for the
+ * root) and token (-1 for the root); out_cap = capacity in candidates.
+ * Errors: SMART_EINVAL (null, batch < 0, depth < 0, k < 1, cap < 1, a
+ * probability outside [0,1], depth * log2(k) > 62), SMART_ECAP (out_cap below
+ * batch * min(cap, nodes of the product); nothing is written).
+ * ------------------------------------------------------------------------- */
+int32_t smart_product_forest(
+    int32_t batch, int32_t depth, int32_t k, const double* h_pos_prob, const int32_t* h_pos_token,
+    int32_t cap, int32_t* h_cand_cu, int32_t* h_cand_parent, double* h_cand_prob,
+    int32_t* h_cand_token, int64_t out_cap);
+
+/* ---------------------------------------------------------------------------
  * Algorithm 1 one layer at a time: smart_select_begin / smart_select_layer
  * (host) and smart_select_begin_device / smart_select_layer_device (device)
  *

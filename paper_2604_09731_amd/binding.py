@@ -28,7 +28,7 @@ SMART_MAX_NODES = 128
 SMART_MAX_LAYER_CAND = 2048
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
-           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_select_begin", "smart_select_layer",
+           "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_product_forest", "smart_select_begin", "smart_select_layer",
            "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
            "kv_cache_write", "kv_cache_write_fp8", "tree_verify_attention", "tree_accept", "tree_accept_sample", "tree_commit", "tree_commit_fp8"]
@@ -104,6 +104,8 @@ def _lib():
                                                   vp, vp, vp, vp, vp, i64, vp, vp]
         lib.smart_baseline_tree.restype = i32
         lib.smart_baseline_tree.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp]
+        lib.smart_product_forest.restype = i32
+        lib.smart_product_forest.argtypes = [i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, i64]
         sp = ctypes.POINTER(LayerStateStruct)
         lib.smart_select_begin.restype = i32
         lib.smart_select_begin.argtypes = [sp, vp, vp]
@@ -230,6 +232,27 @@ def smart_baseline_tree(cand_cu, cand_parent, cand_prob, cand_token, cost, k=10,
     n = int(o_cu[-1])
     return dict(cu_nodes=o_cu, parent=o_parent[:n], token=o_token[:n], cand_index=o_cand[:n], pathprob=o_pp[:n],
                 L=o_L[:batch], R=o_R[:batch])
+
+
+def smart_product_forest(pos_prob, pos_token, cap):
+    """Candidate forests of a drafter with independent positions: pos_prob, pos_token [batch][depth][k]; the `cap`
+    most probable nodes of the Cartesian product per sequence.  Returns cand_cu / cand_parent / cand_prob /
+    cand_token as smart_select_tree and smart_baseline_tree read them."""
+    pos_prob = np.ascontiguousarray(pos_prob, np.float64)
+    pos_token = np.ascontiguousarray(pos_token, np.int32)
+    if pos_prob.ndim != 3 or pos_prob.shape != pos_token.shape:
+        raise ValueError("pos_prob and pos_token must both be [batch][depth][k]")
+    batch, depth, k = (int(v) for v in pos_prob.shape)
+    total = max(1, batch * int(cap))
+    cu = np.zeros(batch + 1, np.int32)
+    parent, token = np.zeros(total, np.int32), np.zeros(total, np.int32)
+    prob = np.zeros(total, np.float64)
+    p = lambda a: ctypes.c_void_p(a.ctypes.data)
+    rc = _lib().smart_product_forest(batch, depth, k, p(pos_prob), p(pos_token), int(cap), p(cu), p(parent), p(prob),
+                                     p(token), total)
+    _check(rc, "smart_product_forest")
+    n = int(cu[-1])
+    return dict(cand_cu=cu, cand_parent=parent[:n], cand_prob=prob[:n], cand_token=token[:n])
 
 
 class HostLayerState:

@@ -7,9 +7,11 @@ sequence (the paper profiles a handful of forward passes per device), take the p
 step (a tree that is only its root) as c_T, fit the power-exponential model of Eq. "exp_model"
 to the EXTRA time over that step as a function of the drafted tokens batch * (n - 1), build the
 cost tables (cost[n] = 1 + model / c_T) and let smart_select_tree choose trees over the same
-candidate forests.  The likelihood-maximising expand-and-rerank policy (Sec. 3.1, first paragraph)
-is run over the same forests for comparison: its modelled speedup under the same cost table, and
-the measured attention time of both policies' trees.  Prints one JSON row per batch size.
+candidate forests (--forest product: those of a drafter with independent positions, the
+Cartesian-product tree of the paper's appendix).  The likelihood-maximising expand-and-rerank
+policy (Sec. 3.1, first paragraph) is run over the same forests for comparison: its modelled
+speedup under the same cost table, and the measured attention time of both policies' trees.
+Prints one JSON row per batch size.
 
 This measures ONE attention layer, not a whole target model: the point is the loop (measure,
 fit, select) on this hardware, not the absolute speedups.
@@ -37,6 +39,10 @@ def main(argv=None):
     ap.add_argument("--baseline-k", type=int, default=8)
     ap.add_argument("--baseline-depth", type=int, default=6)
     ap.add_argument("--baseline-g", type=int, default=59)
+    ap.add_argument("--forest", choices=["autoregressive", "product"], default="autoregressive",
+                    help="candidate forests: the workloads' autoregressive drafts (children conditioned on the path), "
+                         "or the Cartesian product of independent per-position top-k candidates (the tree the paper's "
+                         "appendix builds for a block-diffusion drafter), cut at 1024 candidates")
     ap.add_argument("--with-dense", action="store_true",
                     help="add the time of the layer's dense products at the same token count (library GEMMs through "
                          "torch.matmul: query/key/value/output projections and a gated MLP of an 8B-class layer), so "
@@ -129,11 +135,20 @@ def main(argv=None):
         table, dtable = B.smart_cost_tables(0.0, fit["gamma"], fit["delta"], fit["rho"], c_T, float(batch), n_max)
         # cost[n]: one plain step plus the fitted extra of the n - 1 drafted nodes
         cost = np.concatenate([[0.0], 1.0 + table[:n_max + 1]])
-        forest = W.make_forest(base.scaled(batch=min(batch, 32)))
+        if args.forest == "product":
+            import types
+            rng_f = np.random.default_rng(base.seed + 7)
+            n_f = min(batch, 32)
+            logits = rng_f.normal(0.0, 2.0, size=(n_f, base.max_depth, base.top_k))
+            pos_prob = np.exp(logits) / np.exp(logits).sum(-1, keepdims=True)      # softmax over the k candidates
+            pos_token = rng_f.integers(0, 32000, size=pos_prob.shape).astype(np.int32)
+            forest = types.SimpleNamespace(**B.smart_product_forest(pos_prob, pos_token, 1024))
+        else:
+            forest = W.make_forest(base.scaled(batch=min(batch, 32)))
         sel = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost,
                                   alpha=base.alpha, max_depth=base.max_depth, budget=n_max)
         n_sel = np.diff(sel["cu_nodes"])
-        row = dict(batch=batch, with_dense=bool(args.with_dense), sizes=args.sizes, us=[round(float(v), 2) for v in times], c_T_us=round(float(c_T), 2),
+        row = dict(batch=batch, forest=args.forest, with_dense=bool(args.with_dense), sizes=args.sizes, us=[round(float(v), 2) for v in times], c_T_us=round(float(c_T), 2),
                    gamma=fit["gamma"], delta=fit["delta"], rho=fit["rho"],
                    rms_us=round(float(np.sqrt(fit["sse"] / len(x))), 3),
                    tree_nodes_min_median_max=[int(n_sel.min()), int(np.median(n_sel)), int(n_sel.max())],

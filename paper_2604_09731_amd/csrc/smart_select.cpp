@@ -650,3 +650,80 @@ extern "C" int32_t smart_baseline_tree(
   }
   return SMART_OK;
 }
+
+// ---------------------------------------------------------------------------
+// smart_product_forest: candidate forest of a drafter whose positions are
+// independent (the paper's appendix on additional results: a block-diffusion
+// drafter proposes top-k candidates per position in one pass; the tree is the
+// Cartesian product across positions, pruned to the most probable nodes by
+// cumulative probability).  Best-first enumeration: a child is never more
+// probable than its parent and is deeper, so popping the best frontier node
+// lists the product's nodes in exactly the order (P descending, depth, index
+// sequence) without building the product.
+// ---------------------------------------------------------------------------
+namespace {
+
+struct ProductNode {
+  double P;
+  int32_t depth;
+  uint64_t code;    // index sequence read as a base-k number: lexicographic order among equal depths
+  int32_t parent;   // candidate index of the parent
+  int32_t last;     // index chosen at the last position
+};
+
+struct ProductWorse {  // std::push_heap keeps the LARGEST on top: "a < b" means a comes later in the list
+  bool operator()(const ProductNode& a, const ProductNode& b) const {
+    if (a.P != b.P) return a.P < b.P;
+    if (a.depth != b.depth) return a.depth > b.depth;
+    return a.code > b.code;
+  }
+};
+
+}  // namespace
+
+extern "C" int32_t smart_product_forest(
+    int32_t batch, int32_t depth, int32_t k, const double* h_pos_prob, const int32_t* h_pos_token, int32_t cap,
+    int32_t* h_cand_cu, int32_t* h_cand_parent, double* h_cand_prob, int32_t* h_cand_token, int64_t out_cap) {
+  if (batch < 0 || depth < 0 || k < 1 || cap < 1 || out_cap < 0 || !h_cand_cu) return SMART_EINVAL;
+  if (batch > 0 && (!h_cand_parent || !h_cand_prob || !h_cand_token)) return SMART_EINVAL;
+  if (batch > 0 && depth > 0 && (!h_pos_prob || !h_pos_token)) return SMART_EINVAL;
+  if ((double)depth * std::log2((double)k) > 62.0) return SMART_EINVAL;  // the index sequence must fit 64 bits
+  const int64_t per_seq = (int64_t)depth * k;
+  for (int64_t i = 0; i < (int64_t)batch * per_seq; ++i)
+    if (!(h_pos_prob[i] >= 0.0 && h_pos_prob[i] <= 1.0)) return SMART_EINVAL;  // also rejects NaN
+  // nodes of the whole product, saturated at cap
+  int64_t kept = 0, layer = 1;
+  for (int l = 0; l <= depth && kept < cap; ++l) {
+    kept = std::min<int64_t>(cap, kept + layer);
+    layer = std::min<int64_t>((int64_t)cap, layer * k);
+  }
+  if (kept * batch > out_cap) return SMART_ECAP;
+  std::vector<ProductNode> heap;
+  const ProductWorse worse;
+  int32_t off = 0;
+  h_cand_cu[0] = 0;
+  for (int b = 0; b < batch; ++b) {
+    const double* prob = h_pos_prob + (int64_t)b * per_seq;
+    const int32_t* token = h_pos_token + (int64_t)b * per_seq;
+    heap.clear();
+    heap.push_back(ProductNode{1.0, 0, 0, -1, -1});
+    int32_t n = 0;
+    while (n < cap && !heap.empty()) {
+      std::pop_heap(heap.begin(), heap.end(), worse);
+      const ProductNode u = heap.back();
+      heap.pop_back();
+      h_cand_parent[off + n] = u.parent;
+      h_cand_prob[off + n] = u.depth == 0 ? 1.0 : prob[(int64_t)(u.depth - 1) * k + u.last];
+      h_cand_token[off + n] = u.depth == 0 ? -1 : token[(int64_t)(u.depth - 1) * k + u.last];
+      if (u.depth < depth)
+        for (int j = 0; j < k; ++j) {
+          heap.push_back(ProductNode{u.P * prob[(int64_t)u.depth * k + j], u.depth + 1, u.code * (uint64_t)k + (uint64_t)j, n, j});
+          std::push_heap(heap.begin(), heap.end(), worse);
+        }
+      ++n;
+    }
+    off += n;
+    h_cand_cu[b + 1] = off;
+  }
+  return SMART_OK;
+}

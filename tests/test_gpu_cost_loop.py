@@ -29,3 +29,14 @@ def test_cost_loop_with_the_layers_dense_products():
     assert r["with_dense"] and len(r["us"]) == 4 and all(v > 0 for v in r["us"])
     assert r["us"][-1] > r["us"][0]                        # 128 tokens of dense work cost more than 4
     assert r["smart_measured_R"] > 0 and r["baseline_measured_R"] > 0
+
+
+def test_cost_loop_over_product_forests():
+    """Candidate forests of a drafter with independent positions (Cartesian product, cut at 1024 candidates)."""
+    from paper_2604_09731_amd import cost_loop
+    rows = cost_loop.main(["--batches", "2", "--prefix", "256", "--sizes", "1", "4", "16", "32", "--reps", "3",
+                           "--forest", "product"])
+    r = rows[0]
+    assert r["forest"] == "product" and r["baseline_nodes"] == 60
+    lo, med, hi = r["tree_nodes_min_median_max"]
+    assert 1 <= lo <= med <= hi <= 64 and r["smart_measured_R"] > 0 and r["baseline_measured_R"] > 0

@@ -406,3 +406,89 @@ def test_per_sequence_budgets_equal_one_call_per_sequence():
             B.smart_select_tree(f.cand_cu, f.cand_parent, f.cand_prob, f.cand_token, cost, budget=int(budgets.max()),
                                 budgets=bad)
         assert e.value.code == B.SMART_EINVAL
+
+
+# ---------------------------------------------------------------------------
+# Cartesian-product candidate forest (drafter with independent positions)
+# ---------------------------------------------------------------------------
+def test_product_forest_hand_worked_example_library():
+    import json
+    with open(os.path.join(os.path.dirname(__file__), "golden", "product_forest_hand_worked.json")) as f:
+        g = json.load(f)
+    for cap in range(1, 9):
+        r = B.smart_product_forest([g["pos_prob"]], [g["pos_token"]], cap)
+        n = min(cap, 7)
+        assert r["cand_cu"].tolist() == [0, n]
+        assert r["cand_parent"].tolist() == g["parent"][:n] and r["cand_prob"].tolist() == g["prob"][:n]
+        assert r["cand_token"].tolist() == g["token"][:n]
+    t = g["tie_case"]
+    r = B.smart_product_forest([t["pos_prob"]], [[[1, 2], [3, 4]]], 7)
+    assert r["cand_parent"].tolist() == t["parent"]
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_product_forest_bit_exact_against_the_oracle(seed):
+    """Softmax-of-normal position distributions (the recipe of the workloads' drafts), full products small enough
+    for the oracle to enumerate; also repeated probabilities, which exercise the tie order."""
+    rng = np.random.default_rng(100 + seed)
+    batch, d, k = 5, int(rng.integers(1, 6)), int(rng.integers(1, 5))
+    logits = rng.normal(0.0, 2.0, size=(batch, d, k + 2))
+    pp = np.exp(logits) / np.exp(logits).sum(-1, keepdims=True)
+    pp = pp[..., :k]
+    if seed % 2:
+        pp = np.round(pp * 8) / 8                                              # many equal products, some zeros
+    tok = rng.integers(0, 32000, size=(batch, d, k)).astype(np.int32)
+    total = sum(k ** l for l in range(d + 1))
+    for cap in (1, 2, 7, total // 2 + 1, total, total + 3):
+        r = B.smart_product_forest(pp, tok, cap)
+        for b in range(batch):
+            parent, prob, token, _P = S.product_forest(pp[b].tolist(), tok[b].tolist(), cap)
+            lo, hi = int(r["cand_cu"][b]), int(r["cand_cu"][b + 1])
+            assert hi - lo == min(cap, total)
+            assert r["cand_parent"][lo:hi].tolist() == parent and r["cand_prob"][lo:hi].tolist() == prob
+            assert r["cand_token"][lo:hi].tolist() == token
+
+
+def test_product_forest_feeds_both_policies():
+    """A forest cut at a cap well above the budget gives the rule the same tree as the whole product, and the
+    tree "pruned to the top g" is the head of the list."""
+    rng = np.random.default_rng(5)
+    logits = rng.normal(0.0, 2.0, size=(3, 6, 8))
+    pp = np.exp(logits) / np.exp(logits).sum(-1, keepdims=True)
+    tok = rng.integers(0, 32000, size=(3, 6, 8)).astype(np.int32)
+    cost = np.array([1.0 + 0.01 * n for n in range(66)])
+    small, large = B.smart_product_forest(pp, tok, 200), B.smart_product_forest(pp, tok, 2000)
+    sel = [B.smart_select_tree(f["cand_cu"], f["cand_parent"], f["cand_prob"], f["cand_token"], cost, alpha=0.8,
+                               max_depth=6, budget=64) for f in (small, large)]
+    assert sel[0]["cu_nodes"].tolist() == sel[1]["cu_nodes"].tolist() and sel[0]["L"].tolist() == sel[1]["L"].tolist()
+    assert sel[0]["token"].tolist() == sel[1]["token"].tolist() and sel[0]["parent"].tolist() == sel[1]["parent"].tolist()
+    fixed = B.smart_baseline_tree(small["cand_cu"], small["cand_parent"], small["cand_prob"], small["cand_token"], cost,
+                                  k=200, max_depth=6, g=59)
+    for b in range(3):
+        lo, hi = int(fixed["cu_nodes"][b]), int(fixed["cu_nodes"][b + 1])
+        assert sorted(fixed["cand_index"][lo:hi].tolist()) == list(range(60))
+    # a forest of a drafter with few confident positions is smaller than the cap
+    r = B.smart_product_forest(np.full((2, 3, 2), 0.5), np.zeros((2, 3, 2), np.int32), 100)
+    assert r["cand_cu"].tolist() == [0, 15, 30]
+
+
+def test_product_forest_error_paths():
+    pp, tok = np.full((1, 2, 2), 0.5), np.zeros((1, 2, 2), np.int32)
+    assert B.smart_product_forest(pp, tok, 3)["cand_cu"].tolist() == [0, 3]
+    for bad_pp, cap in ((np.full((1, 2, 2), 1.5), 3), (np.full((1, 2, 2), np.nan), 3), (np.full((1, 2, 2), -0.1), 3),
+                        (pp, 0), (np.full((1, 32, 4), 0.5), 3)):
+        with pytest.raises(B.SmartError) as e:
+            B.smart_product_forest(bad_pp, np.zeros(bad_pp.shape, np.int32), cap)
+        assert e.value.code == B.SMART_EINVAL
+    with pytest.raises(ValueError):
+        B.smart_product_forest(pp, np.zeros((1, 2, 3), np.int32), 3)
+    # capacity: the C entry point writes nothing when the outputs are too small
+    lib = B._lib()
+    cu, par, tk = np.full(2, -7, np.int32), np.full(2, -7, np.int32), np.full(2, -7, np.int32)
+    pr = np.full(2, -7.0)
+    p = lambda a: ctypes.c_void_p(a.ctypes.data)
+    rc = lib.smart_product_forest(1, 2, 2, p(pp), p(tok), 3, p(cu), p(par), p(pr), p(tk), 2)
+    assert rc == B.SMART_ECAP and cu.tolist() == [-7, -7] and par.tolist() == [-7, -7]
+    # depth 0: the root alone
+    r = B.smart_product_forest(np.zeros((2, 0, 3)), np.zeros((2, 0, 3), np.int32), 4)
+    assert r["cand_cu"].tolist() == [0, 1, 2] and r["cand_parent"].tolist() == [-1, -1]
