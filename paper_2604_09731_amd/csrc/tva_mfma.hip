@@ -63,6 +63,12 @@ constexpr int kCombineRows = 8;       // rows per combine wavefront (8 lanes per
 constexpr int kMinTilesPerWorker[kClasses] = {16, 16, 8};  // workers are 8-wave workgroups
 constexpr int kChunkTiles = 64;       // tiles whose block ids one pair of registers holds
 constexpr float kLog2e = 1.4426950408889634f;
+// Online softmax with a lazy reference: the value m that the exponentials are taken against follows the running
+// maximum only when the maximum has moved more than 2^kRescaleStep above it (in the exponent's units), so the
+// accumulators are rescaled a few times per segment instead of on most tiles; until then probabilities may reach
+// 2^kRescaleStep instead of 1, which binary32 sums and bf16 operands carry at the same relative precision.  The
+// partial's (m, l, O) stay consistent with each other, which is all the merges downstream need.
+constexpr float kRescaleStep = 8.f;
 
 // ---------------------------------------------------------------------------
 // launch plan (device memory; written by tva_plan_kernel, or for batches of at most 64
@@ -486,7 +492,7 @@ __device__ inline void softmax_tile(const floatx16& s, float& m, float& l, float
   for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
   mx = max_across_halves(mx);
   const float m_new = fmaxf(m, mx);
-  if (__any(m_new > m)) {  // rescale only when some row's maximum moved
+  if (__any((m_new - m) * c > kRescaleStep)) {  // the reference follows the maximum in steps: see kRescaleStep
     const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
     l *= alpha;
 #pragma unroll
@@ -1074,7 +1080,7 @@ __device__ inline void woven_tile(const floatx16& s, floatx16& s_next, floatx16 
   for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
   mx = max_across_halves(mx);
   const float m_new = fmaxf(m, mx);
-  if (__any(m_new > m)) {  // rescale only when some row's maximum moved
+  if (__any((m_new - m) * c > kRescaleStep)) {  // the reference follows the maximum in steps: see kRescaleStep
     const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
     l *= alpha;
 #pragma unroll
@@ -1176,10 +1182,12 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
     score_tile(s, rd + (t0 & (kStages - 1)) * (kStageVecs * 16), q);
     if (si.len - t0 * kTile < kTile) mask_scores(s, si.len - t0 * kTile, h);
   }
-  // iteration t: s_in holds the scores of tile t, s_out receives those of tile t + 1
-  auto iter = [&](int t, const floatx16& s_in, floatx16& s_out) {
+  // iteration t: s_in holds the scores of tile t, s_out receives those of tile t + 1.  Only a sequence's last tile
+  // can be ragged, so the iterations that land and mask a full tile (kChecked = false) carry no test for it.
+  auto iter = [&](auto checked, int t, const floatx16& s_in, floatx16& s_out) {
+    constexpr bool kChecked = decltype(checked)::value;
     asm volatile("s_waitcnt vmcnt(10)" ::: "memory");  // 2 (kStages - 3): tile t + 1 is in
-    land(t + 1);
+    if (kChecked) land(t + 1);
     // every share of tile t + 1 is visible, and everyone is done with tile t - 1
     __builtin_amdgcn_s_barrier();
     auto fetch = [&]() {
@@ -1191,21 +1199,28 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
       const uint32_t k_addr = rd + ((t + 1) & (kStages - 1)) * (kStageVecs * 16);
       const uint32_t v_addr = rd + (t & (kStages - 1)) * (kStageVecs * 16) + 8 * kWave * 16;
       woven_tile(s_in, s_out, o, m, l, q, k_addr, v_addr, c, fetch);
-      const int nv_next = si.len - (t + 1) * kTile;
-      if (nv_next < kTile) mask_scores(s_out, nv_next, h);
+      if (kChecked) {
+        const int nv_next = si.len - (t + 1) * kTile;
+        if (nv_next < kTile) mask_scores(s_out, nv_next, h);
+      }
     } else {
       fetch();
     }
     // the block ids are in before the next iteration issues its LDS reads (no wait among them)
     asm volatile("" ::"s"(nb0), "s"(nb1));
   };
+  // tile t + 1 is full for every t < len / kTile - 1
+  const int t_plain = min(t1, si.len / kTile - 1);
   floatx16 s2;
   int t = t0;
-  for (; t + 2 <= t1; t += 2) {
-    iter(t, s, s2);
-    iter(t + 1, s2, s);
+  for (; t + 2 <= t_plain; t += 2) {
+    iter(std::false_type{}, t, s, s2);
+    iter(std::false_type{}, t + 1, s2, s);
   }
-  if (t < t1) iter(t, s, s2);
+  for (; t < t1; ++t) {
+    iter(std::true_type{}, t, s, s2);
+    s = s2;
+  }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no fetch of this segment may land later
   if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane);
 }

@@ -396,3 +396,34 @@ def test_random_shapes(lib, oracle_attention, seed):
         c = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=lens, trees=(cu, parent), seed=1000 * seed + case)
         worst = max(worst, check_full(lib, oracle_attention, c))
     assert worst <= H.TOL["bf16"]
+
+
+# ----- the softmax reference follows the maximum in steps: drifting and jumping maxima ------------
+@pytest.mark.parametrize("pattern", ["drift", "spikes", "decay"])
+def test_maxima_that_drift_and_jump_along_the_prefix(lib, oracle_attention, pattern):
+    """The kernels rescale their accumulators only when the running maximum has moved well above the value the
+    exponentials are taken against.  Keys whose scores grow slowly along the prefix keep that value stale for many
+    tiles, planted spikes force the rescale, decaying scores never trigger it after the first tile; trees of every
+    class (8, 40 and 128 rows per kv head at G = 4), prefixes long enough for many tiles per wavefront."""
+    rng = np.random.default_rng(77)
+    sizes = [2, 10, 32, 7]
+    trees = [W.random_tree(n, rng, "random") for n in sizes]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    w = W.Workload("maxima_" + pattern, "bf16", 4, 16, 4, 128, 0, 0, seed=91)
+    lens = np.array([4000, 3333, 2900, 517], np.int32)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=lens, trees=(cu, np.concatenate(trees).astype(np.int32)))
+    inp = case.inp
+    k = W.bf16_bits_to_f32(inp.k_cache)
+    for b in range(4):
+        t = np.arange(int(lens[b]))
+        if pattern == "drift":
+            f = 0.1 + 5.0 * t / lens[b]                                       # score spread grows 50-fold
+        elif pattern == "decay":
+            f = 5.0 * (1.0 - t / lens[b]) + 0.05
+        else:
+            f = np.where(rng.random(len(t)) < 0.004, 9.0, 0.3)               # rare keys with 30-fold scores
+        blk, slot = inp.block_table[b][t // 16], t % 16
+        k[blk, :, slot, :] *= f[:, None, None].astype(np.float32)
+    inp.k_cache[...] = np.where(np.isnan(k), inp.k_cache, W.f32_to_bf16_bits(k))
+    case = Case(w, cu, case.parent, inp, B.SMART_KV_INTERLEAVED)
+    check_full(lib, oracle_attention, case)
