@@ -163,10 +163,12 @@ def main():
                                kc8, vc8, B.SMART_KV_INTERLEAVED, bs_, nb_, Hkv_ * bs_ * D_, bs_ * D_, *KV_SCALES)
         torch.cuda.synchronize()
         kc, vc = kc8, vc8
-    # Two copies of the cache, used on alternate steps: an fp8 cache of this size (233 MB) would otherwise stay
-    # in the 256 MB last-level cache from one step to the next, which a real model's many layers never allow.
-    # (The bf16 cache, 466 MB, does not fit anyway; it gets the same treatment.)
-    caches = [(kc, vc), (kc.clone(), vc.clone())]
+    # Several copies of the cache, used in turn from step to step, at least two and enough for 1 GiB together:
+    # a cache of a few hundred MB or less (the fp8 cache of cfg3a, 233 MB; cfg2's 34 MB) would otherwise stay in
+    # the 256 MB last-level cache from one step to the next, which a real model's many layers never allow.
+    cache_bytes = kc.numel() * kc.element_size() + vc.numel() * vc.element_size()
+    n_caches = max(2, 2 * int(np.ceil((1 << 30) / cache_bytes / 2)))     # even: copy j pairs with staging buffer j & 1
+    caches = [(kc, vc)] + [(kc.clone(), vc.clone()) for _ in range(n_caches - 1)]
     block_table = torch.from_numpy(inp.block_table).to(dev)
     prefix_len = torch.from_numpy(inp.prefix_len).to(dev)
     if forest is not None:
@@ -226,7 +228,7 @@ def main():
         if args.kv == "fp8":
             P.kv_cache_dtype = B.SMART_FP8_E4M3
             P.k_scale, P.v_scale = KV_SCALES
-        P.h_cu_nodes = stage_np[ds_index][:Bsz + 1].ctypes.data   # selection wrote it on the host
+        P.h_cu_nodes = stage_np[ds_index & 1][:Bsz + 1].ctypes.data   # selection wrote it on the host
         acc_args = (ctx, stream, Bsz, w.max_depth, vp(d_cu), vp(d_par), vp(d_tok), vp(target_next),
                     vp(accept_len), vp(accept_path), vp(bonus))
         if target_prob is not None:
@@ -235,7 +237,7 @@ def main():
         return pack_args, P, acc_args
 
     accept_call = L.tree_accept if target_prob is None else L.tree_accept_sample
-    calls = [device_calls(d_stage[0], 0), device_calls(d_stage[1], 1)]
+    calls = [device_calls(d_stage[j & 1], j) for j in range(n_caches)]
     hp = lambda t, off: ctypes.c_void_p(t.data_ptr() + 4 * off)
     upload_pack_args = [(ctx, stream, Bsz, N, hp(stage[i], 0), hp(stage[i], Bsz + 1), hp(stage[i], Bsz + 1 + cap),
                          hp(d_stage[i], 0), hp(d_stage[i], Bsz + 1), hp(d_stage[i], Bsz + 1 + cap), vp(prefix_len),
@@ -244,7 +246,7 @@ def main():
     def step(i):
         s = i & 1
         select[s]()                                              # a1: host selection
-        _, P, acc_args = calls[s]
+        _, P, acc_args = calls[i % n_caches]
         rc = L.tree_upload_pack(*upload_pack_args[s])            # tree CSR to the GPU + a2, one launch
         rc = rc or L.tree_verify_attention(ctx, stream, ctypes.byref(P))   # a3 + a4
         rc = rc or accept_call(*acc_args)                        # a5
@@ -301,7 +303,7 @@ def main():
 
     pack_args, P, acc_args = calls[0]
     import itertools
-    flip = itertools.cycle((0, 1))                              # alternate the cache copies here too
+    flip = itertools.cycle(range(n_caches))                     # go round the cache copies here too
     att_us = time_device(lambda: L.tree_verify_attention(ctx, stream, ctypes.byref(calls[next(flip)][1])))
     pack_us = time_device(lambda: L.tree_upload_pack(*upload_pack_args[0]))
     acc_us = time_device(lambda: accept_call(*acc_args))

@@ -69,6 +69,10 @@ constexpr float kLog2e = 1.4426950408889634f;
 // 2^kRescaleStep instead of 1, which binary32 sums and bf16 operands carry at the same relative precision.  The
 // partial's (m, l, O) stay consistent with each other, which is all the merges downstream need.
 constexpr float kRescaleStep = 8.f;
+// Every K/V byte of the cache is read once per call: the loads are marked nontemporal (streaming), which on this
+// machine lifts a plain read stream from about 6.1 to 7.0 TB/s.  The same hint as a cache-policy operand (the nt
+// bit) for the loads that go straight to LDS.
+constexpr int kStreamPolicy = 2;
 
 // ---------------------------------------------------------------------------
 // launch plan (device memory; written by tva_plan_kernel, or for batches of at most 64
@@ -407,7 +411,7 @@ __device__ inline void load_k(bf16x8 (&k)[8], const MainArgs& a, const TilePages
   const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
   const __bf16* kp = a.k_cache + page + (h * 16 + sigma(j & 15)) * 8;
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k[ks] = *(const bf16x8*)(kp + ks * 256);
+  for (int ks = 0; ks < 8; ++ks) k[ks] = __builtin_nontemporal_load((const bf16x8*)(kp + ks * 256));
 }
 
 // V tile as the A operand of the output product: lane (h, j) holds head dim
@@ -418,8 +422,8 @@ __device__ inline void load_v(bf16x8 (&v)[2][4], const MainArgs& a, const TilePa
   const __bf16* vp1 = a.v_cache + tp.page1 + (h * kD + j) * 8;
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt) {
-    v[0][jt] = *(const bf16x8*)(vp0 + jt * 256);
-    v[1][jt] = *(const bf16x8*)(vp1 + jt * 256);
+    v[0][jt] = __builtin_nontemporal_load((const bf16x8*)(vp0 + jt * 256));
+    v[1][jt] = __builtin_nontemporal_load((const bf16x8*)(vp1 + jt * 256));
   }
 }
 
@@ -434,7 +438,7 @@ __device__ inline void load_k(fp8x8 (&k)[8], const MainArgs& a, const TilePages&
   const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
   const uint8_t* kp = (const uint8_t*)a.k_cache + page + (h * 16 + sigma(j & 15)) * 8;
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k[ks] = *(const fp8x8*)(kp + ks * 256);
+  for (int ks = 0; ks < 8; ++ks) k[ks] = __builtin_nontemporal_load((const fp8x8*)(kp + ks * 256));
 }
 
 __device__ inline void load_v(fp8x8 (&v)[2][4], const MainArgs& a, const TilePages& tp, int lane) {
@@ -443,8 +447,8 @@ __device__ inline void load_v(fp8x8 (&v)[2][4], const MainArgs& a, const TilePag
   const uint8_t* vp1 = (const uint8_t*)a.v_cache + tp.page1 + (h * kD + j) * 8;
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt) {
-    v[0][jt] = *(const fp8x8*)(vp0 + jt * 256);
-    v[1][jt] = *(const fp8x8*)(vp1 + jt * 256);
+    v[0][jt] = __builtin_nontemporal_load((const fp8x8*)(vp0 + jt * 256));
+    v[1][jt] = __builtin_nontemporal_load((const fp8x8*)(vp1 + jt * 256));
   }
 }
 
@@ -985,8 +989,8 @@ __device__ inline void request_tile(const MainArgs& a, const FetchLane& f, int32
   const int64_t page1 = clamp_block(blk1, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
   const __bf16* src = f.base + (page0 ^ ((page0 ^ page1) & f.second_page));
   bf16x8* dst = stage + 2 * wv * kWave;
-  __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst, 16, 0, 0);
-  __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(dst + kWave), 16, 0, 0);
+  __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst, 16, 0, kStreamPolicy);
+  __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(dst + kWave), 16, 0, kStreamPolicy);
 }
 
 // LDS reads of the staged tiles are written as assembly: the compiler would otherwise wait
