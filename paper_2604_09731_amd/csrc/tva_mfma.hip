@@ -669,12 +669,17 @@ __device__ inline void state_to_lds(const SmallState& S, float* region, int lane
 // stores that slice of the partial; wavefront 0 also stores the row maxima and sums.
 // kScaled (fp8 cache): the partial leaves in true units, row maxima times m_scale, O times o_scale.
 // kSlotRows / qt: the slot holds kSlotRows rows and this is its row tile qt.
-template <bool kScaled = false, int kSlotRows = kSmallRows>
+// kLoadsInFlight: the caller has global loads outstanding that the barriers must not wait for (the next piece's
+// first tile); the barriers then only wait for this wavefront's LDS traffic.
+template <bool kScaled = false, int kSlotRows = kSmallRows, bool kLoadsInFlight = false>
 __device__ inline void fold_and_store(const SmallState& S, float* lds, float* slot, int wv, int lane, float c,
                                       float m_scale = 1.f, float o_scale = 1.f, int qt = 0) {
   const int h = lane >> 5, j = lane & 31;
   state_to_lds(S, lds + wv * kStateFloats, lane);
-  __syncthreads();
+  if (kLoadsInFlight)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else
+    __syncthreads();
   float mk[kWgWaves], lk[kWgWaves];
 #pragma unroll
   for (int k = 0; k < kWgWaves; ++k) {
@@ -717,7 +722,11 @@ __device__ inline void fold_and_store(const SmallState& S, float* lds, float* sl
       slot[kSlotRows * kD + kSlotRows + qt * 32 + j] = lsum;
     }
   }
-  __syncthreads();  // the next piece reuses the LDS regions
+  // the next piece reuses the LDS regions
+  if (kLoadsInFlight)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else
+    __syncthreads();
 }
 
 // The plan entries of 64 consecutive sequences, one per lane, fetched with one
@@ -808,10 +817,64 @@ __device__ inline void follow(ClassPlan& cp, const PlanView& pv, const int32_t* 
 // piece leaves ONE partial in memory however many wavefronts streamed it.
 constexpr int kSmallWaves = kWgWaves;
 
+// A piece: the part of a worker's unit range that lies in one (sequence, kv head) segment.
+struct SmallPiece {
+  int b, g, base, t0, nt;
+  int64_t seg;
+  SeqInfo si;
+  bool valid;
+};
+
+// The piece that starts at unit u0 of the worker's range [.., u1) (sequences without units of this class are
+// skipped; b moves along).
+__device__ inline SmallPiece small_piece(ClassPlan& cp, const PlanView& pv, const MainArgs& a, int64_t u0, int64_t u1,
+                                         int& b, int lane) {
+  SmallPiece p;
+  p.valid = false;
+  PlanWindow& win = cp.win;
+  while (u0 < u1 && b < a.batch) {
+    follow(cp, pv, a.cu_nodes, 0, a.batch, b, lane);
+    const int64_t seq_begin = window_cum_units(win, b - win.first);
+    const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
+    if (u0 >= seq_end) { ++b; continue; }
+    p.si = window_info(win, b);
+    // (the divisions run on the vector unit; everything is wavefront-uniform and goes back to scalar registers)
+    const int64_t local = u0 - seq_begin;
+    p.b = __builtin_amdgcn_readfirstlane(b);
+    p.g = __builtin_amdgcn_readfirstlane((int)(local / p.si.tiles));
+    p.t0 = __builtin_amdgcn_readfirstlane((int)(local % p.si.tiles));
+    const int64_t left = u1 - u0;
+    p.nt = __builtin_amdgcn_readfirstlane((int)(left < (int64_t)(p.si.tiles - p.t0) ? left : (int64_t)(p.si.tiles - p.t0)));
+    p.seg = uniform64((int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + p.g);
+    p.base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
+    p.valid = true;
+    break;
+  }
+  return p;
+}
+
+// Pulls what a wavefront reads first of its share of piece p into the L2 cache: the share's first K/V tile (128
+// lines of 128 bytes: lanes 0..31 the first cache block, 32..63 the second), the block ids of its first 64 tiles and
+// the query rows.  One dword per lane and line; the values are not used, only kept until the caller has folded the
+// current piece, so the requests are in flight during the fold and the share then starts on L2 hits.
+__device__ inline void small_touch(uint32_t (&touched)[4], const MainArgs& a, const SmallPiece& p, int s0, int32_t blk0,
+                                   int32_t blk1, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  const int64_t page = clamp_block(h ? blk1 : blk0, a.num_blocks) * a.block_stride + (int64_t)p.g * a.head_stride;
+  touched[0] = *(const uint32_t*)(a.k_cache + page + j * 64);
+  touched[1] = *(const uint32_t*)(a.v_cache + page + j * 64);
+  const int32_t* bt_row = a.block_table + (int64_t)p.b * a.max_blocks;
+  const int n_blocks = (p.si.len + kBlock - 1) / kBlock;
+  touched[2] = (uint32_t)bt_row[min(2 * s0 + 2 * lane, n_blocks - 1)];
+  const int M = p.si.n * a.G;
+  const int rho = j < M ? j : M - 1;
+  const int node = p.base + rho / a.G, head = p.g * a.G + rho % a.G;
+  touched[3] = *(const uint32_t*)(a.q + ((int64_t)node * a.Hq + head) * kD + h * 64);
+}
+
 __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp, float* merge_lds /* 132 KB: eight states */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = cp.U, W = cp.W;
-  PlanWindow& win = cp.win;
   if (w >= W || U <= 0) return;
   int64_t u0 = (w * U) / W;
   const int64_t u1 = ((w + 1) * U) / W;
@@ -819,26 +882,37 @@ __device__ inline void small_worker(const MainArgs& a, int64_t w, ClassPlan& cp,
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int b = locate(cp, pv, a.cu_nodes, 0, a.batch, u0, lane);
-  while (u0 < u1 && b < a.batch) {
-    follow(cp, pv, a.cu_nodes, 0, a.batch, b, lane);
-    const int64_t seq_begin = window_cum_units(win, b - win.first);
-    const int64_t seq_end = window_cum_units(win, b + 1 - win.first);
-    if (u0 >= seq_end) { ++b; continue; }  // also skips sequences without units in this class
-    const SeqInfo si = window_info(win, b);
-    const int64_t local = u0 - seq_begin;
-    const int g = (int)(local / si.tiles);
-    const int t0 = (int)(local % si.tiles);
-    const int64_t left = u1 - u0;
-    const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
-    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + g;
-    const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
-    // this wavefront's share of the piece
-    const int s0 = t0 + (int)(((int64_t)nt * wv) / kSmallWaves);
-    const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kSmallWaves);
+  SmallPiece cur = small_piece(cp, pv, a, u0, u1, b, lane);
+  while (cur.valid) {
+    // The piece after this one is located first: what this wavefront will read first of it is requested before
+    // the fold of this piece, so that the stream does not start from memory latency at every piece boundary.
+    const SmallPiece nxt = small_piece(cp, pv, a, u0 + cur.nt, u1, b, lane);
+    // this wavefront's share of the piece, and of the next
+    const int s0 = cur.t0 + (int)(((int64_t)cur.nt * wv) / kSmallWaves);
+    const int s1 = cur.t0 + (int)(((int64_t)cur.nt * (wv + 1)) / kSmallWaves);
+    int n0 = 0, n1 = 0;
+    if (nxt.valid) {
+      n0 = nxt.t0 + (int)(((int64_t)nxt.nt * wv) / kSmallWaves);
+      n1 = nxt.t0 + (int)(((int64_t)nxt.nt * (wv + 1)) / kSmallWaves);
+    }
+    const bool pre = n0 < n1;
+    // block ids of the next share's first tile: scalar loads, issued a whole share ahead
+    int32_t nb0 = 0, nb1 = 0;
+    if (pre) {
+      const int32_t* row = a.block_table + (int64_t)nxt.b * a.max_blocks;
+      const int nblk = (nxt.si.len + kBlock - 1) / kBlock;
+      nb0 = sload(row + min(2 * n0, nblk - 1));
+      nb1 = sload(row + min(2 * n0 + 1, nblk - 1));
+    }
     SmallState S;
-    small_segment(S, a, b, g, base, s0, s1, si, lane);
-    fold_and_store(S, merge_lds, a.ws[0] + (size_t)(w + seg) * kSmallSlot, wv, lane, a.scale_log2e);
-    u0 += nt;
+    small_segment(S, a, cur.b, cur.g, cur.base, s0, s1, cur.si, lane);
+    uint32_t touched[4] = {0u, 0u, 0u, 0u};
+    if (pre) small_touch(touched, a, nxt, n0, nb0, nb1, lane);
+    fold_and_store<false, kSmallRows, true>(S, merge_lds, a.ws[0] + (size_t)(w + cur.seg) * kSmallSlot, wv, lane,
+                                            a.scale_log2e);
+    asm volatile("" ::"v"(touched[0]), "v"(touched[1]), "v"(touched[2]), "v"(touched[3]));
+    u0 += cur.nt;
+    cur = nxt;
   }
 }
 
