@@ -581,15 +581,15 @@ __device__ inline TilePages pages_from_ids(const MainArgs& a, const BlockIds& id
   return tp;
 }
 
-template <bool kMasked, typename Raw>
+// One tile of a share that is not its last: the requests for the next tile go out as soon as the registers they
+// refill are free (K after the score product, V after the output product).
+template <typename Raw>
 __device__ inline void small_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4], const bf16x8 (&q)[8],
-                                  int lane, float c, int n_valid, const MainArgs& a,
-                                  const TilePages& next) {
+                                  int lane, float c, const MainArgs& a, const TilePages& next) {
   floatx16 s = (floatx16)(0.f);
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(k[ks]), q[ks], s, 0, 0, 0);
   load_k(k, a, next, lane);
-  if (kMasked) mask_tail(s, v, n_valid, lane >> 5);
   bf16x8 pb0, pb1;
   softmax_tile(s, S.m, S.l, S.o, pb0, pb1, c);
 #pragma unroll
@@ -598,6 +598,24 @@ __device__ inline void small_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4], co
     S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(v[1][jt]), pb1, S.o[jt], 0, 0, 0);
   }
   load_v(v, a, next, lane);
+}
+
+// The last tile of a share: nothing follows, so nothing is requested (the streamed lines are not kept in L2, a
+// repeated request would go to memory again); it is also the only tile that can be ragged (n_valid < 32).
+template <typename Raw>
+__device__ inline void small_last_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4], const bf16x8 (&q)[8],
+                                       int lane, float c, int n_valid) {
+  floatx16 s = (floatx16)(0.f);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(k[ks]), q[ks], s, 0, 0, 0);
+  if (n_valid < kTile) mask_tail(s, v, n_valid, lane >> 5);
+  bf16x8 pb0, pb1;
+  softmax_tile(s, S.m, S.l, S.o, pb0, pb1, c);
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(v[0][jt]), pb0, S.o[jt], 0, 0, 0);
+    S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(v[1][jt]), pb1, S.o[jt], 0, 0, 0);
+  }
 }
 
 template <typename Raw = bf16x8>
@@ -630,23 +648,22 @@ __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, in
     // Both id registers must have landed before the tile stream starts: inside the loop
     // nothing may wait on them, or the wait would also drain the K/V requests in flight.
     asm volatile("" ::"v"(ids.lo), "v"(ids.hi));
-    // complete tiles (32 valid keys) end here; at most the sequence's last tile is ragged
-    const int full_end = min(te, si.len / kTile);
     Raw k[8], v[2][4];
     {
       const TilePages first = pages_from_ids(a, ids, 0, g);
       load_k(k, a, first, lane);
       load_v(v, a, first, lane);
     }
+    // The share's last tile (which the sequence's ragged last tile always is, when the share holds it) is taken
+    // out of the loop.  A chunk that is not the share's last ends on a repeated request for its own last tile.
+    const bool ends_here = te == t1;
+    const int loop_end = ends_here ? te - 1 : te;
     int t = tc;
-    for (; t < full_end; ++t) {
+    for (; t < loop_end; ++t) {
       const TilePages next = pages_from_ids(a, ids, min(t + 1, te - 1) - tc, g);
-      small_tile<false>(S, k, v, q, lane, c, kTile, a, next);
+      small_tile(S, k, v, q, lane, c, a, next);
     }
-    if (t < te) {  // the ragged last tile of the sequence
-      const TilePages next = pages_from_ids(a, ids, te - 1 - tc, g);
-      small_tile<true>(S, k, v, q, lane, c, si.len - t * kTile, a, next);
-    }
+    if (ends_here) small_last_tile(S, k, v, q, lane, c, si.len - t * kTile);
   }
 }
 
@@ -1057,14 +1074,22 @@ __device__ inline FetchLane fetch_lane(const MainArgs& a, int wv, int lane) {
   return f;
 }
 
+// `again`: the tile is one that was requested before (a request past the end of a segment repeats the segment's last
+// tile so that every iteration issues the same number of requests; it is never consumed).  Such a request is made
+// cacheable, so that the repeats after the first hit in L2 instead of going to memory like the stream does.
 __device__ inline void request_tile(const MainArgs& a, const FetchLane& f, int32_t blk0, int32_t blk1, int g,
-                                    bf16x8* stage, int wv) {
+                                    bf16x8* stage, int wv, bool again) {
   const int64_t page0 = clamp_block(blk0, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
   const int64_t page1 = clamp_block(blk1, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
   const __bf16* src = f.base + (page0 ^ ((page0 ^ page1) & f.second_page));
   bf16x8* dst = stage + 2 * wv * kWave;
-  __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst, 16, 0, kStreamPolicy);
-  __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(dst + kWave), 16, 0, kStreamPolicy);
+  if (again) {
+    __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(dst + kWave), 16, 0, 0);
+  } else {
+    __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst, 16, 0, kStreamPolicy);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(dst + kWave), 16, 0, kStreamPolicy);
+  }
 }
 
 // LDS reads of the staged tiles are written as assembly: the compiler would otherwise wait
@@ -1249,7 +1274,7 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
   __builtin_amdgcn_s_barrier();  // the previous segment is done with every stage
 #pragma unroll
   for (int i = 0; i < kStages - 1; ++i)  // tiles t0 .. t0 + kStages - 2; past the end: the last tile again (L2 hits)
-    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv);
+    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv, t0 + i > last);
   int32_t nb0 = block_id(t0 + kStages - 1, 0), nb1 = block_id(t0 + kStages - 1, 1);
   asm volatile("" ::"s"(nb0), "s"(nb1));
   asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // 2 (kStages - 2): tile t0 is in
@@ -1269,7 +1294,7 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
     // every share of tile t + 1 is visible, and everyone is done with tile t - 1
     __builtin_amdgcn_s_barrier();
     auto fetch = [&]() {
-      request_tile(a, f, nb0, nb1, g, stage_of(t + kStages - 1), wv);
+      request_tile(a, f, nb0, nb1, g, stage_of(t + kStages - 1), wv, t + kStages - 1 > last);
       nb0 = block_id(t + kStages, 0);
       nb1 = block_id(t + kStages, 1);
     };
@@ -1447,7 +1472,7 @@ __device__ inline void grouped_segment(const MainArgs& a, int b, int g, int base
   __builtin_amdgcn_s_barrier();  // the previous segment is done with the LDS
 #pragma unroll
   for (int i = 0; i < kAhead * K; ++i)  // past the end: the last tile again (L2 hits), never consumed
-    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv);
+    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv, t0 + i > last);
   int32_t nb[K][2];
 #pragma unroll
   for (int x = 0; x < K; ++x) {
@@ -1467,7 +1492,7 @@ __device__ inline void grouped_segment(const MainArgs& a, int b, int g, int base
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int x = 0; x < K; ++x)
-      request_tile(a, f, nb[x][0], nb[x][1], g, stage_of(tb + kAhead * K + x), wv);
+      request_tile(a, f, nb[x][0], nb[x][1], g, stage_of(tb + kAhead * K + x), wv, tb + kAhead * K + x > last);
 #pragma unroll
     for (int x = 0; x < K; ++x) {
       nb[x][0] = block_id(tb + (kAhead + 1) * K + x, 0);
