@@ -401,8 +401,17 @@ __device__ inline TilePages tile_pages(const MainArgs& a, const int32_t* bt_row,
   return tp;
 }
 
+// A load of cache contents that this call reads once (kStream: marked nontemporal) or that another wavefront or a
+// later row group reads again (left to the caches).
+template <bool kStream, typename T>
+__device__ inline T stream_load(const T* p) {
+  if (kStream) return __builtin_nontemporal_load(p);
+  return *p;
+}
+
 // K tile as the A operand of the score product: lane (h, j) holds key row j,
 // head dims 16 ks + 8 h .. + 7 for k step ks.
+template <bool kStream>
 __device__ inline void load_k(bf16x8 (&k)[8], const MainArgs& a, const TilePages& tp, int lane) {
   const int h = lane >> 5, j = lane & 31;
   // rows 0..15 come from the tile's first cache block, rows 16..31 from its second
@@ -411,19 +420,20 @@ __device__ inline void load_k(bf16x8 (&k)[8], const MainArgs& a, const TilePages
   const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
   const __bf16* kp = a.k_cache + page + (h * 16 + sigma(j & 15)) * 8;
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k[ks] = __builtin_nontemporal_load((const bf16x8*)(kp + ks * 256));
+  for (int ks = 0; ks < 8; ++ks) k[ks] = stream_load<kStream>((const bf16x8*)(kp + ks * 256));
 }
 
 // V tile as the A operand of the output product: lane (h, j) holds head dim
 // 32 jt + j, tokens 8 h .. 8 h + 7 of cache block kk.
+template <bool kStream>
 __device__ inline void load_v(bf16x8 (&v)[2][4], const MainArgs& a, const TilePages& tp, int lane) {
   const int h = lane >> 5, j = lane & 31;
   const __bf16* vp0 = a.v_cache + tp.page0 + (h * kD + j) * 8;
   const __bf16* vp1 = a.v_cache + tp.page1 + (h * kD + j) * 8;
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt) {
-    v[0][jt] = __builtin_nontemporal_load((const bf16x8*)(vp0 + jt * 256));
-    v[1][jt] = __builtin_nontemporal_load((const bf16x8*)(vp1 + jt * 256));
+    v[0][jt] = stream_load<kStream>((const bf16x8*)(vp0 + jt * 256));
+    v[1][jt] = stream_load<kStream>((const bf16x8*)(vp1 + jt * 256));
   }
 }
 
@@ -432,23 +442,25 @@ __device__ inline void load_v(bf16x8 (&v)[2][4], const MainArgs& a, const TilePa
 typedef __attribute__((ext_vector_type(2))) uint32_t fp8x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
+template <bool kStream>
 __device__ inline void load_k(fp8x8 (&k)[8], const MainArgs& a, const TilePages& tp, int lane) {
   const int h = lane >> 5, j = lane & 31;
   const int64_t mask = -(int64_t)(j >> 4);
   const int64_t page = tp.page0 ^ ((tp.page0 ^ tp.page1) & mask);
   const uint8_t* kp = (const uint8_t*)a.k_cache + page + (h * 16 + sigma(j & 15)) * 8;
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k[ks] = __builtin_nontemporal_load((const fp8x8*)(kp + ks * 256));
+  for (int ks = 0; ks < 8; ++ks) k[ks] = stream_load<kStream>((const fp8x8*)(kp + ks * 256));
 }
 
+template <bool kStream>
 __device__ inline void load_v(fp8x8 (&v)[2][4], const MainArgs& a, const TilePages& tp, int lane) {
   const int h = lane >> 5, j = lane & 31;
   const uint8_t* vp0 = (const uint8_t*)a.v_cache + tp.page0 + (h * kD + j) * 8;
   const uint8_t* vp1 = (const uint8_t*)a.v_cache + tp.page1 + (h * kD + j) * 8;
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt) {
-    v[0][jt] = __builtin_nontemporal_load((const fp8x8*)(vp0 + jt * 256));
-    v[1][jt] = __builtin_nontemporal_load((const fp8x8*)(vp1 + jt * 256));
+    v[0][jt] = stream_load<kStream>((const fp8x8*)(vp0 + jt * 256));
+    v[1][jt] = stream_load<kStream>((const fp8x8*)(vp1 + jt * 256));
   }
 }
 
@@ -583,13 +595,13 @@ __device__ inline TilePages pages_from_ids(const MainArgs& a, const BlockIds& id
 
 // One tile of a share that is not its last: the requests for the next tile go out as soon as the registers they
 // refill are free (K after the score product, V after the output product).
-template <typename Raw>
+template <bool kStream, typename Raw>
 __device__ inline void small_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4], const bf16x8 (&q)[8],
                                   int lane, float c, const MainArgs& a, const TilePages& next) {
   floatx16 s = (floatx16)(0.f);
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(k[ks]), q[ks], s, 0, 0, 0);
-  load_k(k, a, next, lane);
+  load_k<kStream>(k, a, next, lane);
   bf16x8 pb0, pb1;
   softmax_tile(s, S.m, S.l, S.o, pb0, pb1, c);
 #pragma unroll
@@ -597,7 +609,7 @@ __device__ inline void small_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4], co
     S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(v[0][jt]), pb0, S.o[jt], 0, 0, 0);
     S.o[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(v[1][jt]), pb1, S.o[jt], 0, 0, 0);
   }
-  load_v(v, a, next, lane);
+  load_v<kStream>(v, a, next, lane);
 }
 
 // The last tile of a share: nothing follows, so nothing is requested (the streamed lines are not kept in L2, a
@@ -618,7 +630,8 @@ __device__ inline void small_last_tile(SmallState& S, Raw (&k)[8], Raw (&v)[2][4
   }
 }
 
-template <typename Raw = bf16x8>
+// kStream: no other wavefront and no later row group reads these tiles (see stream_load).
+template <typename Raw = bf16x8, bool kStream = true>
 __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, int g, int base, int t0,
                                      int t1, const SeqInfo si, int lane, int row0 = 0) {
   const int h = lane >> 5, j = lane & 31;
@@ -651,8 +664,8 @@ __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, in
     Raw k[8], v[2][4];
     {
       const TilePages first = pages_from_ids(a, ids, 0, g);
-      load_k(k, a, first, lane);
-      load_v(v, a, first, lane);
+      load_k<kStream>(k, a, first, lane);
+      load_v<kStream>(v, a, first, lane);
     }
     // The share's last tile (which the sequence's ragged last tile always is, when the share holds it) is taken
     // out of the loop.  A chunk that is not the share's last ends on a repeated request for its own last tile.
@@ -661,7 +674,7 @@ __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, in
     int t = tc;
     for (; t < loop_end; ++t) {
       const TilePages next = pages_from_ids(a, ids, min(t + 1, te - 1) - tc, g);
-      small_tile(S, k, v, q, lane, c, a, next);
+      small_tile<kStream>(S, k, v, q, lane, c, a, next);
     }
     if (ends_here) small_last_tile(S, k, v, q, lane, c, si.len - t * kTile);
   }
@@ -1016,13 +1029,18 @@ __device__ inline void fp8_worker(const MainArgs& a, int64_t w, ClassPlan& cp, f
     if (si.n * a.G - row0 <= kSmallRows) {
       const int s0 = t0 + (int)(((int64_t)nt * wv) / kWgWaves);
       const int s1 = t0 + (int)(((int64_t)nt * (wv + 1)) / kWgWaves);
-      small_segment<fp8x8>(S, a, b, g, base, s0, s1, si, lane, row0);
+      // a tree with one tile of rows reads every K/V tile once; otherwise the other half of the workgroup or the
+      // other row groups read the same tiles again, out of the caches
+      if (si.rg == 1)
+        small_segment<fp8x8, true>(S, a, b, g, base, s0, s1, si, lane, row0);
+      else
+        small_segment<fp8x8, false>(S, a, b, g, base, s0, s1, si, lane, row0);
       fold_and_store<true, kMediumRows>(S, merge_lds, slot, wv, lane, a.scale_log2e, a.m_scale, a.o_scale, 0);
     } else {
       const int rt = wv >> 2, sub = wv & 3;
       const int s0 = t0 + (int)(((int64_t)nt * sub) / 4);
       const int s1 = t0 + (int)(((int64_t)nt * (sub + 1)) / 4);
-      small_segment<fp8x8>(S, a, b, g, base, s0, s1, si, lane, row0 + rt * kSmallRows);
+      small_segment<fp8x8, false>(S, a, b, g, base, s0, s1, si, lane, row0 + rt * kSmallRows);
       fold_halves_and_store(S, merge_lds, slot, wv, lane, a.scale_log2e, a.m_scale, a.o_scale);
     }
     u0 += nt;
@@ -1074,9 +1092,10 @@ __device__ inline FetchLane fetch_lane(const MainArgs& a, int wv, int lane) {
   return f;
 }
 
-// `again`: the tile is one that was requested before (a request past the end of a segment repeats the segment's last
-// tile so that every iteration issues the same number of requests; it is never consumed).  Such a request is made
-// cacheable, so that the repeats after the first hit in L2 instead of going to memory like the stream does.
+// `again`: the tile is requested more than once -- a request past the end of a segment repeats the segment's last
+// tile so that every iteration issues the same number of requests (it is never consumed), and a tree with several row
+// groups streams the prefix once per group.  Such requests are left cacheable, so that the repeats can hit in L2 or
+// the last-level cache instead of going to memory like the read-once stream does.
 __device__ inline void request_tile(const MainArgs& a, const FetchLane& f, int32_t blk0, int32_t blk1, int g,
                                     bf16x8* stage, int wv, bool again) {
   const int64_t page0 = clamp_block(blk0, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
@@ -1274,7 +1293,7 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
   __builtin_amdgcn_s_barrier();  // the previous segment is done with every stage
 #pragma unroll
   for (int i = 0; i < kStages - 1; ++i)  // tiles t0 .. t0 + kStages - 2; past the end: the last tile again (L2 hits)
-    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv, t0 + i > last);
+    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv, t0 + i > last || si.rg > 1);
   int32_t nb0 = block_id(t0 + kStages - 1, 0), nb1 = block_id(t0 + kStages - 1, 1);
   asm volatile("" ::"s"(nb0), "s"(nb1));
   asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // 2 (kStages - 2): tile t0 is in
@@ -1294,7 +1313,7 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
     // every share of tile t + 1 is visible, and everyone is done with tile t - 1
     __builtin_amdgcn_s_barrier();
     auto fetch = [&]() {
-      request_tile(a, f, nb0, nb1, g, stage_of(t + kStages - 1), wv, t + kStages - 1 > last);
+      request_tile(a, f, nb0, nb1, g, stage_of(t + kStages - 1), wv, t + kStages - 1 > last || si.rg > 1);
       nb0 = block_id(t + kStages, 0);
       nb1 = block_id(t + kStages, 1);
     };
@@ -1472,7 +1491,7 @@ __device__ inline void grouped_segment(const MainArgs& a, int b, int g, int base
   __builtin_amdgcn_s_barrier();  // the previous segment is done with the LDS
 #pragma unroll
   for (int i = 0; i < kAhead * K; ++i)  // past the end: the last tile again (L2 hits), never consumed
-    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv, t0 + i > last);
+    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv, t0 + i > last || si.rg > 1);
   int32_t nb[K][2];
 #pragma unroll
   for (int x = 0; x < K; ++x) {
@@ -1492,7 +1511,7 @@ __device__ inline void grouped_segment(const MainArgs& a, int b, int g, int base
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int x = 0; x < K; ++x)
-      request_tile(a, f, nb[x][0], nb[x][1], g, stage_of(tb + kAhead * K + x), wv, tb + kAhead * K + x > last);
+      request_tile(a, f, nb[x][0], nb[x][1], g, stage_of(tb + kAhead * K + x), wv, tb + kAhead * K + x > last || si.rg > 1);
 #pragma unroll
     for (int x = 0; x < K; ++x) {
       nb[x][0] = block_id(tb + (kAhead + 1) * K + x, 0);
