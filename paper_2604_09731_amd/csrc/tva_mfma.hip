@@ -1579,7 +1579,9 @@ template <bool kFp8>
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
   __shared__ float4 lds_raw[8448];  // 132 KB, carved up per class (class 0: eight states of 16.5 KB)
-  const int64_t wg = blockIdx.x;
+  // Workgroups are dealt to the eight XCDs round robin; consecutive WORKERS (consecutive unit ranges: the row groups
+  // of one segment, the two ends of a segment) are put on one XCD so that what they read in common meets in its L2.
+  const int64_t wg = gridDim.x % 8 == 0 ? (int64_t)(blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8 : (int64_t)blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   ClassPlan cp;
