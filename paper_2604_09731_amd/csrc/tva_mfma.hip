@@ -568,9 +568,11 @@ __device__ inline int find_sequence(const int64_t* cum_units, int batch, int64_t
 // K and V each have one register buffer.  The loop body is straight-line:
 // scores -> request next K -> softmax -> output product -> request next V, so
 // each request is in flight during the other half of the iteration and during
-// the co-resident wavefront's work (two wavefronts per SIMD).  Requests past
-// the end of the range are clamped to its last tile (an L2 hit) rather than
-// predicated, which keeps the hardware wait counters exact.
+// the co-resident wavefront's work (two wavefronts per SIMD).  The last tile
+// of a wavefront's share is taken out of the loop and requests nothing (the
+// loop body itself has no conditional request, which keeps the hardware wait
+// counters exact); within a share longer than 64 tiles, a 64-tile chunk ends on
+// a repeated request for its own last tile.
 struct SmallState {
   floatx16 o[4];
   float m, l;
