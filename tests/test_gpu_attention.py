@@ -427,3 +427,22 @@ def test_maxima_that_drift_and_jump_along_the_prefix(lib, oracle_attention, patt
     inp.k_cache[...] = np.where(np.isnan(k), inp.k_cache, W.f32_to_bf16_bits(k))
     case = Case(w, cu, case.parent, inp, B.SMART_KV_INTERLEAVED)
     check_full(lib, oracle_attention, case)
+
+
+# ----- a wavefront's share of a piece longer than the 64 tiles its block-id registers hold -----------
+def test_long_prefix_few_workers_shares_of_several_chunks(lib, oracle_attention):
+    """One sequence with 1251 tiles (ragged end) and a tree of one row tile: with one or two workers a piece is a
+    whole (sequence, kv head) segment and every wavefront's share of it is about 156 tiles, i.e. three refills of
+    its block-id registers.  (The fp8 cache streams through the same loop: tests/test_gpu_fp8_cache.py.)"""
+    rng = np.random.default_rng(3)
+    sizes = [2, 3]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([W.random_tree(n, rng, "random") for n in sizes]).astype(np.int32)
+    w = W.Workload("long", "bf16", 2, 8, 2, 128, 0, 0, seed=17)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([40011, 70], np.int32), trees=(cu, parent), seed=17)
+    for workers in (1, 2, 0):
+        lib.set_option(B.SMART_OPT_TVA_WORKERS, workers)
+        try:
+            check_full(lib, oracle_attention, case)
+        finally:
+            lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)

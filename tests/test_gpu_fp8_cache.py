@@ -124,6 +124,40 @@ def test_attention_over_an_fp8_cache(lib, oracle_attention, dtype, layout, D):
     assert H.rel_err(ref, ref0) > 1e-3
 
 
+def test_fp8_long_prefix_few_workers_shares_of_several_chunks(lib, oracle_attention):
+    """A wavefront's share of a piece longer than the 64 tiles its block-id registers hold (one or two workers, one
+    sequence of 1251 tiles with a ragged end), for trees of one row tile, of two (the halves of the workgroup stream
+    the same tiles) and of several row groups."""
+    import torch
+    rng = np.random.default_rng(3)
+    sizes = [2, 12, 40]                                              # 8, 48 and 160 rows per kv head at G = 4
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([W.random_tree(n, rng, "random") for n in sizes]).astype(np.int32)
+    lens = np.array([40011, 20500, 70], np.int32)
+    w = W.Workload("fp8long", "bf16", 3, 8, 2, 128, 0, 0, seed=19)
+    ks, vs = 0.05, 0.02
+    inp, kc, vc, kq, vq = _fp8_case(lib, w, cu, parent, lens, ks, vs, B.SMART_KV_INTERLEAVED, 19)
+    f64 = lambda x: W.bf16_bits_to_f32(x).astype(np.float64)
+    d_cu, d_par, d_len = _dev(cu), _dev(parent), _dev(lens)
+    _, _, _, mask, _ = lib.tree_pack(d_cu, d_par, d_len)
+    nb, Hkv, bs, D = inp.k_cache.shape
+    kc4, vc4 = kc.view(nb, Hkv, D // 8, bs, 8), vc.view(nb, Hkv, bs // 8, D, 8)
+    ref, _ = oracle_attention.tree_attention(f64(inp.q), f64(inp.k_tree), f64(inp.v_tree), kq, vq, inp.block_table,
+                                             lens, cu, parent, inp.scale)
+    q, kt, vt = (H.torch_elems(x, "bf16", "cuda") for x in (inp.q, inp.k_tree, inp.v_tree))
+    for workers in (1, 2, 0):
+        lib.set_option(B.SMART_OPT_TVA_WORKERS, workers)
+        try:
+            out, _ = lib.tree_verify_attention(q, kt, vt, kc4, vc4, _dev(inp.block_table), d_len, d_cu, mask, inp.scale,
+                                               B.SMART_KV_INTERLEAVED, block_size=bs, want_lse=True, k_scale=ks, v_scale=vs)
+            torch.cuda.synchronize()
+        finally:
+            lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
+        got = H.out_to_f64(out, "bf16")
+        assert np.isfinite(got).all()
+        assert H.rel_err(got, ref) <= H.TOL["bf16"], (workers, H.rel_err(got, ref))
+
+
 def test_fp8_argument_checks(lib):
     import ctypes
     import torch
