@@ -66,10 +66,20 @@ __global__ __launch_bounds__(kWave) void tree_pack_kernel(
                 position, node_seq, anc_mask, status);
 }
 
+// The offsets of a batch of at most 64 sequences travel in the kernel arguments (the host reads
+// them from the pinned array when it launches), which saves the first of two round trips over
+// the host link.
+constexpr int kCuInArgs = 64;
+struct CuArgs {
+  int32_t v[kCuInArgs + 1];
+};
+
 // tree_upload of the selected trees and tree_pack in one launch: the wavefront of sequence b
-// fetches its tree from pinned host memory (two round trips over the host link: offsets, then
-// nodes), leaves device copies for the kernels that follow, and packs from LDS.
+// fetches its tree from pinned host memory (offsets -- unless they came with the arguments --
+// then nodes: a round trip over the host link each), leaves device copies for the kernels that
+// follow, and packs from LDS.
 __global__ __launch_bounds__(kWave) void tree_upload_pack_kernel(
+    const CuArgs cu_args, int cu_in_args,
     int batch, int total_nodes, const int32_t* __restrict__ h_cu_nodes, const int32_t* __restrict__ h_parent,
     const int32_t* __restrict__ h_token, int32_t* __restrict__ cu_nodes, int32_t* __restrict__ parent,
     int32_t* __restrict__ token, const int32_t* __restrict__ prefix_len, int32_t* __restrict__ depth,
@@ -79,8 +89,8 @@ __global__ __launch_bounds__(kWave) void tree_upload_pack_kernel(
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
   if (b >= batch) return;
-  const int base = h_cu_nodes[b];
-  const int end = h_cu_nodes[b + 1];
+  const int base = cu_in_args ? cu_args.v[b] : h_cu_nodes[b];
+  const int end = cu_in_args ? cu_args.v[b + 1] : h_cu_nodes[b + 1];
   const int len = prefix_len[b];
   if (lane == 0) {
     cu_nodes[b] = base;
@@ -241,8 +251,11 @@ extern "C" int32_t tree_upload_pack(smart_ctx* ctx, void* stream, int32_t batch,
   if (!device_can_address(h_pinned_cu_nodes) || (total_nodes > 0 && !device_can_address(h_pinned_parent)) ||
       (h_pinned_token && total_nodes > 0 && !device_can_address(h_pinned_token)))
     return SMART_EINVAL;
-  hipLaunchKernelGGL(tree_upload_pack_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, batch,
-                     total_nodes, h_pinned_cu_nodes, h_pinned_parent, h_pinned_token, d_cu_nodes, d_parent,
+  CuArgs cu_args;
+  const int cu_in_args = batch <= kCuInArgs;
+  for (int b = 0; b <= kCuInArgs; ++b) cu_args.v[b] = cu_in_args && b <= batch ? h_pinned_cu_nodes[b] : 0;
+  hipLaunchKernelGGL(tree_upload_pack_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, cu_args, cu_in_args,
+                     batch, total_nodes, h_pinned_cu_nodes, h_pinned_parent, h_pinned_token, d_cu_nodes, d_parent,
                      d_token, d_prefix_len, d_depth, d_position, d_node_seq, d_anc_mask, d_status);
   SMART_HIP_CHECK(hipGetLastError());
   return SMART_OK;
