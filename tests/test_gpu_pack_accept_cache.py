@@ -263,3 +263,33 @@ def test_tree_upload_pack_equals_upload_then_pack(lib, seed):
     # pageable memory is refused
     with pytest.raises(B.SmartError):
         lib.tree_upload_pack(torch.from_numpy(cu), pin(parent), pin(token), _dev(prefix_len))
+
+
+@pytest.mark.parametrize("batch", [64, 65, 150])
+def test_tree_upload_pack_offsets_in_the_arguments_or_fetched(lib, batch):
+    """Up to 64 sequences the offsets travel with the launch, above that the kernel fetches them from the pinned
+    array: both leave the same copies and packing; offsets that leave the node arrays are reported per sequence."""
+    import torch
+    rng0 = np.random.default_rng(batch)
+    sizes = [int(n) for n in rng0.integers(1, 12, size=batch)]
+    cu, parent, rng = _random_batch(500 + batch, sizes, ["random"] * batch)
+    N = int(cu[-1])
+    token = rng.integers(0, 1000, size=N).astype(np.int32)
+    prefix_len = rng.integers(0, 5000, size=batch).astype(np.int32)
+    pin = lambda a: torch.from_numpy(np.ascontiguousarray(a)).pin_memory()
+    d_cu, d_par, d_tok, depth, position, node_seq, mask, status = lib.tree_upload_pack(
+        pin(cu), pin(parent), pin(token), _dev(prefix_len))
+    torch.cuda.synchronize()
+    assert np.array_equal(d_cu.cpu().numpy(), cu) and np.array_equal(d_par.cpu().numpy(), parent)
+    assert np.array_equal(d_tok.cpu().numpy(), token) and not status.cpu().numpy().any()
+    r_depth, r_pos, r_seq, r_mask = PA.pack(cu, parent, prefix_len)
+    assert np.array_equal(depth.cpu().numpy(), np.array(r_depth)) and np.array_equal(position.cpu().numpy(), np.array(r_pos))
+    assert np.array_equal(node_seq.cpu().numpy(), np.array(r_seq))
+    assert np.array_equal(mask.cpu().numpy().view(np.uint64), _mask_words(r_mask))
+    # a sequence whose offsets run backwards is reported and left alone (its neighbours' ranges are their own)
+    cu_bad = cu.copy()
+    cu_bad[5] = cu[4] - 1 if cu[4] > 0 else cu[6] + 1
+    out = lib.tree_upload_pack(pin(cu_bad), pin(parent), pin(token), _dev(prefix_len))
+    torch.cuda.synchronize()
+    st = out[-1].cpu().numpy()
+    assert st[4] == B.SMART_ETREE or st[5] == B.SMART_ETREE
