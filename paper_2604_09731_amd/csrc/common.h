@@ -50,6 +50,8 @@ int32_t ensure_workspace(smart_ctx* ctx, hipStream_t stream, size_t ws_bytes, si
 // Profiling hooks: bracket the dominant kernel of the current call.
 int32_t profile_begin(smart_ctx* ctx, hipStream_t stream);
 int32_t profile_end(smart_ctx* ctx, hipStream_t stream);
+bool profile_events(smart_ctx* ctx, hipEvent_t* start, hipEvent_t* stop);
+void profile_launched(smart_ctx* ctx);
 
 // Entry points of the two attention implementations (validated params).
 int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p);

@@ -54,6 +54,20 @@ int32_t profile_begin(smart_ctx* ctx, hipStream_t stream) {
   return SMART_OK;
 }
 
+// The event pair of this call if it is one that records, for a launch that attaches events to the dispatch
+// itself (they then hold the kernel's own start and end, with no marker commands on the stream); the caller
+// reports the launch with profile_launched.
+bool profile_events(smart_ctx* ctx, hipEvent_t* start, hipEvent_t* stop) {
+  ctx->prof_open = false;
+  if (ctx->prof_cap <= 0) return false;
+  if (ctx->prof_calls++ % ctx->prof_stride != 0) return false;
+  *start = ctx->prof_start[ctx->prof_recorded % ctx->prof_cap];
+  *stop = ctx->prof_stop[ctx->prof_recorded % ctx->prof_cap];
+  return true;
+}
+
+void profile_launched(smart_ctx* ctx) { ctx->prof_recorded += 1; }
+
 int32_t profile_end(smart_ctx* ctx, hipStream_t stream) {
   if (!ctx->prof_open) return SMART_OK;
   ctx->prof_open = false;

@@ -32,6 +32,7 @@
 //
 // The paper (Sec. 1) only says that the tree is verified in one forward pass
 // of the target model; this file is the attention sub-step of that pass.
+#include <hip/hip_ext.h>
 #include <math.h>
 
 #include "common.h"
@@ -1958,17 +1959,24 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.scale_log2e = p.softmax_scale * kLog2e * (fp8 ? p.k_scale : 1.f);
   ma.m_scale = fp8 ? p.k_scale : 1.f;
   ma.o_scale = fp8 ? p.v_scale : 1.f;
-  rc = profile_begin(ctx, stream);
-  if (rc != SMART_OK) return rc;
   // (every class with work needs a workgroup, however few were asked for)
   const dim3 grid(workgroups > kClasses ? workgroups : kClasses);
-  if (fp8)
-    hipLaunchKernelGGL(tva_prefix_kernel<true>, grid, dim3(kWgWaves * kWave), 0, stream, ma);
-  else
-    hipLaunchKernelGGL(tva_prefix_kernel<false>, grid, dim3(kWgWaves * kWave), 0, stream, ma);
-  SMART_HIP_CHECK(hipGetLastError());
-  rc = profile_end(ctx, stream);
-  if (rc != SMART_OK) return rc;
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  if (profile_events(ctx, &ev_start, &ev_stop)) {
+    // a recorded call: the events ride on the dispatch and hold the kernel's own start and end
+    if (fp8)
+      hipExtLaunchKernelGGL(tva_prefix_kernel<true>, grid, dim3(kWgWaves * kWave), 0, stream, ev_start, ev_stop, 0, ma);
+    else
+      hipExtLaunchKernelGGL(tva_prefix_kernel<false>, grid, dim3(kWgWaves * kWave), 0, stream, ev_start, ev_stop, 0, ma);
+    SMART_HIP_CHECK(hipGetLastError());
+    profile_launched(ctx);
+  } else {
+    if (fp8)
+      hipLaunchKernelGGL(tva_prefix_kernel<true>, grid, dim3(kWgWaves * kWave), 0, stream, ma);
+    else
+      hipLaunchKernelGGL(tva_prefix_kernel<false>, grid, dim3(kWgWaves * kWave), 0, stream, ma);
+    SMART_HIP_CHECK(hipGetLastError());
+  }
 
   CombineArgs ca;
   ca.q = (const uint16_t*)p.d_q;
