@@ -269,8 +269,7 @@ def main():
         guarded_step(i)
     torch.cuda.synchronize()
 
-    # HIP events around the dominant kernel on every PROFILE_STRIDE-th step of the timed region
-    # (a pair of event records costs about 6 us of stream time)
+    # HIP events on the dominant kernel's dispatch on every PROFILE_STRIDE-th step of the timed region
     stride = min(PROFILE_STRIDE, max(1, args.steps))
     lib.set_option(B.SMART_OPT_TVA_PROFILE_STRIDE, stride)
     lib.set_option(B.SMART_OPT_TVA_PROFILE, max(1, args.steps))

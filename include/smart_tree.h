@@ -98,10 +98,12 @@ enum {
   SMART_OPT_TVA_WORKERS = 1,      /* number of split-KV workers (waves); 0 = automatic   */
   SMART_OPT_TVA_FORCE_GENERAL = 2, /* 1 = always run the general (non matrix-core) kernel */
   SMART_OPT_TVA_PROFILE_STRIDE = 4, /* record every value-th tree_verify_attention call only
-                                      (default 1); the event records cost a few us a call  */
+                                      (default 1)                                          */
   SMART_OPT_TVA_PROFILE = 3        /* n > 0: keep n pairs of HIP events and record one pair
-                                      around the dominant attention kernel of every
-                                      tree_verify_attention call (ring); 0 = off (default) */
+                                      on the dominant attention kernel of every
+                                      tree_verify_attention call (ring; the matrix-core path
+                                      attaches the pair to the kernel's dispatch, so it holds
+                                      the kernel's own start and end); 0 = off (default)   */
 };
 
 typedef struct smart_ctx smart_ctx;
