@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 
 METRIC = "tree-verify \u00b5s/step + HBM GB/s & MFMA util (% peak), bs=32, 4k prefix, 8B shapes"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-PROFILE_STRIDE = 4              # the dominant kernel is event-timed on every 4th timed step
+PROFILE_STRIDE = 8              # the dominant kernel is event-timed on every 8th timed step (a recorded dispatch costs the step about 4 us)
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
