@@ -526,9 +526,16 @@ int32_t kv_cache_write_fp8(smart_ctx* ctx, void* stream, int32_t src_dtype, int3
  * total_nodes may exceed d_cu_nodes[batch] (a capacity, when only the device
  * knows the trees' sizes: see tree_compact_pack): rows from d_cu_nodes[batch]
  * on are then either left untouched or zero-filled, never read.
- * Host errors: SMART_EINVAL for null pointers, Hq % Hkv != 0, G > 16,
- * head_dim not in {64, 128}, block_size not a multiple of 8 or > 64,
- * unknown dtype / layout, strides smaller than a page; SMART_ENOMEM / SMART_EHIP.
+ * d_cu_nodes must be a running sum, 0 <= cu[b] <= cu[b+1] <= total_nodes; a
+ * batch whose offsets are not (checked on the device) is treated as a batch of
+ * empty trees by the matrix-core path (no output row is written); the general
+ * kernel zero-fills the rows of a sequence whose range leaves [0, total_nodes].
+ * Any group size G = Hq / Hkv is accepted (a tree's rows per kv head, n x G,
+ * are served in groups of up to 256).
+ * Host errors: SMART_EINVAL for null pointers, Hq % Hkv != 0,
+ * total_nodes x Hq >= 2^31, head_dim not in {64, 128}, block_size not a
+ * multiple of 8 or > 64, unknown dtype / layout, strides smaller than a page;
+ * SMART_ENOMEM / SMART_EHIP.
  * ------------------------------------------------------------------------- */
 typedef struct {
   int32_t dtype;     /* SMART_F32 | SMART_BF16: q, k, v, out share it */

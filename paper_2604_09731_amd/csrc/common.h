@@ -53,9 +53,22 @@ int32_t profile_end(smart_ctx* ctx, hipStream_t stream);
 bool profile_events(smart_ctx* ctx, hipEvent_t* start, hipEvent_t* stop);
 void profile_launched(smart_ctx* ctx);
 
-// Entry points of the two attention implementations (validated params).
+// Device memory for the matrix-core path's partial results and launch plan that somebody else owns.
+struct TvaWorkspace {
+  void* ws;
+  size_t ws_bytes;
+  void* plan;
+  size_t plan_bytes;
+};
+
+// Argument checks of tree_verify_attention (host only; nothing is enqueued).
+int32_t tva_check_params(const tva_params& p);
+// Entry points of the two attention implementations (validated params).  `fixed`: the buffers to use
+// instead of the context's own growable workspace (then nothing is allocated; SMART_ECAP if they are too small).
 int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
-int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p);
+int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p, const TvaWorkspace* fixed);
+// Dispatch between the two (validated params, the context's device current).
+int32_t tva_dispatch(smart_ctx* ctx, hipStream_t stream, const tva_params& p, const TvaWorkspace* fixed);
 bool tva_mfma_supported(const tva_params& p);
 // Workspace the matrix-core path needs for a problem of this size.
 void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,

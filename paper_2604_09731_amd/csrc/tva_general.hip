@@ -83,7 +83,8 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
   int len = prefix_len[b];
   const int cap = max_blocks * lay.block_size;
   len = len < 0 ? 0 : (len > cap ? cap : len);
-  if (node - base >= n_b) {  // a node no sequence owns (inconsistent offsets): defined output
+  if (base < 0 || base + n_b > total_nodes) n_b = 0;  // a range that leaves the arrays: nothing of it is read
+  if (node - base >= n_b || node < base) {  // a node no sequence owns (inconsistent offsets): defined output
     T* o = out + ((size_t)node * Hq + h) * D;
     for (int d = lane; d < D; d += kWave) from_float(0.f, &o[d]);
     if (lse && lane == 0) lse[(size_t)node * Hq + h] = -INFINITY;

@@ -92,6 +92,11 @@ struct SeqInfo {
   int32_t rg;     // row groups (1 for class 1)
 };
 
+// Segments (partial-result slot groups) per class that the host left room for.
+struct SegCaps {
+  int64_t segs[kClasses];
+};
+
 struct PlanView {
   int64_t* header;               // [2c] units U_c, [2c+1] workers W_c, [6+c] first workgroup of class c
   int64_t* cum_units[kClasses];  // [B+1] per class: units before sequence b
@@ -164,8 +169,10 @@ __device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
   return incl - v;
 }
 
-// What the plan records of one sequence (inputs clamped so that nothing downstream can leave
-// its arrays whatever the offsets say).
+// What the plan records of one sequence: lengths and sizes clamped to what the arrays hold.  The
+// offsets themselves are checked by offsets_malformed for the whole batch: only a running sum
+// guarantees that the sizes add up to at most total_nodes, which is what the host sized the
+// partial-result slots and the combine grid for.
 // kAllMedium (fp8 cache): every sequence is class 1, in row groups of 64 rows.
 template <bool kAllMedium = false>
 __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_nodes, int G, int max_blocks) {
@@ -184,6 +191,13 @@ __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_n
   else
     si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
   return si;
+}
+
+// cu_nodes must be a running sum: 0 <= cu[b] <= cu[b + 1] <= total_nodes for every b.  Otherwise the
+// sizes of overlapping ranges could add up to more than total_nodes, the bound every buffer of the
+// call was sized by; such a batch is planned as if every tree were empty (no output row is written).
+__device__ inline bool offsets_malformed(int base, int next, int total_nodes) {
+  return base < 0 || next < base || next > total_nodes;
 }
 
 // The prefix kernel is ONE launch of max(workgroups, kClasses) workgroups; the classes share
@@ -240,14 +254,18 @@ __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroup
 template <bool kOnlySmall>
 __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     void* plan_base, int batch, int total_nodes, int G, int Hkv, int max_blocks, int workgroups,
-    const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ cu_nodes) {
+    SegCaps caps, const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ cu_nodes) {
   PlanView pv = plan_view(plan_base, batch);
   const int t = threadIdx.x;
   const int per = (batch + kWave - 1) / kWave;
   const int b0 = min(batch, t * per), b1 = min(batch, b0 + per);
+  bool bad = false;
+  for (int b = b0; b < b1; ++b) bad = bad || offsets_malformed(cu_nodes[b], cu_nodes[b + 1], total_nodes);
+  const bool malformed = __any(bad);
   int64_t units[kClasses] = {0, 0, 0}, segs[kClasses] = {0, 0, 0}, chunks = 0;
   for (int b = b0; b < b1; ++b) {
-    const SeqInfo si = sequence_info<kOnlySmall>(prefix_len[b], cu_nodes[b], cu_nodes[b + 1], total_nodes, G, max_blocks);
+    SeqInfo si = sequence_info<kOnlySmall>(prefix_len[b], cu_nodes[b], cu_nodes[b + 1], total_nodes, G, max_blocks);
+    if (malformed) si.n = si.rg = 0;
     pv.info[b] = si;
     const int rows = si.n * G;
     const int c = kOnlySmall ? 1 : seq_class(rows);
@@ -261,6 +279,12 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     s[c] = wave_excl_scan(segs[c], t, &tot_s[c]);
   }
   int64_t ch = wave_excl_scan(chunks, t, &tot_c);
+  // more segments than the host left room for (it sized by a hint that does not hold): nothing runs
+  const bool over = tot_s[0] > caps.segs[0] || tot_s[1] > caps.segs[1] || tot_s[2] > caps.segs[2];
+  if (over) {
+    for (int c = 0; c < kClasses; ++c) tot_u[c] = tot_s[c] = u[c] = s[c] = 0;
+    tot_c = ch = 0;
+  }
   if (t == 0) {
     int64_t workers[kClasses], first_wg[kClasses + 1];
     apportion<kOnlySmall>(tot_u, workgroups, workers, first_wg);
@@ -275,7 +299,11 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     pv.cum_chunks[batch] = (int32_t)tot_c;
   }
   for (int b = b0; b < b1; ++b) {
-    const SeqInfo si = pv.info[b];
+    SeqInfo si = pv.info[b];
+    if (over) {
+      si.n = si.rg = 0;
+      pv.info[b] = si;
+    }
     const int rows = si.n * G;
     const int c = kOnlySmall ? 1 : seq_class(rows);
     for (int k = 0; k < kClasses; ++k) {
@@ -307,26 +335,35 @@ struct LanePlan {
 
 template <bool kOnlySmall = false>
 __device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const int32_t* cu_nodes, int batch,
-                                 int total_nodes, int G, int Hkv, int max_blocks, int workgroups, int lane) {
+                                 int total_nodes, int G, int Hkv, int max_blocks, int workgroups,
+                                 const SegCaps& caps, int lane) {
   const int b = min(lane, batch - 1);
   const int32_t len = prefix_len[b], base = cu_nodes[min(lane, batch)], next = cu_nodes[b + 1];
+  const bool malformed = __any(lane < batch && offsets_malformed(base, next, total_nodes));
   SeqInfo si = sequence_info<kOnlySmall>(len, base, next, total_nodes, G, max_blocks);
   if (lane >= batch) si.len = si.n = si.tiles = si.rg = 0;
-  p.si = si;
+  if (malformed) si.n = si.rg = 0;
   p.cu = base;
-  const int rows = si.n * G;
-  const int cls = kOnlySmall ? 1 : seq_class(rows);
-  const int64_t my_units = (int64_t)si.tiles * Hkv * si.rg;
-  const int64_t my_segs = Hkv * si.rg;
-  int64_t tot_s, tot_c;
+  // (a second pass only if the first finds more segments than the host left room for: it sized by a
+  // hint that does not hold; then nothing runs)
+  for (int pass = 0; pass < 2; ++pass) {
+    const int rows = si.n * G;
+    const int cls = kOnlySmall ? 1 : seq_class(rows);
+    const int64_t my_units = (int64_t)si.tiles * Hkv * si.rg;
+    const int64_t my_segs = Hkv * si.rg;
+    int64_t tot_s, tot_c;
 #pragma unroll
-  for (int c = 0; c < kClasses; ++c) {
-    p.cum_units[c] = wave_excl_scan(cls == c ? my_units : 0, lane, &p.units[c]);
-    p.cum_segs[c] = (int32_t)wave_excl_scan(cls == c ? my_segs : 0, lane, &tot_s);
-    p.total_segs[c] = (int32_t)tot_s;
+    for (int c = 0; c < kClasses; ++c) {
+      p.cum_units[c] = wave_excl_scan(cls == c ? my_units : 0, lane, &p.units[c]);
+      p.cum_segs[c] = (int32_t)wave_excl_scan(cls == c ? my_segs : 0, lane, &tot_s);
+      p.total_segs[c] = (int32_t)tot_s;
+    }
+    p.cum_chunks = (int32_t)wave_excl_scan((int64_t)Hkv * ((rows + kCombineRows - 1) / kCombineRows), lane, &tot_c);
+    p.chunks = (int32_t)tot_c;
+    if (p.total_segs[0] <= caps.segs[0] && p.total_segs[1] <= caps.segs[1] && p.total_segs[2] <= caps.segs[2]) break;
+    si.n = si.rg = 0;
   }
-  p.cum_chunks = (int32_t)wave_excl_scan((int64_t)Hkv * ((rows + kCombineRows - 1) / kCombineRows), lane, &tot_c);
-  p.chunks = (int32_t)tot_c;
+  p.si = si;
   apportion<kOnlySmall>(p.units, workgroups, p.workers, p.first_wg);
 }
 
@@ -344,6 +381,7 @@ struct MainArgs {
   float* ws[3];  // partial slots per class
   int64_t block_stride, head_stride;
   int32_t batch, total_nodes, Hq, Hkv, G, max_blocks, num_blocks, workgroups;
+  SegCaps caps;  // segments per class the partial-result slots have room for
   float scale_log2e;
   // fp8 cache only: k_cache / v_cache then point at bytes (E4M3), scale_log2e already includes k_scale,
   // a partial's row maxima are multiplied by m_scale (= k_scale) and its O by o_scale (= v_scale)
@@ -1595,7 +1633,8 @@ void tva_prefix_kernel(MainArgs a) {
     __shared__ PlanShare share;
     if (wv == 0) {
       LanePlan lp;
-      lane_plan<kFp8>(lp, a.prefix_len, a.cu_nodes, a.batch, a.total_nodes, a.G, a.Hkv, a.max_blocks, a.workgroups, lane);
+      lane_plan<kFp8>(lp, a.prefix_len, a.cu_nodes, a.batch, a.total_nodes, a.G, a.Hkv, a.max_blocks, a.workgroups, a.caps,
+                      lane);
 #pragma unroll
       for (int c = 0; c < kClasses; ++c) {
         share.cum_units[c][lane] = lp.cum_units[c];
@@ -1884,21 +1923,49 @@ static int32_t class_workers(const smart_ctx* ctx, int cls) {
 }
 int32_t tva_mfma_default_workers(const smart_ctx* ctx) { return prefix_workgroups(ctx); }
 
-static size_t class_slots(const smart_ctx* ctx, int cls, int32_t batch, int32_t total_nodes,
-                          int32_t num_q_heads, int32_t num_kv_heads) {
+// Segments per class a call can have at most when only the totals are known (every tree's size may be
+// anything that adds up to total_nodes): one row group per sequence in classes 0 and 1; with an fp8
+// cache every sequence is class 1, in row groups of 64 rows.
+static void segment_bounds(int32_t batch, int32_t total_nodes, int32_t num_q_heads, int32_t num_kv_heads,
+                           int64_t (&segs)[kClasses]) {
   const int64_t G = num_q_heads / num_kv_heads;
-  int64_t segs = (int64_t)num_kv_heads * batch;  // one row group per sequence in classes 0 and 1
-  // (with an fp8 cache every sequence is class 1, in row groups of 64 rows)
-  if (cls == 1) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kMediumRows - 1) / kMediumRows + batch);
-  if (cls == 2) segs = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
+  segs[0] = (int64_t)num_kv_heads * batch;
+  segs[1] = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kMediumRows - 1) / kMediumRows + batch);
+  segs[2] = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
+}
+
+// The same from the trees' sizes (host copy of the offsets): exactly the segments the plan will count.
+// False if the offsets are not a running sum inside [0, total_nodes].
+static bool segment_counts(const int32_t* h_cu_nodes, int32_t batch, int32_t total_nodes, int32_t num_q_heads,
+                           int32_t num_kv_heads, bool fp8, int64_t (&segs)[kClasses]) {
+  const int G = num_q_heads / num_kv_heads;
+  for (int c = 0; c < kClasses; ++c) segs[c] = 0;
+  for (int32_t b = 0; b < batch; ++b) {
+    const int64_t base = h_cu_nodes[b], next = h_cu_nodes[b + 1];
+    if (base < 0 || next < base || next > total_nodes) return false;
+    int64_t n = next - base;
+    n = n > SMART_MAX_NODES ? SMART_MAX_NODES : n;
+    const int rows = (int)n * G;
+    if (rows == 0) continue;
+    if (fp8) segs[1] += (int64_t)num_kv_heads * ((rows + kMediumRows - 1) / kMediumRows);
+    else if (seq_class(rows) < 2) segs[seq_class(rows)] += num_kv_heads;
+    else segs[2] += (int64_t)num_kv_heads * ((rows + kLargeRows - 1) / kLargeRows);
+  }
+  return true;
+}
+
+// Slots of a class: worker w's piece of segment s goes to slot w + s.
+static size_t class_slots(const smart_ctx* ctx, int cls, int64_t segs) {
+  if (segs == 0) return 0;  // no sequence of this class: the plan gives it no worker
   return (size_t)class_workers(ctx, cls) + (size_t)segs + 1;
 }
 
 void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,
                         int32_t num_kv_heads, size_t* ws_bytes, size_t* plan_bytes) {
+  int64_t segs[kClasses];
+  segment_bounds(batch, total_nodes, num_q_heads, num_kv_heads, segs);
   size_t floats = 0;
-  for (int c = 0; c < kClasses; ++c)
-    floats += class_slots(ctx, c, batch, total_nodes, num_q_heads, num_kv_heads) * class_slot(c);
+  for (int c = 0; c < kClasses; ++c) floats += class_slots(ctx, c, segs[c]) * class_slot(c);
   *ws_bytes = floats * sizeof(float);
   *plan_bytes = plan_bytes_for(batch);
 }
@@ -1911,28 +1978,50 @@ bool tva_mfma_supported(const tva_params& p) {
          aligned16(p.d_k_tree) && aligned16(p.d_v_tree) && aligned16(p.d_out) && p.num_blocks > 0;
 }
 
-int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p) {
+int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p, const TvaWorkspace* fixed) {
   if (p.batch == 0 || p.total_nodes == 0) return SMART_OK;
   const int G = p.num_q_heads / p.num_kv_heads;
   const int32_t workgroups = prefix_workgroups(ctx);
-  size_t ws_bytes = 0, plan_bytes = 0;
-  tva_mfma_workspace(ctx, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, &ws_bytes, &plan_bytes);
-  int32_t rc = ensure_workspace(ctx, stream, ws_bytes, plan_bytes);
-  if (rc != SMART_OK) return rc;
-  float* ws[kClasses];
-  ws[0] = (float*)ctx->ws;
-  for (int c = 1; c < kClasses; ++c)
-    ws[c] = ws[c - 1] + class_slots(ctx, c - 1, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads) * class_slot(c - 1);
-
   const bool fp8 = p.kv_cache_dtype == SMART_FP8_E4M3;
+  // Room for partial results: by the totals alone (the context's own workspace, grown when needed), or, in a
+  // caller-provided buffer of fixed size, by the trees' sizes when the host copy of the offsets is there.  The
+  // plan counts the segments again on the device and runs nothing if they do not fit.
+  SegCaps caps;
+  if (!fixed || !p.h_cu_nodes) {
+    segment_bounds(p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, caps.segs);
+  } else if (!segment_counts(p.h_cu_nodes, p.batch, p.total_nodes, p.num_q_heads, p.num_kv_heads, fp8, caps.segs)) {
+    return SMART_EINVAL;
+  }
+  size_t slots[kClasses], floats = 0;
+  for (int c = 0; c < kClasses; ++c) {
+    slots[c] = class_slots(ctx, c, caps.segs[c]);
+    floats += slots[c] * class_slot(c);
+  }
+  const size_t ws_bytes = floats * sizeof(float), plan_bytes = plan_bytes_for(p.batch);
+  void* ws_base;
+  void* plan_base;
+  if (fixed) {
+    if (ws_bytes > fixed->ws_bytes || plan_bytes > fixed->plan_bytes) return SMART_ECAP;
+    ws_base = fixed->ws;
+    plan_base = fixed->plan;
+  } else {
+    int32_t rc = ensure_workspace(ctx, stream, ws_bytes, plan_bytes);
+    if (rc != SMART_OK) return rc;
+    ws_base = ctx->ws;
+    plan_base = ctx->plan;
+  }
+  float* ws[kClasses];
+  ws[0] = (float*)ws_base;
+  for (int c = 1; c < kClasses; ++c) ws[c] = ws[c - 1] + slots[c - 1] * class_slot(c - 1);
+
   if (p.batch > kWave) {  // smaller batches: the prefix kernel derives the plan itself
     if (fp8)
-      hipLaunchKernelGGL(tva_plan_kernel<true>, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
-                         p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
+      hipLaunchKernelGGL(tva_plan_kernel<true>, dim3(1), dim3(kWave), 0, stream, plan_base, p.batch,
+                         p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, caps, p.d_prefix_len,
                          p.d_cu_nodes);
     else
-      hipLaunchKernelGGL(tva_plan_kernel<false>, dim3(1), dim3(kWave), 0, stream, (void*)ctx->plan, p.batch,
-                         p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, p.d_prefix_len,
+      hipLaunchKernelGGL(tva_plan_kernel<false>, dim3(1), dim3(kWave), 0, stream, plan_base, p.batch,
+                         p.total_nodes, G, p.num_kv_heads, p.max_blocks_per_seq, workgroups, caps, p.d_prefix_len,
                          p.d_cu_nodes);
     SMART_HIP_CHECK(hipGetLastError());
   }
@@ -1946,7 +2035,8 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ma.prefix_len = p.d_prefix_len;
   ma.total_nodes = p.total_nodes;
   ma.workgroups = workgroups;
-  ma.plan = ctx->plan;
+  ma.plan = plan_base;
+  ma.caps = caps;
   for (int c = 0; c < kClasses; ++c) ma.ws[c] = ws[c];
   ma.block_stride = p.cache_block_stride;
   ma.head_stride = p.cache_head_stride;
@@ -1984,7 +2074,7 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p)
   ca.v_tree = (const uint16_t*)p.d_v_tree;
   ca.cu_nodes = p.d_cu_nodes;
   ca.anc_mask = p.d_anc_mask;
-  ca.plan = ctx->plan;
+  ca.plan = plan_base;
   for (int c = 0; c < kClasses; ++c) ca.ws[c] = ws[c];
   ca.out = (uint16_t*)p.d_out;
   ca.lse = p.d_lse;

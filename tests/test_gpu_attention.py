@@ -111,7 +111,7 @@ def test_bf16_ragged_small(lib, oracle_attention, force_general):
         lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 0)
 
 
-@pytest.mark.parametrize("G,Hkv", [(4, 8), (7, 4), (8, 2), (1, 4)])
+@pytest.mark.parametrize("G,Hkv", [(4, 8), (7, 4), (8, 2), (1, 4), (32, 1)])
 def test_bf16_group_sizes_and_big_trees(lib, oracle_attention, G, Hkv):
     rng = np.random.default_rng(G)
     sizes = [128, 96, 5, 33]
@@ -161,24 +161,60 @@ def test_reduced_configs_full_compare(lib, oracle_attention, name):
     check_full(lib, oracle_attention, make_case(w, B.SMART_KV_INTERLEAVED))
 
 
-@pytest.mark.parametrize("name", ["cfg3a", "cfg3b", "cfg4", "cfg5a", "cfg5b"])
+def _library_trees_checked_against_oracle(w):
+    """The trees the library's smart_select_tree builds for this workload, after checking that
+    the oracle's selection builds exactly the same ones (node order, parents, tokens)."""
+    forest = W.make_forest(w)
+    cu, parent, token, cand = H.trees_from_library(w, forest)
+    cu_o, parent_o, token_o, cand_o = H.trees_from_oracle(w, forest)
+    assert np.array_equal(cu, cu_o) and np.array_equal(parent, parent_o)
+    assert np.array_equal(token, token_o) and np.array_equal(cand, cand_o)
+    return cu, parent
+
+
+def test_cfg3a_full_size_every_row(lib, oracle_attention):
+    """The benchmark's workload at full size, in the launch configuration the benchmark times:
+    every output element and every lse against the oracle."""
+    w = W.WORKLOADS["cfg3a"]
+    case = make_case(w, B.SMART_KV_INTERLEAVED, trees=_library_trees_checked_against_oracle(w))
+    check_full(lib, oracle_attention, case)
+
+
+@pytest.mark.parametrize("name", ["cfg3b", "cfg4", "cfg5a", "cfg5b"])
 def test_full_size_configs_sampled(lib, oracle_attention, name):
-    """Full size, in the launch configuration the benchmark times; the oracle
-    computes a seeded sample of (node, head) rows one by one, plus the row-sum
-    property on every row (lse finite, outputs finite)."""
+    """Full size, in the launch configuration the benchmark times; the oracle computes a seeded
+    sample of (node, head) rows one by one: at least one row of every (sequence, kv head) segment
+    (so every piece of every worker's share is merged into some compared row), the first and the
+    last node of the smallest and the largest tree of every row class, and 64 rows drawn freely;
+    plus finiteness of every output and lse."""
     w = W.WORKLOADS[name]
-    case = make_case(w, B.SMART_KV_INTERLEAVED)
+    cu, parent = _library_trees_checked_against_oracle(w)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, trees=(cu, parent))
     out, lse = case.run(lib)
     o = H.out_to_f64(out, w.dtype)
     assert np.isfinite(o).all() and np.isfinite(lse.cpu().numpy()).all()
     rng = np.random.default_rng(9)
-    N = int(case.cu[-1])
-    n_sel = 96
-    nodes = rng.integers(0, N, n_sel).astype(np.int32)
-    # make sure first / last node of some sequences and the largest tree are sampled
-    big = int(np.argmax(np.diff(case.cu)))
-    nodes[:4] = [0, N - 1, case.cu[big], case.cu[big + 1] - 1]
-    heads = rng.integers(0, w.num_q_heads, n_sel).astype(np.int32)
+    N = int(cu[-1])
+    G = w.num_q_heads // w.num_kv_heads
+    sizes = np.diff(cu)
+    nodes, heads = [], []
+    for b in range(w.batch):                                   # one row per (sequence, kv head)
+        for g in range(w.num_kv_heads):
+            nodes.append(int(cu[b]) + int(rng.integers(0, sizes[b])))
+            heads.append(g * G + int(rng.integers(0, G)))
+    rows = sizes * G
+    for in_class in (rows <= 32, (rows > 32) & (rows <= 64), rows > 64):
+        members = np.flatnonzero(in_class)
+        if len(members) == 0:
+            continue
+        for b in (members[np.argmin(sizes[members])], members[np.argmax(sizes[members])]):
+            for node in (int(cu[b]), int(cu[b + 1]) - 1):
+                for h in (0, w.num_q_heads - 1):
+                    nodes.append(node)
+                    heads.append(h)
+    nodes += rng.integers(0, N, 64).tolist()
+    heads += rng.integers(0, w.num_q_heads, 64).tolist()
+    nodes, heads = np.array(nodes, np.int32), np.array(heads, np.int32)
     ref, ref_lse = case.oracle(oracle_attention, sel=(nodes, heads))
     got = o[nodes, heads]
     scale = np.abs(ref).max()
@@ -371,6 +407,36 @@ def test_medium_trees_every_tail_of_the_two_tile_iteration(lib, oracle_attention
             check_full(lib, oracle_attention, case)
         finally:
             lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
+
+
+def test_offsets_that_are_no_running_sum(lib):
+    """d_cu_nodes must be a running sum inside [0, total_nodes].  Overlapping or decreasing offsets
+    would make the trees' sizes add up to more than total_nodes, the bound every buffer of the call
+    is sized by: the matrix-core path then writes no output row at all, the general kernel zero-fills
+    what no well-formed range owns, and neither reads or writes outside the arrays."""
+    import torch
+    rng = np.random.default_rng(8)
+    sizes = [128, 0, 0, 0]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    w = W.Workload("offsets", "bf16", 4, 8, 2, 128, 0, 0, seed=12)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([300, 200, 100, 50], np.int32),
+                     trees=(cu, W.random_tree(128, rng, "random").astype(np.int32)))
+    _, _, _, mask, _ = lib.tree_pack(case.cu_nodes, case.parent_d, case.prefix_len)
+    for bad in ([0, 128, 0, 128, 128], [0, 128, 128, 64, 128], [-1, 128, 128, 128, 128], [0, 64, 128, 200, 128]):
+        d_bad = torch.tensor(bad, dtype=torch.int32, device="cuda")
+        for force_general in (0, 1):
+            lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, force_general)
+            try:
+                out = torch.full_like(case.q, 7.0)
+                lib.tree_verify_attention(case.q, case.k_tree, case.v_tree, case.k_cache, case.v_cache,
+                                          case.block_table, case.prefix_len, d_bad, mask, case.inp.scale,
+                                          B.SMART_KV_INTERLEAVED, out=out)
+                torch.cuda.synchronize()
+            finally:
+                lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 0)
+            assert torch.isfinite(out.float()).all()
+            if not force_general:
+                assert (out.float() == 7.0).all()
 
 
 # ----- seeded random shapes: batch sizes around the 64-sequence plan window, group sizes 1..16, ------
