@@ -568,6 +568,40 @@ typedef struct {
 int32_t tree_verify_attention(smart_ctx* ctx, void* stream, const tva_params* params);
 
 /* ---------------------------------------------------------------------------
+ * tree_verify_attention_static (device)
+ *
+ * For callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same results as tree_verify_attention, but the
+ * split-KV partial results and the launch plan live in a static device array
+ * of SMART_STATIC_SCRATCH_BYTES that is part of the library's code object (one
+ * copy per GPU the library runs on, held until the process ends; its address
+ * on the context's device is resolved once, by smart_create).  The call
+ * allocates and frees nothing and never synchronises.
+ * Limits: the partial results of the call must fit the array -- SMART_ECAP if
+ * they do not (nothing is enqueued then).  Their size is counted from the
+ * trees' sizes when params->h_cu_nodes (host copy of d_cu_nodes) is given,
+ * which is what makes the usual problem sizes fit (all workloads named in this
+ * repository do); without it, from batch and total_nodes alone, assuming the
+ * least favourable tree sizes.  If h_cu_nodes is given it must be a running sum
+ * inside [0, total_nodes] (SMART_EINVAL otherwise); if it disagrees with
+ * d_cu_nodes so that the device counts more partial results than the host left
+ * room for, the call writes no output at all.  At most about a thousand
+ * sequences per call (the plan's corner of the array; SMART_ECAP beyond).
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on
+ * one GPU (different streams, different contexts, different threads) race;
+ * calls on one stream do not.  The array keeps the previous call's contents;
+ * nothing in it needs to start at zero, every word that is read was written
+ * by the same call before.
+ * The general (non matrix-core) kernel needs no scratch memory and is used as
+ * in tree_verify_attention.
+ * Errors: as tree_verify_attention, plus SMART_ECAP as above, and SMART_EHIP
+ * if the array's address could not be resolved when the context was created.
+ * ------------------------------------------------------------------------- */
+#define SMART_STATIC_SCRATCH_BYTES (128u << 20)
+int32_t tree_verify_attention_static(smart_ctx* ctx, void* stream, const tva_params* params);
+
+/* ---------------------------------------------------------------------------
  * tree_accept (device)
  *
  * Greedy verification walk per sequence.  d_target_next[i] is the target

@@ -31,7 +31,7 @@ EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_dest
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_product_forest", "smart_select_begin", "smart_select_layer",
            "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
-           "kv_cache_write", "kv_cache_write_fp8", "tree_verify_attention", "tree_accept", "tree_accept_sample", "tree_commit", "tree_commit_fp8"]
+           "kv_cache_write", "kv_cache_write_fp8", "tree_verify_attention", "tree_verify_attention_static", "tree_accept", "tree_accept_sample", "tree_commit", "tree_commit_fp8"]
 
 
 class SmartError(RuntimeError):
@@ -137,6 +137,8 @@ def _lib():
                                            i64, i64, i64, ctypes.c_float, ctypes.c_float]
         lib.tree_verify_attention.restype = i32
         lib.tree_verify_attention.argtypes = [vp, vp, ctypes.POINTER(TvaParams)]
+        lib.tree_verify_attention_static.restype = i32
+        lib.tree_verify_attention_static.argtypes = [vp, vp, ctypes.POINTER(TvaParams)]
         lib.tree_commit.restype = i32
         lib.tree_commit.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp,
                                     vp, vp, i64, i64, i64, vp, vp]
@@ -538,9 +540,12 @@ class SmartTree:
     # -- tree_verify_attention ---------------------------------------------
     def tree_verify_attention(self, q, k_tree, v_tree, k_cache, v_cache, block_table, prefix_len,
                               cu_nodes, anc_mask, softmax_scale, kv_layout, block_size=16,
-                              out=None, lse=None, want_lse=False, h_cu_nodes=None, k_scale=None, v_scale=None):
+                              out=None, lse=None, want_lse=False, h_cu_nodes=None, k_scale=None, v_scale=None,
+                              static=False):
         """k_cache / v_cache: [num_blocks, Hkv, ...] with one contiguous page of
-        block_size * D elements per (block, head) (any of the two layouts)."""
+        block_size * D elements per (block, head) (any of the two layouts).
+        ``static``: call tree_verify_attention_static (no device allocation inside the library;
+        pass ``out`` / ``lse`` so that nothing is allocated here either)."""
         torch = _torch()
         N, Hq, D = q.shape
         Hkv = k_tree.shape[1]
@@ -578,8 +583,9 @@ class SmartTree:
             h_cu_nodes = np.ascontiguousarray(h_cu_nodes, np.int32)
             assert h_cu_nodes.shape[0] == B + 1
             p.h_cu_nodes = h_cu_nodes.ctypes.data
-        _check(_lib().tree_verify_attention(self._h, _stream_ptr(), ctypes.byref(p)),
-               "tree_verify_attention")
+        entry = _lib().tree_verify_attention_static if static else _lib().tree_verify_attention
+        _check(entry(self._h, _stream_ptr(), ctypes.byref(p)),
+               "tree_verify_attention_static" if static else "tree_verify_attention")
         return (out, lse) if (want_lse or lse is not None) else out
 
     # -- tree_accept -------------------------------------------------------

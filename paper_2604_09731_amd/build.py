@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libsmart_tree.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 HIP_SOURCES = ["smart_ctx.hip", "tree_pack_accept.hip", "kv_cache_write.hip", "tva_general.hip",
-               "tva_mfma.hip", "tva_api.hip", "smart_select_device.hip", "tree_rope.hip",
+               "tva_mfma.hip", "tva_api.hip", "tva_static.hip", "smart_select_device.hip", "tree_rope.hip",
                "tree_accept_sample.hip"]
 HOST_SOURCES = ["smart_select.cpp", "smart_cost_model.cpp"]
 

@@ -19,6 +19,10 @@ struct smart_ctx {
   // options
   int64_t opt_workers = 0;
   int64_t opt_force_general = 0;
+  // this device's copy of the static scratch array (tree_verify_attention_static), resolved by smart_create
+  void* scratch = nullptr;
+  size_t scratch_bytes = 0;
+  int32_t scratch_rc = 0;     // what resolving it returned
   // profiling ring (SMART_OPT_TVA_PROFILE)
   hipEvent_t* prof_start = nullptr;
   hipEvent_t* prof_stop = nullptr;
@@ -69,6 +73,8 @@ int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params&
 int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p, const TvaWorkspace* fixed);
 // Dispatch between the two (validated params, the context's device current).
 int32_t tva_dispatch(smart_ctx* ctx, hipStream_t stream, const tva_params& p, const TvaWorkspace* fixed);
+// This device's copy of the library's static scratch array (the device must be current); resolved once per device.
+int32_t static_scratch(int device, void** ptr, size_t* bytes);
 bool tva_mfma_supported(const tva_params& p);
 // Workspace the matrix-core path needs for a problem of this size.
 void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes, int32_t num_q_heads,

@@ -103,6 +103,16 @@ extern "C" int32_t smart_create(smart_ctx** out_ctx, int32_t device_id) {
   if (!c) return SMART_ENOMEM;
   c->device = device_id;
   c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  // this device's copy of the static scratch array (every GPU has its own, at its own address); a failure
+  // here only disables tree_verify_attention_static, which then returns it
+  int prev = 0;
+  if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(device_id) == hipSuccess) {
+    c->scratch_rc = smart::static_scratch(device_id, &c->scratch, &c->scratch_bytes);
+    (void)hipSetDevice(prev);
+  } else {
+    (void)hipGetLastError();
+    c->scratch_rc = SMART_EHIP;
+  }
   *out_ctx = c;
   return SMART_OK;
 }
