@@ -11,9 +11,15 @@ block table / target tokens on the GPU) is resident before the clock starts.
 
 Prints ONE JSON line.  `value` = microseconds per step.  `roofline` is for the
 dominant kernel (the prefix-streaming attention kernel), timed with HIP events
-the library records around it on the launch stream during the timed steps.
-`cpu_baseline` is the CPU oracle's attention on a bounded sample of the same
-workload, extrapolated to a full step.
+the library attaches to its dispatch during the timed steps; `roofline_call` is
+the same bound for the whole tree_verify_attention call (that kernel plus the
+combine kernel, timed with events around the call).  `cpu_baseline` is the CPU
+oracle's attention on a bounded sample of the same workload, extrapolated to a
+full step; `parity_err` compares the GPU output of the last timed step with the
+rows the oracle computed for it.  With the default workload (cfg3a, trees as the
+rule selects them at batch 32) the run then also times cfg3b (the same shapes
+with trees of 4 .. 64 nodes, the range the workload is worded with) and reports
+it under `also`.
 """
 from __future__ import annotations
 
@@ -32,12 +38,24 @@ if ROOT not in sys.path:
 
 METRIC = "tree-verify \u00b5s/step + HBM GB/s & MFMA util (% peak), bs=32, 4k prefix, 8B shapes"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-PROFILE_STRIDE = 8              # the dominant kernel is event-timed on every 8th timed step (a recorded dispatch costs the step about 4 us)
+KERNEL_SAMPLES = 10             # the dominant kernel is event-timed on about this many of the timed steps (a recorded
+                                # dispatch costs its step about 4 us, so not on every one)
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
-# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs scaled by a plain copy of known size (see profiles/); bytes.
-MEASURED_TRAFFIC = {"cfg3a": 477.5e6}   # profiles/tva_prefix_kernel_cfg3a.md
+
+def measured_traffic(workload: str, kv: str):
+    """HBM bytes per launch of the dominant kernel as the byte counters read them (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size): the line
+    `paper_2604_09731_amd.profile_summary traffic` wrote for this workload into profiles/hbm_traffic.txt, else None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) >= 4 and not line.startswith("#") and f[0] == workload and f[1] == kv:
+                return float(f[3])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -62,6 +80,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for rocprofv3 byte counters)")
+    ap.add_argument("--no-second", action="store_true", help="with the default workload: do not also time cfg3b")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -69,13 +88,25 @@ def main():
         sys.exit(2)
 
     import torch
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    result = measure(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    if args.workload == "cfg3a" and args.kv == "bf16" and args.accept == "greedy" and not args.no_second:
+        second = measure(args, "cfg3b", min(args.steps, 100), min(args.warmup, 20), False)
+        result["also"] = {"cfg3b": {k: second[k] for k in ("value", "unit", "steps", "config", "breakdown_us",
+                                                           "attention_tflops", "attention_mfma_frac", "roofline",
+                                                           "roofline_call")}}
+    print(json.dumps(result), flush=True)
+
+
+def measure(args, workload, steps, warmup, cpu_baseline):
+    """One workload: set-up, timed steps, per-kernel breakdown, roofline figures; returns the result dictionary."""
+    import torch
     from paper_2604_09731_amd import binding as B
     from paper_2604_09731_amd import workloads as W
 
-    assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    w = W.WORKLOADS[args.workload]
+    w = W.WORKLOADS[workload]
     lib = B.SmartTree(0)
     L = B._lib()
 
@@ -265,25 +296,26 @@ def main():
 
     copy_done[0].record()
     copy_done[1].record()
-    for i in range(args.warmup):
+    for i in range(warmup):
         guarded_step(i)
     torch.cuda.synchronize()
 
-    # HIP events on the dominant kernel's dispatch on every PROFILE_STRIDE-th step of the timed region
-    stride = min(PROFILE_STRIDE, max(1, args.steps))
+    # HIP events on the dominant kernel's dispatch on every stride-th step of the timed region
+    stride = max(1, steps // KERNEL_SAMPLES)
     lib.set_option(B.SMART_OPT_TVA_PROFILE_STRIDE, stride)
-    lib.set_option(B.SMART_OPT_TVA_PROFILE, max(1, args.steps))
+    lib.set_option(B.SMART_OPT_TVA_PROFILE, max(1, steps))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         guarded_step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kernel_ms = lib.profile_read()
     lib.set_option(B.SMART_OPT_TVA_PROFILE, 0)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     lib.set_option(B.SMART_OPT_TVA_PROFILE_STRIDE, 1)
-    assert len(kernel_ms) == (args.steps + stride - 1) // stride
+    assert len(kernel_ms) == (steps + stride - 1) // stride
+    out_last = out.clone()                      # what the last timed step left (for parity_err below)
     dom_ms = float(np.mean(kernel_ms))
     assert not status.cpu().numpy().any()
 
@@ -326,7 +358,10 @@ def main():
     e = 2 if w.dtype == "bf16" else 4
     kv_bytes = work["kv_bytes"] // (2 if args.kv == "fp8" and w.dtype == "bf16" else 1)
     dom_bytes = kv_bytes + N * w.num_q_heads * w.head_dim * e   # prefix K/V once + Q
+    # the whole call: prefix K/V once, Q, tree K/V and the output (masks, block table and lengths are a few KB)
+    call_bytes = kv_bytes + N * (2 * w.num_kv_heads + 2 * w.num_q_heads) * w.head_dim * e
     achieved_gbs = dom_bytes / (dom_ms * 1e-3) / 1e9
+    call_gbs = call_bytes / (att_us * 1e-6) / 1e9
     tflops = work["flops"] / (att_us * 1e-6) / 1e12
     result = {
         # the headline metric as the baseline file words it; `value` is its first component (us per
@@ -335,8 +370,8 @@ def main():
         "value": round(ms_per_step * 1e3, 2),
         "unit": "us/step",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": False,
         "scaling": "weak",
@@ -357,23 +392,38 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "tva_prefix_kernel",
                      "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-                     "kernel_us": round(dom_ms * 1e3, 2), "algorithmic_bytes": int(dom_bytes),
-                     "traffic": MEASURED_TRAFFIC.get(w.name) if args.kv == "bf16" else None},
+                     "kernel_us": round(dom_ms * 1e3, 2), "kernel_samples": len(kernel_ms),
+                     "algorithmic_bytes": int(dom_bytes), "traffic": measured_traffic(w.name, args.kv)},
+        "roofline_call": {"bound": "hbm", "call": "tree_verify_attention", "achieved": round(call_gbs, 1),
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(call_gbs / HBM_PEAK_GBS, 4),
+                          "call_us": round(att_us, 2), "algorithmic_bytes": int(call_bytes)},
     }
 
     # ---------------- CPU baseline: the oracle, bounded sample ----------------
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         from oracle import attention as OA
         rng = np.random.default_rng(w.seed)
         total_rows = N * w.num_q_heads
 
+        got = out_last.double().cpu().numpy() if w.dtype == "bf16" else out_last.cpu().numpy().astype(np.float64)
+        checked = {"rows": 0, "err": 0.0, "scale": 0.0}
+
         def run_sample(n_rows):
-            nodes = rng.integers(0, N, n_rows).astype(np.int32)
-            heads = rng.integers(0, w.num_q_heads, n_rows).astype(np.int32)
+            if n_rows >= total_rows:            # the whole output, every (node, head) row once
+                nodes = np.repeat(np.arange(N, dtype=np.int32), w.num_q_heads)
+                heads = np.tile(np.arange(w.num_q_heads, dtype=np.int32), N)
+            else:
+                nodes = rng.integers(0, N, n_rows).astype(np.int32)
+                heads = rng.integers(0, w.num_q_heads, n_rows).astype(np.int32)
             t = time.perf_counter()
-            OA.tree_attention(inp.q, inp.k_tree, inp.v_tree, inp.k_cache, inp.v_cache, inp.block_table,
-                              inp.prefix_len, cu_nodes, parent, inp.scale, sel=(nodes, heads))
-            return time.perf_counter() - t
+            ref, _ = OA.tree_attention(inp.q, inp.k_tree, inp.v_tree, inp.k_cache, inp.v_cache, inp.block_table,
+                                       inp.prefix_len, cu_nodes, parent, inp.scale, sel=(nodes, heads))
+            dt = time.perf_counter() - t
+            # the GPU's rows of the last timed step against the rows the oracle just computed
+            checked["rows"] = len(nodes)
+            checked["err"] = max(checked["err"], float(np.abs(got[nodes, heads] - ref).max()))
+            checked["scale"] = max(checked["scale"], float(np.abs(ref).max()))
+            return dt
 
         threads = OA.num_threads()
         pilot_rows = min(total_rows, 4 * threads)
@@ -390,7 +440,15 @@ def main():
             "value": round(full_us, 1), "unit": "us/step", "cores": threads, "kind": "oracle",
             "sample": f"fp64 oracle attention on {n_rows} of {total_rows} (node, head) rows of this workload, "
                       f"{secs:.1f} s measured, extrapolated by row count (attention only)"}
-    print(json.dumps(result), flush=True)
+        tol = 2e-2 if w.dtype == "bf16" else 1e-5
+        result["parity_err"] = {"value": checked["err"] / (checked["scale"] or 1.0), "tolerance": tol,
+                                "rows": checked["rows"],
+                                "what": "max |gpu - oracle| / max |oracle| over the (node, head) rows the oracle computed "
+                                        "for cpu_baseline (rows = size of its last sample), gpu output of the last timed step"}
+        assert result["parity_err"]["value"] <= tol, result["parity_err"]
+    del caches, kc, vc
+    torch.cuda.empty_cache()
+    return result
 
 
 if __name__ == "__main__":
