@@ -55,6 +55,30 @@ def cost_tables(lam, gamma, delta, rho, c_T, tokens_per_node, n_max):
     return cost, dcost
 
 
+def cost_tables_biased(lam, beta, gamma, delta, rho, eta, c_T, tokens_per_node, undrafted_nodes, n_max):
+    """The same tables with the bias terms of Eqs. "linear_model" and "exp_model" kept (the paper
+    sets both to zero when it fits whole forward passes; a cost that is measured as the extra time
+    over a plain decoding step needs them: eta = c_T, beta = 0) and with the nodes that are not
+    drafted (the root, which every verification step carries anyway) left out of the token count:
+
+        x(n)     = tokens_per_node * max(n - undrafted_nodes, 0)
+        cost[n]  = (lambda x + beta + gamma (exp(delta x**rho) - 1) + eta) / c_T
+        dcost[n] = tokens_per_node * (lambda + gamma delta rho x**(rho-1) exp(delta x**rho)) / c_T
+
+    (dcost at x = 0 with rho < 1: +inf.)"""
+    def x_of(n):
+        return tokens_per_node * max(n - undrafted_nodes, 0)
+    cost = [(spec_cost(x_of(n), lam, gamma, delta, rho) + beta + eta) / c_T for n in range(n_max + 2)]
+    dcost = []
+    for n in range(n_max + 1):
+        x = x_of(n)
+        if x == 0.0 and rho < 1.0:
+            dcost.append(math.inf)
+        else:
+            dcost.append(tokens_per_node * spec_marginal(x, lam, gamma, delta, rho) / c_T)
+    return cost, dcost
+
+
 def fit_linear(x, t):
     """Least squares for t ~ lambda * x (a line through the origin)."""
     x = np.asarray(x, np.float64)

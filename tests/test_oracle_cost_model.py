@@ -78,3 +78,30 @@ def test_exp_fit_beats_every_grid_point_on_noisy_data():
         for s in np.exp(np.linspace(math.log(1e-5), math.log(30.0), 60)):
             grid_sse, _ = CM._reduced(x, t, s / xm ** rho, rho)
             assert sse <= grid_sse * (1 + 1e-9)
+
+
+def test_biased_tables_closed_forms_and_reductions():
+    """The tables with the bias terms of Eqs. "linear_model" / "exp_model" kept and the root left out of the
+    drafted tokens: pinned to hand-evaluated closed forms (rho = 1), to the unbiased tables they reduce to,
+    and to the shift by one node."""
+    lam, gamma, delta, c_T, b = 0.25, 3.0, 0.01, 2.0, 4.0
+    cost, dcost = CM.cost_tables_biased(lam, 0.5, gamma, delta, 1.0, 2.0, c_T, b, 1, 6)
+    assert len(cost) == 8 and len(dcost) == 7
+    # n = 0 and n = 1 (only the root): no drafted token, the biases alone
+    assert cost[0] == pytest.approx((0.5 + 2.0) / c_T, rel=1e-15) and cost[1] == cost[0]
+    # n = 4: x = 4 (4 - 1) = 12 drafted tokens
+    assert cost[4] == pytest.approx((0.25 * 12 + 0.5 + 3.0 * (math.exp(0.12) - 1.0) + 2.0) / c_T, rel=1e-14)
+    assert dcost[4] == pytest.approx(b * (0.25 + 3.0 * 0.01 * math.exp(0.12)) / c_T, rel=1e-14)
+    # zero biases, every node drafted: the unbiased tables
+    c0, d0 = CM.cost_tables(lam, gamma, delta, 1.3, c_T, b, 9)
+    c1, d1 = CM.cost_tables_biased(lam, 0.0, gamma, delta, 1.3, 0.0, c_T, b, 0, 9)
+    assert c0 == c1 and d0 == d1
+    # leaving the root out shifts the unbiased tables by one node and adds the constant
+    c2, d2 = CM.cost_tables_biased(lam, 0.0, gamma, delta, 1.3, c_T, c_T, b, 1, 8)
+    assert all(c2[n] == pytest.approx(1.0 + c0[n - 1], rel=1e-14) for n in range(1, 10))
+    assert all(d2[n] == pytest.approx(d0[n - 1], rel=1e-14) for n in range(1, 9))
+    # a plain step costs exactly one unit when eta = c_T: R(root only) = 1
+    assert c2[1] == 1.0
+    # rho < 1: infinite marginal cost where nothing is drafted yet
+    _, d3 = CM.cost_tables_biased(lam, 0.0, gamma, delta, 0.5, c_T, c_T, b, 1, 3)
+    assert math.isinf(d3[0]) and math.isinf(d3[1]) and all(math.isfinite(v) for v in d3[2:])
