@@ -81,6 +81,14 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     ap.add_argument("--no-second", action="store_true", help="with the default workload: do not also time cfg3b")
+    ap.add_argument("--cost-loop", action="store_true",
+                    help="instead of the benchmark: the paper's cost-model loop on this device "
+                         "(paper_2604_09731_amd.cost_loop; its options follow after --, e.g. -- --batches 1 8 32)")
+    ap.add_argument("--with-dense", action="store_true",
+                    help="--cost-loop: add the time of a layer's dense products at the same token count (library GEMMs "
+                         "through torch.matmul: query/key/value/output projections and a gated MLP of an 8B-class layer; "
+                         "a stand-in for what surrounds attention in a verification pass, not part of the library)")
+    ap.add_argument("rest", nargs="*", help="options handed to the cost loop")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -90,6 +98,10 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.cost_loop:
+        from paper_2604_09731_amd import cost_loop
+        cost_loop.main(args.rest, extra_us=dense_layer_us() if args.with_dense else None)
+        return
     result = measure(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
     if args.workload == "cfg3a" and args.kv == "bf16" and args.accept == "greedy" and not args.no_second:
         second = measure(args, "cfg3b", min(args.steps, 100), min(args.warmup, 20), False)
@@ -97,6 +109,37 @@ def main():
                                                            "attention_tflops", "attention_mfma_frac", "roofline",
                                                            "roofline_call")}}
     print(json.dumps(result), flush=True)
+
+
+def dense_layer_us(reps=50):
+    """tokens -> microseconds of the dense products of one 8B-class transformer layer for that many rows, as
+    library GEMMs (torch.matmul).  Harness only: the stand-in for what surrounds the attention in a verification
+    pass when the cost-model loop is asked for a whole layer's cost."""
+    import torch
+    hid, qkv, mlp = 4096, 4096 + 2 * 1024, 14336
+    mk = lambda a, b: torch.randn((a, b), device="cuda", dtype=torch.bfloat16) * 0.02
+    w_qkv, w_o, w_up, w_down = mk(hid, qkv), mk(hid, hid), mk(hid, 2 * mlp), mk(mlp, hid)
+
+    def us(tokens):
+        x = torch.randn((tokens, hid), device="cuda", dtype=torch.bfloat16)
+        h = torch.randn((tokens, mlp), device="cuda", dtype=torch.bfloat16)
+
+        def run():
+            x @ w_qkv
+            x @ w_o
+            x @ w_up
+            h @ w_down
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+    return us
 
 
 def measure(args, workload, steps, warmup, cpu_baseline):

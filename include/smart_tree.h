@@ -371,6 +371,18 @@ int32_t tree_compact_pack(smart_ctx* ctx, void* stream, const smart_layer_state*
  * ------------------------------------------------------------------------- */
 int32_t smart_cost_tables(double lambda, double gamma, double delta, double rho, double c_T,
                           double tokens_per_node, int32_t n_max, double* h_cost, double* h_dcost);
+/* The same with the bias terms of Eqs. "linear_model" (beta) and "exp_model" (eta) kept, and with the first
+ * undrafted_nodes nodes of a tree (the root, which every verification step carries anyway) left out of the token
+ * count:  x(n) = tokens_per_node max(n - undrafted_nodes, 0),
+ *   h_cost[n]  = (lambda x + beta + gamma (exp(delta x^rho) - 1) + eta) / c_T,
+ *   h_dcost[n] = tokens_per_node (lambda + gamma delta rho x^(rho-1) exp(delta x^rho)) / c_T   (x = 0, rho < 1: +inf).
+ * A cost measured as the extra time of a verification step over the plain decoding step c_T is eta = c_T,
+ * beta = 0, undrafted_nodes = 1: then h_cost[1] = 1 exactly and h_cost[n] = 1 + model(drafted tokens) / c_T.
+ * smart_cost_tables is this with zero biases and undrafted_nodes = 0.
+ * Errors: as smart_cost_tables; also negative or non-finite biases, negative undrafted_nodes. */
+int32_t smart_cost_tables_biased(double lambda, double beta, double gamma, double delta, double rho, double eta,
+                                 double c_T, double tokens_per_node, int32_t undrafted_nodes, int32_t n_max,
+                                 double* h_cost, double* h_dcost);
 int32_t smart_fit_cost_models(int32_t n_points, const double* h_x, const double* h_t_draft,
                               const double* h_t_verify, double* h_lambda, double* h_gamma,
                               double* h_delta, double* h_rho, double* h_sse);

@@ -29,7 +29,7 @@ SMART_MAX_LAYER_CAND = 2048
 
 EXPORTS = ["smart_strerror", "smart_last_hip_error", "smart_create", "smart_destroy",
            "smart_reserve", "smart_set_option", "smart_tva_profile_read", "smart_select_tree", "smart_select_tree_budgets", "smart_baseline_tree", "smart_product_forest", "smart_select_begin", "smart_select_layer",
-           "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_fit_cost_models", "tree_upload",
+           "smart_select_begin_device", "smart_select_layer_device", "tree_compact_pack", "tree_rope", "smart_cost_tables", "smart_cost_tables_biased", "smart_fit_cost_models", "tree_upload",
            "tree_upload_pack", "tree_pack",
            "kv_cache_write", "kv_cache_write_fp8", "tree_verify_attention", "tree_verify_attention_static", "tree_accept", "tree_accept_sample", "tree_commit", "tree_commit_fp8"]
 
@@ -121,6 +121,8 @@ def _lib():
         lib.tree_rope.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, f64, vp, vp, vp]
         lib.smart_cost_tables.restype = i32
         lib.smart_cost_tables.argtypes = [f64, f64, f64, f64, f64, f64, i32, vp, vp]
+        lib.smart_cost_tables_biased.restype = i32
+        lib.smart_cost_tables_biased.argtypes = [f64, f64, f64, f64, f64, f64, f64, f64, i32, i32, vp, vp]
         lib.smart_fit_cost_models.restype = i32
         lib.smart_fit_cost_models.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.tree_upload.restype = i32
@@ -328,6 +330,20 @@ def smart_cost_tables(lam, gamma, delta, rho, c_T, tokens_per_node, n_max, want_
     rc = _lib().smart_cost_tables(float(lam), float(gamma), float(delta), float(rho), float(c_T),
                                   float(tokens_per_node), int(n_max), p(cost), p(dcost))
     _check(rc, "smart_cost_tables")
+    return cost, dcost
+
+
+def smart_cost_tables_biased(lam, beta, gamma, delta, rho, eta, c_T, tokens_per_node, undrafted_nodes, n_max,
+                             want_dcost=True):
+    """The tables with the models' bias terms kept and the first undrafted_nodes nodes (the root) left out of
+    the drafted tokens; (cost[n_max + 2], dcost[n_max + 1] or None)."""
+    cost = np.zeros(n_max + 2, np.float64)
+    dcost = np.zeros(n_max + 1, np.float64) if want_dcost else None
+    p = lambda a: ctypes.c_void_p(a.ctypes.data) if a is not None else None
+    rc = _lib().smart_cost_tables_biased(float(lam), float(beta), float(gamma), float(delta), float(rho), float(eta),
+                                         float(c_T), float(tokens_per_node), int(undrafted_nodes), int(n_max),
+                                         p(cost), p(dcost))
+    _check(rc, "smart_cost_tables_biased")
     return cost, dcost
 
 

@@ -5,16 +5,26 @@ attention layer this library implements.
 For each batch size: time tree_verify_attention for trees of 1, 4, 8, 16, 32 and 64 nodes per
 sequence (the paper profiles a handful of forward passes per device), take the plain decoding
 step (a tree that is only its root) as c_T, fit the power-exponential model of Eq. "exp_model"
-to the EXTRA time over that step as a function of the drafted tokens batch * (n - 1), build the
-cost tables (cost[n] = 1 + model / c_T) and let smart_select_tree choose trees over the same
-candidate forests (--forest product: those of a drafter with independent positions, the
-Cartesian-product tree of the paper's appendix).  The likelihood-maximising expand-and-rerank
-policy (Sec. 3.1, first paragraph) is run over the same forests for comparison: its modelled
-speedup under the same cost table, and the measured attention time of both policies' trees.
-Prints one JSON row per batch size.
+to the EXTRA time over that step as a function of the drafted tokens batch * (n - 1), and the
+line of Eq. "linear_model" to the draft side's time for the same tokens; the library builds the
+cost tables from the fits (smart_cost_tables_biased: cost[n] = 1 + (draft + verify model) / c_T,
+and the differentiated marginal cost of Eq. "marginal_cost") and smart_select_tree chooses trees
+over the same candidate forests, once with the exact difference cost[n+1] - cost[n] and once
+with the differentiated marginal cost (--forest product: the forests of a drafter with
+independent positions, the Cartesian-product tree of the paper's appendix).  The
+likelihood-maximising expand-and-rerank policy (Sec. 3.1, first paragraph) is run over the same
+forests for comparison: its modelled speedup under the same cost table, and the measured
+attention time of both policies' trees.  Prints one JSON row per batch size.
 
-This measures ONE attention layer, not a whole target model: the point is the loop (measure,
-fit, select) on this hardware, not the absolute speedups.
+The draft side is a stand-in (no draft model is part of this library): a drafter of
+--draft-layers layers shaped like the target's (an EAGLE-style head is one), whose time for the
+drafted tokens is that many times the measured extra time of ONE layer, against a target of
+--target-layers such layers; with the default --draft-layers 0 there is no draft leg.
+
+This measures ONE attention layer (times --target-layers), not a whole target model: the point is
+the loop (measure, fit, select) on this hardware, not the absolute speedups.  A caller may pass
+`extra_us(tokens)`, the time of whatever else a layer does for that many tokens (bench.py
+--cost-loop --with-dense adds a layer's dense products that way).
 
     python -m paper_2604_09731_amd.cost_loop [--batches 1 8 32 128] [--prefix 3584]
 """
@@ -27,7 +37,7 @@ import sys
 import numpy as np
 
 
-def main(argv=None):
+def main(argv=None, extra_us=None):
     import torch
     from . import binding as B
     from . import workloads as W
@@ -43,10 +53,10 @@ def main(argv=None):
                     help="candidate forests: the workloads' autoregressive drafts (children conditioned on the path), "
                          "or the Cartesian product of independent per-position top-k candidates (the tree the paper's "
                          "appendix builds for a block-diffusion drafter), cut at 1024 candidates")
-    ap.add_argument("--with-dense", action="store_true",
-                    help="add the time of the layer's dense products at the same token count (library GEMMs through "
-                         "torch.matmul: query/key/value/output projections and a gated MLP of an 8B-class layer), so "
-                         "that the cost is that of a whole transformer layer and turns compute-bound with the batch")
+    ap.add_argument("--target-layers", type=int, default=1, help="the verification pass is this many of the measured layer")
+    ap.add_argument("--draft-layers", type=int, default=0,
+                    help="stand-in draft model: this many layers of the target's shape run over the drafted tokens "
+                         "(0: no draft leg, lambda = 0)")
     args = ap.parse_args(argv)
     assert torch.cuda.is_available(), "needs the MI355X"
     lib = B.SmartTree(0)
@@ -76,37 +86,9 @@ def main(argv=None):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / args.reps
 
-    dense_weights = None
-
-    def dense_us(tokens):
-        """Microseconds of the dense products of one 8B-class layer for `tokens` rows (not part of the library:
-        the stand-in for what surrounds the attention in a verification pass)."""
-        nonlocal dense_weights
-        if not args.with_dense:
-            return 0.0
-        hid, qkv, mlp = 4096, 4096 + 2 * 1024, 14336
-        if dense_weights is None:
-            mk = lambda a, b: torch.randn((a, b), device="cuda", dtype=torch.bfloat16) * 0.02
-            dense_weights = (mk(hid, qkv), mk(hid, hid), mk(hid, 2 * mlp), mk(mlp, hid))
-        w_qkv, w_o, w_up, w_down = dense_weights
-        x = torch.randn((tokens, hid), device="cuda", dtype=torch.bfloat16)
-        h = torch.randn((tokens, mlp), device="cuda", dtype=torch.bfloat16)
-
-        def run():
-            x @ w_qkv
-            x @ w_o
-            x @ w_up
-            h @ w_down
-        for _ in range(3):
-            run()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.reps):
-            run()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / args.reps
+    def layer_us(w, cu, parent):
+        """One layer for these trees: the library's attention, plus the caller's extra for the same tokens."""
+        return time_attention(w, cu, parent) + (extra_us(int(cu[-1])) if extra_us else 0.0)
 
     def tiled(sel, batch):
         """The trees of a selection result, repeated until there are `batch` of them."""
@@ -124,17 +106,21 @@ def main(argv=None):
         times = []
         for n in args.sizes:
             cu = (np.arange(batch + 1) * n).astype(np.int32)
-            times.append(time_attention(w, cu, np.tile(big[:n], batch).astype(np.int32)) + dense_us(batch * n))
+            times.append(layer_us(w, cu, np.tile(big[:n], batch).astype(np.int32)))
         sizes = np.array(args.sizes, np.float64)
-        times = np.array(times)
-        c_T = times[0] if args.sizes[0] == 1 else float(np.interp(1.0, sizes, times))
-        x = batch * (sizes[1:] - 1.0)
+        layer = np.array(times)
+        layer_1 = layer[0] if args.sizes[0] == 1 else float(np.interp(1.0, sizes, layer))
+        times = args.target_layers * layer                   # a verification pass
+        c_T = args.target_layers * layer_1                    # a plain decoding step of the target
+        x = batch * (sizes[1:] - 1.0)                         # drafted tokens
         extra = np.maximum(times[1:] - c_T, 1e-3)
-        fit = B.smart_fit_cost_models(x, None, extra)
+        draft = args.draft_layers * np.maximum(layer[1:] - layer_1, 1e-3) if args.draft_layers else None
+        fit = B.smart_fit_cost_models(x, draft, extra)
+        lam = fit.get("lambda", 0.0)
         n_max = base.budget
-        table, dtable = B.smart_cost_tables(0.0, fit["gamma"], fit["delta"], fit["rho"], c_T, float(batch), n_max)
-        # cost[n]: one plain step plus the fitted extra of the n - 1 drafted nodes
-        cost = np.concatenate([[0.0], 1.0 + table[:n_max + 1]])
+        # cost[n] = (c_T + draft + extra verification time of the n - 1 drafted nodes) / c_T, and its derivative
+        cost, dcost = B.smart_cost_tables_biased(lam, 0.0, fit["gamma"], fit["delta"], fit["rho"], c_T, c_T, float(batch),
+                                                 1, n_max)
         if args.forest == "product":
             import types
             rng_f = np.random.default_rng(base.seed + 7)
@@ -147,19 +133,27 @@ def main(argv=None):
             forest = W.make_forest(base.scaled(batch=min(batch, 32)))
         sel = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost,
                                   alpha=base.alpha, max_depth=base.max_depth, budget=n_max)
-        n_sel = np.diff(sel["cu_nodes"])
-        row = dict(batch=batch, forest=args.forest, with_dense=bool(args.with_dense), sizes=args.sizes, us=[round(float(v), 2) for v in times], c_T_us=round(float(c_T), 2),
+        sel_d = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost, dcost,
+                                    alpha=base.alpha, max_depth=base.max_depth, budget=n_max)
+        n_sel, n_sel_d = np.diff(sel["cu_nodes"]), np.diff(sel_d["cu_nodes"])
+        row = dict(batch=batch, forest=args.forest, extra=bool(extra_us), target_layers=args.target_layers,
+                   draft_layers=args.draft_layers, sizes=args.sizes, us=[round(float(v), 2) for v in times],
+                   c_T_us=round(float(c_T), 2), lam=lam,
                    gamma=fit["gamma"], delta=fit["delta"], rho=fit["rho"],
                    rms_us=round(float(np.sqrt(fit["sse"] / len(x))), 3),
                    tree_nodes_min_median_max=[int(n_sel.min()), int(np.median(n_sel)), int(n_sel.max())],
-                   L_mean=round(float(sel["L"].mean()), 3), R_mean=round(float(sel["R"].mean()), 3))
+                   L_mean=round(float(sel["L"].mean()), 3), R_mean=round(float(sel["R"].mean()), 3),
+                   derivative_tree_nodes_min_median_max=[int(n_sel_d.min()), int(np.median(n_sel_d)), int(n_sel_d.max())],
+                   derivative_R_mean=round(float(sel_d["R"].mean()), 3))
         # The fixed expand-and-rerank policy over the same forests, under the same cost table: its modelled
         # speedup, and what the kernel really takes for both policies' trees (measured R = L c_T / time).
         fixed = B.smart_baseline_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost,
                                       k=args.baseline_k, max_depth=args.baseline_depth, g=min(args.baseline_g, n_max - 1))
         for name, res in (("smart", sel), ("baseline", fixed)):
             cu, parent, L_mean = tiled(res, batch)
-            us = time_attention(w, cu, parent) + dense_us(int(cu[-1]))
+            one = layer_us(w, cu, parent)
+            # a verification pass of these trees, and the draft side's time for their drafted tokens
+            us = args.target_layers * one + args.draft_layers * max(one - layer_1, 0.0)
             row[name + "_us"] = round(float(us), 2)
             row[name + "_measured_R"] = round(L_mean * float(c_T) / float(us), 3)
         row["baseline_nodes"] = int(np.median(np.diff(fixed["cu_nodes"])))

@@ -57,19 +57,22 @@ constexpr double kLogSLo = -13.815510557964274 /* log 1e-6 */, kLogSHi = 3.68887
 
 }  // namespace
 
-extern "C" int32_t smart_cost_tables(double lambda, double gamma, double delta, double rho, double c_T,
-                                     double tokens_per_node, int32_t n_max, double* h_cost,
-                                     double* h_dcost) {
-  if (!h_cost || n_max < 0 || !(c_T > 0.0) || !(tokens_per_node > 0.0) || !(rho > 0.0) || !(delta >= 0.0) ||
-      !(gamma >= 0.0) || !(lambda >= 0.0))
+extern "C" int32_t smart_cost_tables_biased(double lambda, double beta, double gamma, double delta, double rho,
+                                            double eta, double c_T, double tokens_per_node,
+                                            int32_t undrafted_nodes, int32_t n_max, double* h_cost,
+                                            double* h_dcost) {
+  if (!h_cost || n_max < 0 || undrafted_nodes < 0 || !(c_T > 0.0) || !(tokens_per_node > 0.0) || !(rho > 0.0) ||
+      !(delta >= 0.0) || !(gamma >= 0.0) || !(lambda >= 0.0) || !(beta >= 0.0) || !(eta >= 0.0) ||
+      !std::isfinite(beta) || !std::isfinite(eta))
     return SMART_EINVAL;
+  auto tokens = [&](int n) { return tokens_per_node * (double)(n > undrafted_nodes ? n - undrafted_nodes : 0); };
   for (int n = 0; n <= n_max + 1; ++n) {
-    const double x = tokens_per_node * n;
-    h_cost[n] = (lambda * x + gamma * expm1(delta * pow(x, rho))) / c_T;
+    const double x = tokens(n);
+    h_cost[n] = (lambda * x + gamma * expm1(delta * pow(x, rho)) + beta + eta) / c_T;
   }
   if (h_dcost) {
     for (int n = 0; n <= n_max; ++n) {
-      const double x = tokens_per_node * n;
+      const double x = tokens(n);
       if (x == 0.0 && rho < 1.0)
         h_dcost[n] = std::numeric_limits<double>::infinity();
       else
@@ -77,6 +80,12 @@ extern "C" int32_t smart_cost_tables(double lambda, double gamma, double delta, 
     }
   }
   return SMART_OK;
+}
+
+extern "C" int32_t smart_cost_tables(double lambda, double gamma, double delta, double rho, double c_T,
+                                     double tokens_per_node, int32_t n_max, double* h_cost,
+                                     double* h_dcost) {
+  return smart_cost_tables_biased(lambda, 0.0, gamma, delta, rho, 0.0, c_T, tokens_per_node, 0, n_max, h_cost, h_dcost);
 }
 
 extern "C" int32_t smart_fit_cost_models(int32_t n_points, const double* h_x, const double* h_t_draft,

@@ -95,3 +95,61 @@ def test_fitted_tables_drive_the_selection_rule():
         assert got["parent"].tolist() == [p for t in ref for p in t.parent]
         sizes.append(int(got["cu_nodes"][-1]))
     assert all(a >= b for a, b in zip(sizes, sizes[1:])) and sizes[0] > sizes[-1]
+
+
+@pytest.mark.parametrize("params", [(0.02, 0.0, 1.5, 0.002, 1.2, 4.0, 4.0, 32.0, 1, 64), (0.1, 0.3, 3.0, 1e-5, 2.0, 0.7, 1.0, 1.0, 0, 128),
+                                    (0.3, 0.0, 0.7, 0.05, 0.5, 2.5, 2.5, 8.0, 2, 20)])
+def test_biased_tables_match_the_oracle(params):
+    lam, beta, gamma, delta, rho, eta, c_T, tpn, undrafted, n_max = params
+    cost, dcost = B.smart_cost_tables_biased(lam, beta, gamma, delta, rho, eta, c_T, tpn, undrafted, n_max)
+    r_cost, r_dcost = CM.cost_tables_biased(lam, beta, gamma, delta, rho, eta, c_T, tpn, undrafted, n_max)
+    assert np.allclose(cost, r_cost, rtol=1e-12, atol=0)
+    inf = np.isinf(r_dcost)
+    assert np.array_equal(np.isinf(dcost), inf)
+    assert np.allclose(dcost[~inf], np.array(r_dcost)[~inf], rtol=1e-12, atol=0)
+    lib = B._lib()
+    buf = (ctypes.c_double * (n_max + 2))()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert lib.smart_cost_tables_biased(lam, -1.0, gamma, delta, rho, eta, c_T, tpn, undrafted, n_max, p, None) == B.SMART_EINVAL
+    assert lib.smart_cost_tables_biased(lam, beta, gamma, delta, rho, float("inf"), c_T, tpn, undrafted, n_max, p, None) == B.SMART_EINVAL
+    assert lib.smart_cost_tables_biased(lam, beta, gamma, delta, rho, eta, c_T, tpn, -1, n_max, p, None) == B.SMART_EINVAL
+
+
+def test_draft_and_verify_legs_with_both_marginal_costs():
+    """The whole loop of Sec. 3.1 / 3.2 on the host with BOTH cost legs: a linear draft cost (Eq. "linear_model",
+    lambda fitted) and a power-exponential verification cost (Eq. "exp_model") measured as extra time over the plain
+    step, tables built by the library alone, and the rule run once with the exact finite difference and once with
+    the differentiated marginal cost of Eq. "marginal_cost".  Library against the oracle in every leg: the fitted
+    lambda, the tables, and the trees, L and R of both runs."""
+    from oracle import selection as OS
+    from paper_2604_09731_amd import workloads as W
+    batch = 32
+    n_nodes = np.array([4.0, 8.0, 16.0, 32.0, 64.0])
+    x = batch * (n_nodes - 1.0)                              # drafted tokens (the root is not drafted)
+    c_T = 80.0
+    extra_verify = _curve(x, 25.0, 6e-4, 1.15)              # verification time over the plain step, microseconds
+    extra_draft = 0.004 * x                                 # the draft model's time for those tokens
+    fit = B.smart_fit_cost_models(x, extra_draft, extra_verify)
+    assert fit["lambda"] == pytest.approx(CM.fit_linear(x, extra_draft), rel=1e-12)
+    w = W.WORKLOADS["cfg3a"].scaled(batch=6)
+    forest = W.make_forest(w)
+    cost, dcost = B.smart_cost_tables_biased(fit["lambda"], 0.0, fit["gamma"], fit["delta"], fit["rho"], c_T, c_T, batch, 1, w.budget)
+    r_cost, r_dcost = CM.cost_tables_biased(fit["lambda"], 0.0, fit["gamma"], fit["delta"], fit["rho"], c_T, c_T, batch, 1, w.budget)
+    assert cost[1] == 1.0 and np.allclose(cost, r_cost, rtol=1e-12, atol=0)
+    sizes = {}
+    for name, marginal, r_marginal in (("difference", None, None), ("derivative", dcost, list(r_dcost))):
+        got = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost, marginal,
+                                  alpha=w.alpha, max_depth=w.max_depth, budget=w.budget)
+        ref = OS.select_batch(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, list(r_cost),
+                              r_marginal, alpha=w.alpha, max_depth=w.max_depth, budget=w.budget)
+        assert got["cu_nodes"].tolist() == np.cumsum([0] + [len(t.parent) for t in ref]).tolist()
+        assert got["parent"].tolist() == [p for t in ref for p in t.parent]
+        assert np.allclose(got["L"], [t.L for t in ref], rtol=0, atol=0) and np.allclose(got["R"], [t.R for t in ref], rtol=1e-15)
+        sizes[name] = np.diff(got["cu_nodes"])
+    # the derivative at n nodes is below the step to n + 1 nodes of a convex cost, so it can only let more nodes in
+    assert (sizes["derivative"] >= sizes["difference"]).all()
+    # the draft leg matters: without it the trees are at least as large
+    cost_nd, _ = B.smart_cost_tables_biased(0.0, 0.0, fit["gamma"], fit["delta"], fit["rho"], c_T, c_T, batch, 1, w.budget)
+    no_draft = B.smart_select_tree(forest.cand_cu, forest.cand_parent, forest.cand_prob, forest.cand_token, cost_nd, None,
+                                   alpha=w.alpha, max_depth=w.max_depth, budget=w.budget)
+    assert (np.diff(no_draft["cu_nodes"]) >= sizes["difference"]).all()
