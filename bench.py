@@ -80,6 +80,10 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for rocprofv3 byte counters)")
+    ap.add_argument("--loop", choices=["verify", "full"], default="verify",
+                    help="verify: select -> upload+pack -> attention -> accept (the headline step); full: the step of a "
+                         "drop-in verification layer, select -> upload+pack -> tree_rope -> attention -> accept -> "
+                         "tree_commit (the accepted path's K/V rows go into the cache after every sequence's prefix)")
     ap.add_argument("--no-second", action="store_true", help="with the default workload: do not also time cfg3b")
     ap.add_argument("--cost-loop", action="store_true",
                     help="instead of the benchmark: the paper's cost-model loop on this device "
@@ -102,8 +106,10 @@ def main():
         from paper_2604_09731_amd import cost_loop
         cost_loop.main(args.rest, extra_us=dense_layer_us() if args.with_dense else None)
         return
-    result = measure(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
-    if args.workload == "cfg3a" and args.kv == "bf16" and args.accept == "greedy" and not args.no_second:
+    # (the full loop rotates the queries and keys in place step after step: no oracle comparison there)
+    result = measure(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline and args.loop == "verify")
+    if (args.workload == "cfg3a" and args.kv == "bf16" and args.accept == "greedy" and args.loop == "verify"
+            and not args.no_second):
         second = measure(args, "cfg3b", min(args.steps, 100), min(args.warmup, 20), False)
         result["also"] = {"cfg3b": {k: second[k] for k in ("value", "unit", "steps", "config", "breakdown_us",
                                                            "attention_tflops", "attention_mfma_frac", "roofline",
@@ -237,13 +243,23 @@ def measure(args, workload, steps, warmup, cpu_baseline):
                                kc8, vc8, B.SMART_KV_INTERLEAVED, bs_, nb_, Hkv_ * bs_ * D_, bs_ * D_, *KV_SCALES)
         torch.cuda.synchronize()
         kc, vc = kc8, vc8
+    block_table_np = inp.block_table
+    if args.loop == "full":
+        # room for the accepted path after every prefix: one more block per sequence, listed right after its last one
+        assert args.kv == "bf16", "--loop full runs on the bf16 cache"
+        nb0 = kc.shape[0]
+        grow = lambda c: torch.cat([c, torch.zeros((Bsz,) + tuple(c.shape[1:]), dtype=c.dtype, device=dev)])
+        kc, vc = grow(kc), grow(vc)
+        used = (inp.prefix_len + 15) // 16
+        block_table_np = np.concatenate([inp.block_table, np.full((Bsz, 1), -1, np.int32)], axis=1)
+        block_table_np[np.arange(Bsz), used] = nb0 + np.arange(Bsz, dtype=np.int32)
     # Several copies of the cache, used in turn from step to step, at least two and enough for 1 GiB together:
     # a cache of a few hundred MB or less (the fp8 cache of cfg3a, 233 MB; cfg2's 34 MB) would otherwise stay in
     # the 256 MB last-level cache from one step to the next, which a real model's many layers never allow.
     cache_bytes = kc.numel() * kc.element_size() + vc.numel() * vc.element_size()
     n_caches = max(2, 2 * int(np.ceil((1 << 30) / cache_bytes / 2)))     # even: copy j pairs with staging buffer j & 1
     caches = [(kc, vc)] + [(kc.clone(), vc.clone()) for _ in range(n_caches - 1)]
-    block_table = torch.from_numpy(inp.block_table).to(dev)
+    block_table = torch.from_numpy(np.ascontiguousarray(block_table_np)).to(dev)
     prefix_len = torch.from_numpy(inp.prefix_len).to(dev)
     if forest is not None:
         target_np = W.make_target_next(forest, cu_nodes, h_cand[:N], seed=w.seed + 1)
@@ -308,8 +324,19 @@ def measure(args, workload, steps, warmup, cpu_baseline):
         if target_prob is not None:
             acc_args = (ctx, stream, Bsz, N, w.max_depth, args.vocab, vp(d_cu), vp(d_par), vp(d_tok),
                         vp(target_prob), target_prob.stride(0), w.seed, 0, vp(accept_len), vp(accept_path), vp(bonus))
-        return pack_args, P, acc_args
+        rope_args = commit_args = None
+        if args.loop == "full":
+            dt = B.SMART_BF16 if w.dtype == "bf16" else B.SMART_F32
+            rope_args = (ctx, stream, dt, N, w.num_q_heads, w.num_kv_heads, w.head_dim, w.head_dim, B.SMART_ROPE_HALF_SPLIT,
+                         500000.0, vp(position), vp(q), vp(k_tree))
+            commit_args = (ctx, stream, dt, B.SMART_KV_INTERLEAVED, Bsz, w.max_depth, w.num_kv_heads, w.head_dim, 16,
+                           block_table.shape[1], kc.shape[0], vp(d_cu), vp(accept_len), vp(accept_path), vp(k_tree),
+                           vp(v_tree), vp(block_table), vp(prefix_len), vp(caches[ds_index][0]), vp(caches[ds_index][1]),
+                           kc.stride(0), kc.stride(1), w.head_dim, vp(new_len), vp(commit_status))
+        return pack_args, P, acc_args, rope_args, commit_args
 
+    new_len = torch.empty(Bsz, dtype=torch.int32, device=dev)
+    commit_status = torch.zeros(Bsz, dtype=torch.int32, device=dev)
     accept_call = L.tree_accept if target_prob is None else L.tree_accept_sample
     calls = [device_calls(d_stage[j & 1], j) for j in range(n_caches)]
     hp = lambda t, off: ctypes.c_void_p(t.data_ptr() + 4 * off)
@@ -320,10 +347,14 @@ def measure(args, workload, steps, warmup, cpu_baseline):
     def step(i):
         s = i & 1
         select[s]()                                              # a1: host selection
-        _, P, acc_args = calls[i % n_caches]
+        _, P, acc_args, rope_args, commit_args = calls[i % n_caches]
         rc = L.tree_upload_pack(*upload_pack_args[s])            # tree CSR to the GPU + a2, one launch
+        if rope_args is not None:
+            rc = rc or L.tree_rope(*rope_args)                   # rotary embedding by the tree's position ids
         rc = rc or L.tree_verify_attention(ctx, stream, ctypes.byref(P))   # a3 + a4
         rc = rc or accept_call(*acc_args)                        # a5
+        if commit_args is not None:
+            rc = rc or L.tree_commit(*commit_args)               # the accepted path's K/V rows into the cache
         if rc:
             raise B.SmartError(rc, "verify step")
 
@@ -375,12 +406,16 @@ def measure(args, workload, steps, warmup, cpu_baseline):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps
 
-    pack_args, P, acc_args = calls[0]
+    pack_args, P, acc_args, rope_args, commit_args = calls[0]
     import itertools
     flip = itertools.cycle(range(n_caches))                     # go round the cache copies here too
     att_us = time_device(lambda: L.tree_verify_attention(ctx, stream, ctypes.byref(calls[next(flip)][1])))
     pack_us = time_device(lambda: L.tree_upload_pack(*upload_pack_args[0]))
     acc_us = time_device(lambda: accept_call(*acc_args))
+    rope_us = time_device(lambda: L.tree_rope(*rope_args)) if rope_args is not None else None
+    commit_us = time_device(lambda: L.tree_commit(*commit_args)) if commit_args is not None else None
+    if commit_args is not None:
+        assert not commit_status.cpu().numpy().any()
     th0 = time.perf_counter()
     for _ in range(50):
         select[0]()
@@ -426,9 +461,11 @@ def measure(args, workload, steps, warmup, cpu_baseline):
                    "prefix_len_min_max": [int(inp.prefix_len.min()), int(inp.prefix_len.max())],
                    "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
                    "block_size": 16, "kv_layout": "interleaved", "kv_cache": args.kv, "accept": args.accept,
+                   "loop": args.loop,
                    **({"vocab": args.vocab} if args.accept == "sample" else {})},
         "breakdown_us": {"select_host": round(sel_us, 1), "tree_upload_pack": round(pack_us, 2),
-                         "tree_verify_attention": round(att_us, 2), ("tree_accept" if args.accept == "greedy" else "tree_accept_sample"): round(acc_us, 2)},
+                         "tree_verify_attention": round(att_us, 2), ("tree_accept" if args.accept == "greedy" else "tree_accept_sample"): round(acc_us, 2),
+                         **({"tree_rope": round(rope_us, 2), "tree_commit": round(commit_us, 2)} if rope_us is not None else {})},
         "attended_tokens_per_s": round(work["attended_tokens"] / (att_us * 1e-6), 1),
         "attention_tflops": round(tflops, 2),
         "attention_mfma_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),

@@ -70,6 +70,8 @@ enum {
 };
 
 enum { SMART_F32 = 0, SMART_BF16 = 1 };
+/* tva_params.d_status values */
+enum { SMART_TVA_BAD_BLOCK = 1 };
 /* Element type of an fp8 KV cache (cache only; q, tree k / v and outputs stay SMART_F32 / SMART_BF16):
  * E4M3 of the OCP 8-bit floating point specification (bias 7, no infinities, largest value 448). */
 enum { SMART_FP8_E4M3 = 2 };
@@ -533,7 +535,7 @@ int32_t kv_cache_write_fp8(smart_ctx* ctx, void* stream, int32_t src_dtype, int3
  * Shapes: q, out [total_nodes][Hq][D]; k_tree, v_tree [total_nodes][Hkv][D]
  * (tree K/V are not in the cache yet); block_table [batch][max_blocks_per_seq]
  * (entries past a sequence's prefix are never read; read entries are clamped
- * to [0, num_blocks)); prefix_len is clamped to
+ * to [0, num_blocks) and reported through d_status); prefix_len is clamped to
  * [0, max_blocks_per_seq * block_size]; anc_mask as written by tree_pack.
  * total_nodes may exceed d_cu_nodes[batch] (a capacity, when only the device
  * knows the trees' sizes: see tree_compact_pack): rows from d_cu_nodes[batch]
@@ -575,6 +577,12 @@ typedef struct {
    * without it.  If given it must agree with d_cu_nodes. */
   const int32_t* h_cu_nodes;
   float k_scale, v_scale; /* fp8 cache only: positive, finite */
+  /* Optional [batch] (device) or NULL: per sequence 0, or SMART_TVA_BAD_BLOCK if one of the block-table entries the
+   * call reads for it (the first ceil(prefix_len / block_size) of its row) lies outside [0, num_blocks).  Such an
+   * entry is read as the nearest valid block, so the call stays inside the cache, but that sequence's output is
+   * then not meaningful.  Written for every sequence by every call that gets the pointer and has work to launch
+   * (batch > 0 and total_nodes > 0). */
+  int32_t* d_status;
 } tva_params;
 
 int32_t tree_verify_attention(smart_ctx* ctx, void* stream, const tva_params* params);

@@ -18,6 +18,7 @@ LIB_PATH = os.environ.get("SMART_TREE_LIB") or os.path.join(_HERE, "libsmart_tre
 SMART_OK, SMART_EINVAL, SMART_ETREE, SMART_ECAP, SMART_EHIP, SMART_ENOMEM = 0, -1, -2, -3, -4, -5
 SMART_F32, SMART_BF16 = 0, 1
 SMART_FP8_E4M3 = 2
+SMART_TVA_BAD_BLOCK = 1
 SMART_KV_PLAIN, SMART_KV_INTERLEAVED = 0, 1
 SMART_BEST_FIRST, SMART_LAYERWISE = 0, 1
 SMART_DILUTION_NONE, SMART_DILUTION_PATH_MEAN = 0, 1
@@ -58,6 +59,7 @@ class TvaParams(ctypes.Structure):
         ("d_out", ctypes.c_void_p), ("d_lse", ctypes.c_void_p),
         ("h_cu_nodes", ctypes.c_void_p),
         ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float),
+        ("d_status", ctypes.c_void_p),
     ]
 
 
@@ -557,9 +559,10 @@ class SmartTree:
     def tree_verify_attention(self, q, k_tree, v_tree, k_cache, v_cache, block_table, prefix_len,
                               cu_nodes, anc_mask, softmax_scale, kv_layout, block_size=16,
                               out=None, lse=None, want_lse=False, h_cu_nodes=None, k_scale=None, v_scale=None,
-                              static=False):
+                              static=False, status=None):
         """k_cache / v_cache: [num_blocks, Hkv, ...] with one contiguous page of
         block_size * D elements per (block, head) (any of the two layouts).
+        ``status``: optional int32 [B] tensor that receives the per-sequence block-table check.
         ``static``: call tree_verify_attention_static (no device allocation inside the library;
         pass ``out`` / ``lse`` so that nothing is allocated here either)."""
         torch = _torch()
@@ -595,6 +598,7 @@ class SmartTree:
         p.d_anc_mask = anc_mask.data_ptr()
         p.d_out = out.data_ptr()
         p.d_lse = lse.data_ptr() if lse is not None else None
+        p.d_status = status.data_ptr() if status is not None else None
         if h_cu_nodes is not None:      # numpy int32 [B+1], host copy of cu_nodes
             h_cu_nodes = np.ascontiguousarray(h_cu_nodes, np.int32)
             assert h_cu_nodes.shape[0] == B + 1

@@ -81,5 +81,26 @@ void tva_mfma_workspace(const smart_ctx* ctx, int32_t batch, int32_t total_nodes
                         int32_t num_kv_heads, size_t* ws_bytes, size_t* plan_bytes);
 int32_t tva_mfma_default_workers(const smart_ctx* ctx);
 
+#ifdef __HIPCC__
+// One wavefront checks the block-table entries a call reads for sequence b (the first ceil(len / block_size) of its
+// row, len clamped like the kernels clamp it) and writes status[b]: 0, or SMART_TVA_BAD_BLOCK if one of them lies
+// outside [0, num_blocks) (the kernels read such an entry as the nearest valid block).
+__device__ inline void tva_validate_block_table(int b, const int32_t* block_table, const int32_t* prefix_len,
+                                                int max_blocks, int block_size, int num_blocks, int32_t* status,
+                                                int lane) {
+  const int cap = max_blocks * block_size;
+  int len = prefix_len[b];
+  len = len < 0 ? 0 : (len > cap ? cap : len);
+  const int n_blocks = (len + block_size - 1) / block_size;
+  bool bad = false;
+  for (int i = lane; i < n_blocks; i += 64) {
+    const int32_t e = block_table[(size_t)b * max_blocks + i];
+    bad = bad || e < 0 || e >= num_blocks;
+  }
+  const bool any_bad = __any(bad);
+  if (lane == 0) status[b] = any_bad ? SMART_TVA_BAD_BLOCK : 0;
+}
+#endif
+
 }  // namespace smart
 #endif

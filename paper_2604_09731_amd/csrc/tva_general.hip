@@ -62,10 +62,14 @@ __global__ __launch_bounds__(kWave) void tva_general_kernel(
     const C* __restrict__ k_cache, const C* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ prefix_len,
     const int32_t* __restrict__ cu_nodes, const uint64_t* __restrict__ anc_mask,
-    T* __restrict__ out, float* __restrict__ lse) {
+    T* __restrict__ out, float* __restrict__ lse, int32_t* __restrict__ status) {
   __shared__ float s_q[128];
   const int lane = threadIdx.x;
   const int row = blockIdx.x;
+  // block-table check: the wavefronts share the sequences between them
+  if (status)
+    for (int b = row; b < batch; b += gridDim.x)
+      smart::tva_validate_block_table(b, block_table, prefix_len, max_blocks, lay.block_size, num_blocks, status, lane);
   const int node = row / Hq, h = row % Hq;
   if (node >= total_nodes) return;
   const int g = h / (Hq / Hkv);
@@ -182,7 +186,7 @@ int32_t tva_launch_general(smart_ctx* ctx, hipStream_t stream, const tva_params&
                      p.total_nodes, p.num_q_heads, p.num_kv_heads, p.head_dim, p.max_blocks_per_seq,         \
                      p.num_blocks, p.softmax_scale, ks, vs, lay, (const T*)p.d_q, (const T*)p.d_k_tree,      \
                      (const T*)p.d_v_tree, (const C*)p.d_k_cache, (const C*)p.d_v_cache, p.d_block_table,    \
-                     p.d_prefix_len, p.d_cu_nodes, p.d_anc_mask, (T*)p.d_out, p.d_lse)
+                     p.d_prefix_len, p.d_cu_nodes, p.d_anc_mask, (T*)p.d_out, p.d_lse, p.d_status)
   if (p.dtype == SMART_F32) {
     if (fp8) SMART_LAUNCH_GENERAL(float, uint8_t); else SMART_LAUNCH_GENERAL(float, float);
   } else {

@@ -1735,6 +1735,11 @@ struct CombineArgs {
   int32_t batch, Hq, Hkv, G;
   float scale, scale_log2e;
   int32_t only_small;  // fp8 cache: every sequence was streamed as class 1, in row groups of 64 rows
+  // block-table check (status may be null: no check)
+  const int32_t* block_table;
+  const int32_t* prefix_len;
+  int32_t* status;
+  int32_t max_blocks, num_blocks;
 };
 
 __device__ inline float bf16_to_f32(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
@@ -1754,6 +1759,9 @@ constexpr int kKeyBatch = 4;
 __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   const int wc = blockIdx.x;
   const int lane = threadIdx.x;
+  // the first `batch` wavefronts also check one sequence's block-table entries each (the grid has at least that many)
+  if (a.status && wc < a.batch)
+    smart::tva_validate_block_table(wc, a.block_table, a.prefix_len, a.max_blocks, kBlock, a.num_blocks, a.status, lane);
   const PlanView pv = plan_view(a.plan, a.batch);
   int b;
   if (a.batch <= kWave) {
@@ -2085,6 +2093,11 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p,
   ca.scale = p.softmax_scale;
   ca.scale_log2e = p.softmax_scale * kLog2e;
   ca.only_small = fp8 ? 1 : 0;
+  ca.block_table = p.d_block_table;
+  ca.prefix_len = p.d_prefix_len;
+  ca.status = p.d_status;
+  ca.max_blocks = p.max_blocks_per_seq;
+  ca.num_blocks = p.num_blocks;
   const int64_t max_chunks =
       (int64_t)p.num_kv_heads * (((int64_t)p.total_nodes * G + kCombineRows - 1) / kCombineRows + p.batch);
   if (max_chunks > 0x7FFFFFFF) return SMART_EINVAL;

@@ -439,6 +439,40 @@ def test_offsets_that_are_no_running_sum(lib):
                 assert (out.float() == 7.0).all()
 
 
+@pytest.mark.parametrize("force_general", [0, 1])
+def test_block_table_entries_outside_the_cache_are_reported(lib, force_general):
+    """Entries of the block table that the call reads and that lie outside [0, num_blocks) are read as the nearest
+    valid block (nothing leaves the cache) and reported per sequence; entries past a sequence's prefix are never
+    read and never reported; a later call with a sound table clears the report."""
+    import torch
+    rng = np.random.default_rng(4)
+    sizes = [5, 20, 70, 3, 9]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([W.random_tree(n, rng, "random") for n in sizes]).astype(np.int32)
+    w = W.Workload("table", "bf16", len(sizes), 8, 2, 128, 0, 0, seed=19)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([100, 333, 64, 0, 50], np.int32), trees=(cu, parent))
+    _, _, _, mask, _ = lib.tree_pack(case.cu_nodes, case.parent_d, case.prefix_len)
+    nb = case.k_cache.shape[0]
+    bt = case.block_table.clone()
+    bt[1, 3] = -5                       # read: sequence 1 uses blocks 0 .. 20
+    bt[2, 3] = nb + 3                   # read: the last block sequence 2 uses (64 tokens = blocks 0 .. 3)
+    bt[0, 7] = nb + 100                 # not read: sequence 0 uses blocks 0 .. 6
+    bt[4, 4:] = -9                      # not read: sequence 4 uses blocks 0 .. 3
+    lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, force_general)
+    try:
+        for table, expect in ((bt, [0, 1, 1, 0, 0]), (case.block_table, [0, 0, 0, 0, 0])):
+            status = torch.full((len(sizes),), 77, dtype=torch.int32, device="cuda")
+            out = lib.tree_verify_attention(case.q, case.k_tree, case.v_tree, case.k_cache, case.v_cache, table,
+                                            case.prefix_len, case.cu_nodes, mask, case.inp.scale, B.SMART_KV_INTERLEAVED,
+                                            status=status)
+            torch.cuda.synchronize()
+            assert status.cpu().tolist() == [e * B.SMART_TVA_BAD_BLOCK for e in expect]
+            ok_rows = torch.cat([out[cu[b]:cu[b + 1]] for b in (0, 3, 4)])
+            assert torch.isfinite(ok_rows.float()).all()
+    finally:
+        lib.set_option(B.SMART_OPT_TVA_FORCE_GENERAL, 0)
+
+
 # ----- seeded random shapes: batch sizes around the 64-sequence plan window, group sizes 1..16, ------
 # ----- all three row classes mixed in one call, chains / stars / random trees, ragged and empty prefixes
 @pytest.mark.parametrize("seed", [1, 2])
