@@ -92,6 +92,49 @@ struct SeqInfo {
   int32_t rg;     // row groups (1 for class 1)
 };
 
+// Class 2 shares its workers by time rather than by tiles.  The eight wavefronts of a workgroup take one 32-row
+// tile each (two per SIMD), so a 32-key tile of a segment with up to four row tiles takes what one wavefront
+// takes (measured: 0.68 .. 0.76 us), and with five or more what two on one SIMD take (0.9 .. 1.07 us); starting
+// and finishing a piece takes 11 .. 13 us.  In units of 0.06 us: kLargeTileCost[row tiles] per tile and
+// kLargeSegStart per segment; a worker's share of that space that begins inside the start cost of a segment
+// begins at the segment's first tile.
+constexpr int kLargeTileCost[kLargeRows / 32 + 1] = {11, 11, 11, 12, 12, 16, 16, 17, 17};
+constexpr int kLargeSegStart = 200;
+// (the same currency for a tile of classes 0 and 1, for dealing the workgroups to the classes)
+constexpr int kClassTileCost[kClasses] = {9, 11, 1};
+
+// What the unit space of class 2 holds of one sequence: per kv head its row groups in order, all but the last
+// with eight row tiles.
+struct LargeSpans {
+  int32_t cost_last;   // cost of a tile of the last row group
+  int64_t span_full;   // units of a row group with eight row tiles
+  int64_t span_last;   // units of the last row group
+  int64_t span_head;   // units of one kv head: (rg - 1) span_full + span_last
+};
+__host__ __device__ inline LargeSpans large_spans(const SeqInfo& si, int G) {
+  LargeSpans ls;
+  const int rows_last = si.n * G - (si.rg - 1) * kLargeRows;
+  ls.cost_last = kLargeTileCost[rows_last > 0 ? (rows_last + 31) / 32 : 0];
+  const bool any = si.tiles > 0 && si.rg > 0;
+  ls.span_full = any ? kLargeSegStart + (int64_t)si.tiles * (kLargeTileCost[kLargeRows / 32]) : 0;
+  ls.span_last = any ? kLargeSegStart + (int64_t)si.tiles * ls.cost_last : 0;
+  ls.span_head = any ? (si.rg - 1) * ls.span_full + ls.span_last : 0;
+  return ls;
+}
+// Units of the whole sequence (classes 0 and 1: its tiles per kv head; class 2: in the cost currency).
+__host__ __device__ inline int64_t sequence_units(const SeqInfo& si, int cls, int G, int Hkv) {
+  if (cls < 2) return (int64_t)si.tiles * Hkv * si.rg;
+  return large_spans(si, G).span_head * Hkv;
+}
+// Tile of a class-2 segment at which a share that begins `off` units into the segment begins.
+__host__ __device__ inline int large_tile_at(int64_t off, int cost, int tiles) {
+  const int64_t t = off <= kLargeSegStart ? 0 : (off - kLargeSegStart) / cost;
+  return t > tiles ? tiles : (int)t;
+}
+// First unit of worker w of W over U units (w = W: U).  Every piece of code that cuts the unit space of class 2
+// calls this one function, so that workers and the combine step agree on the pieces.
+__host__ __device__ inline int64_t share_begin(int64_t w, int64_t U, int64_t W) { return (w * U) / W; }
+
 // Segments (partial-result slot groups) per class that the host left room for.
 struct SegCaps {
   int64_t segs[kClasses];
@@ -213,7 +256,7 @@ template <bool kOnlySmall = false>
 __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
                                  int64_t (&first_wg)[kClasses + 1]) {
   const int64_t tot_u[kClasses] = {kOnlySmall ? 0 : all_u[0], all_u[1], kOnlySmall ? 0 : all_u[2]};
-  const int64_t weight[kClasses] = {2, 2, 3};
+  const int64_t weight[kClasses] = {kClassTileCost[0], kClassTileCost[1], kClassTileCost[2]};
   const int64_t launched = workgroups > kClasses ? workgroups : kClasses;
   int64_t cost[kClasses], total = 0;
 #pragma unroll
@@ -222,18 +265,33 @@ __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroup
     total += cost[c];
   }
   int64_t wg[kClasses], used = 0;
+  double frac[kClasses];
   int biggest = 0;
 #pragma unroll
   for (int c = 0; c < kClasses; ++c) {
     // (binary64 division: exact enough for a share of a few hundred workgroups, far cheaper than
     // a 64-bit integer division, and every wavefront that plans runs this same code)
-    wg[c] = tot_u[c] > 0 ? (int64_t)((double)cost[c] * (double)launched / (double)(total > 0 ? total : 1)) : 0;
-    if (tot_u[c] > 0 && wg[c] < 1) wg[c] = 1;
+    const double share = tot_u[c] > 0 ? (double)cost[c] * (double)launched / (double)(total > 0 ? total : 1) : 0.0;
+    wg[c] = (int64_t)share;
+    frac[c] = share - (double)wg[c];
+    if (tot_u[c] > 0 && wg[c] < 1) wg[c] = 1, frac[c] = 0.0;
     used += wg[c];
     if (cost[c] > cost[biggest]) biggest = c;
   }
-  // at most kClasses - 1 shares were raised to one, so the biggest class can give those back
-  const int64_t rest = launched - used;
+  // What the rounding left over goes one by one to the classes with the largest remainders (a few workgroups
+  // of a small class differ by tens of percent in its finishing time); at most kClasses - 1 shares were raised
+  // to one, which the biggest class gives back.
+  int64_t rest = launched - used;
+  for (int k = 0; k < kClasses && rest > 0; ++k) {
+    int best = -1;
+#pragma unroll
+    for (int c = 0; c < kClasses; ++c)
+      if (tot_u[c] > 0 && frac[c] > 0.0 && (best < 0 || frac[c] > frac[best])) best = c;
+    if (best < 0) break;
+    wg[best] += 1;
+    frac[best] = 0.0;
+    rest -= 1;
+  }
 #pragma unroll
   for (int c = 0; c < kClasses; ++c)
     if (c == biggest && wg[c] + rest >= 1) wg[c] += rest;
@@ -241,7 +299,7 @@ __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroup
 #pragma unroll
   for (int c = 0; c < kClasses; ++c) {
     int64_t w = wg[c];  // a worker is a workgroup in every class
-    const int64_t cap = tot_u[c] / kMinTilesPerWorker[c];
+    const int64_t cap = tot_u[c] / (kMinTilesPerWorker[c] * (c == 2 ? kLargeTileCost[kLargeRows / 32] : 1));
     if (w > cap) w = cap;
     if (tot_u[c] > 0 && w < 1) w = 1;
     workers[c] = w;
@@ -269,7 +327,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     pv.info[b] = si;
     const int rows = si.n * G;
     const int c = kOnlySmall ? 1 : seq_class(rows);
-    units[c] += (int64_t)si.tiles * Hkv * si.rg;
+    units[c] += sequence_units(si, c, G, Hkv);
     segs[c] += Hkv * si.rg;
     chunks += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
   }
@@ -311,7 +369,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
       pv.cum_segs[k][b] = (int32_t)s[k];
     }
     pv.cum_chunks[b] = (int32_t)ch;
-    u[c] += (int64_t)si.tiles * Hkv * si.rg;
+    u[c] += sequence_units(si, c, G, Hkv);
     s[c] += Hkv * si.rg;
     ch += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
   }
@@ -349,7 +407,7 @@ __device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const i
   for (int pass = 0; pass < 2; ++pass) {
     const int rows = si.n * G;
     const int cls = kOnlySmall ? 1 : seq_class(rows);
-    const int64_t my_units = (int64_t)si.tiles * Hkv * si.rg;
+    const int64_t my_units = sequence_units(si, cls, G, Hkv);
     const int64_t my_segs = Hkv * si.rg;
     int64_t tot_s, tot_c;
 #pragma unroll
@@ -1316,7 +1374,7 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
     for (int ks = 0; ks < 8; ++ks) q[ks] = *(const bf16x8*)(qp + ks * 16);
 #pragma unroll
     for (int jt = 0; jt < 4; ++jt) o[jt] = (floatx16)(0.f);
-    asm volatile("" ::"v"(q[0]), "v"(q[7]));  // landed: the counted waits below see tile fetches only
+    // (not waited for here: the tile requests below are younger loads, so the wait for the first tile covers these)
   }
   const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
   const int n_blocks = (si.len + kBlock - 1) / kBlock;
@@ -1576,8 +1634,8 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
   const int64_t U = cp.U, W = cp.W;
   PlanWindow& win = cp.win;
   if (w >= W || U <= 0) return;
-  int64_t u0 = (w * U) / W;
-  const int64_t u1 = ((w + 1) * U) / W;
+  int64_t u0 = share_begin(w, U, W);
+  const int64_t u1 = share_begin(w + 1, U, W);
   if (u0 >= u1) return;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1589,27 +1647,44 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
     if (u0 >= seq_end) { ++b; continue; }
     const SeqInfo si = window_info(win, b);
     const int64_t local = u0 - seq_begin;
-    const int seg_local = (int)(local / si.tiles);
-    const int t0 = (int)(local % si.tiles);
-    const int g = seg_local / si.rg, rgi = seg_local % si.rg;
-    const int64_t left = u1 - u0;
-    const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
-    const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
     const int base = __builtin_amdgcn_readlane(win.cu_nodes, b - win.first);
     if (kCls == 1) {
+      const int seg_local = (int)(local / si.tiles);
+      const int t0 = (int)(local % si.tiles);
+      const int g = seg_local;
+      const int64_t left = u1 - u0;
+      const int nt = (int)(left < (int64_t)(si.tiles - t0) ? left : (int64_t)(si.tiles - t0));
+      const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
       // At most 64 rows: row tiles 0 and 1 of four, times two key groups.  (Two row tiles x four
       // key groups would keep every wavefront busy but leaves only one iteration of fetches in
       // flight; measured slower.)
       grouped_segment<4>(a, b, g, base, t0, t0 + nt, si, a.ws[1] + (size_t)(w + seg) * kMediumSlot, kMediumRows, wv,
                          lane, lds);
+      u0 += nt;
     } else {
+      // the unit space of class 2 is a cost: see large_spans and large_tile_at
+      const LargeSpans ls = large_spans(si, a.G);
+      const int g = (int)(local / ls.span_head);
+      const int64_t in_head = local - (int64_t)g * ls.span_head;
+      int rgi = (int)(in_head / ls.span_full);
+      rgi = rgi < si.rg - 1 ? rgi : si.rg - 1;
+      const int64_t off = in_head - (int64_t)rgi * ls.span_full;
+      const int cost = rgi < si.rg - 1 ? kLargeTileCost[kLargeRows / 32] : ls.cost_last;
+      const int64_t span = rgi < si.rg - 1 ? ls.span_full : ls.span_last;
+      const int seg_local = g * si.rg + rgi;
+      const int64_t seg_end = u0 - off + span;
+      const int64_t stop = u1 < seg_end ? u1 : seg_end;
+      const int t0 = large_tile_at(off, cost, si.tiles);
+      const int t1 = stop == seg_end ? si.tiles : large_tile_at(off + (stop - u0), cost, si.tiles);
+      u0 = stop;
+      if (t1 <= t0) continue;  // the share ends inside the start cost, or covers less than a tile
+      const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
       float* slot = a.ws[2] + (size_t)(w + seg) * kLargeSlot;
       // rows of the group are dealt to the eight wavefronts in 32-row tiles
       const int row0 = rgi * kLargeRows + wv * 32;
-      if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
-      else staged_segment<false>(a, b, g, base, row0, t0, t0 + nt, si, slot, wv, lane, lds);
+      if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t1, si, slot, wv, lane, lds);
+      else staged_segment<false>(a, b, g, base, row0, t0, t1, si, slot, wv, lane, lds);
     }
-    u0 += nt;
   }
 }
 
@@ -1874,13 +1949,24 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
     const int rgi = rho / rows_per_group;
     const int seg_local = g * si.rg + rgi;
     const int64_t seg = seg_base + seg_local;
-    const int64_t ub = unit_base + (int64_t)seg_local * si.tiles;
-    const int64_t ue = ub + si.tiles - 1;
+    const LargeSpans ls = large_spans(si, a.G);
+    const bool last_group = rgi == si.rg - 1;
+    const int64_t span = cls < 2 ? si.tiles : (last_group ? ls.span_last : ls.span_full);
+    const int64_t ub = unit_base + (cls < 2 ? (int64_t)seg_local * si.tiles : g * ls.span_head + rgi * ls.span_full);
+    const int64_t ue = ub + span - 1;
     const int64_t w_first = ((ub + 1) * W - 1) / U;
     const int64_t w_last = ((ue + 1) * W - 1) / U;
     const int row = rho % rows_per_group;  // = qt * 32 + j
     const int qt = row >> 5, j = row & 31;
+    const int cost = last_group ? ls.cost_last : kLargeTileCost[kLargeRows / 32];
     for (int64_t w = w_first; w <= w_last; ++w) {
+      if (cls == 2) {
+        // a share of class 2 may hold no tile of a segment it touches (large_tile_at): then it left no partial
+        const int64_t s0 = share_begin(w, U, W), s1 = share_begin(w + 1, U, W);
+        const int t0 = large_tile_at((s0 > ub ? s0 : ub) - ub, cost, si.tiles);
+        const int t1 = s1 > ue ? si.tiles : large_tile_at(s1 - ub, cost, si.tiles);
+        if (t1 <= t0) continue;
+      }
       const float* slot = ws + (size_t)(w + seg) * slot_floats;
       const float mc = slot[rows_per_group * kD + row];
       const float lc = slot[rows_per_group * kD + rows_per_group + row];
