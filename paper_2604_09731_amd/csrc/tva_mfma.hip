@@ -1677,9 +1677,16 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
       const int t0 = large_tile_at(off, cost, si.tiles);
       const int t1 = stop == seg_end ? si.tiles : large_tile_at(off + (stop - u0), cost, si.tiles);
       u0 = stop;
-      if (t1 <= t0) continue;  // the share ends inside the start cost, or covers less than a tile
       const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
       float* slot = a.ws[2] + (size_t)(w + seg) * kLargeSlot;
+      if (t1 <= t0) {
+        // The share ends inside the segment's start cost, or covers less than a tile of it (rare).  The combine step
+        // merges the partial of every worker whose share touches the segment, so this one leaves a partial that adds
+        // nothing: row maxima of -inf (weight exp2(-inf) = 0), sums and O of zero.
+        for (int i = threadIdx.x; i < kLargeSlot; i += kWgWaves * kWave)
+          slot[i] = i >= kLargeRows * kD && i < kLargeRows * kD + kLargeRows ? -INFINITY : 0.f;
+        continue;
+      }
       // rows of the group are dealt to the eight wavefronts in 32-row tiles
       const int row0 = rgi * kLargeRows + wv * 32;
       if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t1, si, slot, wv, lane, lds);
@@ -1958,15 +1965,7 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
     const int64_t w_last = ((ue + 1) * W - 1) / U;
     const int row = rho % rows_per_group;  // = qt * 32 + j
     const int qt = row >> 5, j = row & 31;
-    const int cost = last_group ? ls.cost_last : kLargeTileCost[kLargeRows / 32];
     for (int64_t w = w_first; w <= w_last; ++w) {
-      if (cls == 2) {
-        // a share of class 2 may hold no tile of a segment it touches (large_tile_at): then it left no partial
-        const int64_t s0 = share_begin(w, U, W), s1 = share_begin(w + 1, U, W);
-        const int t0 = large_tile_at((s0 > ub ? s0 : ub) - ub, cost, si.tiles);
-        const int t1 = s1 > ue ? si.tiles : large_tile_at(s1 - ub, cost, si.tiles);
-        if (t1 <= t0) continue;
-      }
       const float* slot = ws + (size_t)(w + seg) * slot_floats;
       const float mc = slot[rows_per_group * kD + row];
       const float lc = slot[rows_per_group * kD + rows_per_group + row];
