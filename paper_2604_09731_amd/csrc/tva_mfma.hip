@@ -1836,7 +1836,7 @@ __device__ inline uint16_t f32_to_bf16(float v) {
 // Memory round trips are the cost here, so independent loads are issued in
 // batches: the plan entries together, four tree keys (K and V rows) at a time,
 // and all of a partial's pieces at once.
-constexpr int kKeyBatch = 4;
+constexpr int kKeyBatch = 2;  // (4 and 8 measured slower: the registers they hold cost resident wavefronts)
 
 __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   const int wc = blockIdx.x;
