@@ -94,14 +94,12 @@ struct SeqInfo {
 
 // Class 2 shares its workers by time rather than by tiles.  The eight wavefronts of a workgroup take one 32-row
 // tile each (two per SIMD), so a 32-key tile of a segment with up to four row tiles takes what one wavefront
-// takes (measured: 0.68 .. 0.76 us), and with five or more what two on one SIMD take (0.9 .. 1.07 us); starting
-// and finishing a piece takes 11 .. 13 us.  In units of 0.06 us: kLargeTileCost[row tiles] per tile and
-// kLargeSegStart per segment; a worker's share of that space that begins inside the start cost of a segment
-// begins at the segment's first tile.
+// takes (measured: 0.68 .. 0.76 us), and with five or more what two on one SIMD take (0.9 .. 1.07 us).  In units
+// of 0.06 us: kLargeTileCost[row tiles] per tile.  (Starting and finishing a piece takes 11 .. 13 us on top; a
+// start cost per segment in the unit space, 0 .. 200 units, changed nothing measurable and is not modelled.)
 constexpr int kLargeTileCost[kLargeRows / 32 + 1] = {11, 11, 11, 12, 12, 16, 16, 17, 17};
-constexpr int kLargeSegStart = 200;
 // (the same currency for a tile of classes 0 and 1, for dealing the workgroups to the classes)
-constexpr int kClassTileCost[kClasses] = {9, 11, 1};
+constexpr int kClassTileCost[kClasses] = {10, 10, 1};
 
 // What the unit space of class 2 holds of one sequence: per kv head its row groups in order, all but the last
 // with eight row tiles.
@@ -116,8 +114,8 @@ __host__ __device__ inline LargeSpans large_spans(const SeqInfo& si, int G) {
   const int rows_last = si.n * G - (si.rg - 1) * kLargeRows;
   ls.cost_last = kLargeTileCost[rows_last > 0 ? (rows_last + 31) / 32 : 0];
   const bool any = si.tiles > 0 && si.rg > 0;
-  ls.span_full = any ? kLargeSegStart + (int64_t)si.tiles * (kLargeTileCost[kLargeRows / 32]) : 0;
-  ls.span_last = any ? kLargeSegStart + (int64_t)si.tiles * ls.cost_last : 0;
+  ls.span_full = any ? (int64_t)si.tiles * kLargeTileCost[kLargeRows / 32] : 0;
+  ls.span_last = any ? (int64_t)si.tiles * ls.cost_last : 0;
   ls.span_head = any ? (si.rg - 1) * ls.span_full + ls.span_last : 0;
   return ls;
 }
@@ -126,9 +124,10 @@ __host__ __device__ inline int64_t sequence_units(const SeqInfo& si, int cls, in
   if (cls < 2) return (int64_t)si.tiles * Hkv * si.rg;
   return large_spans(si, G).span_head * Hkv;
 }
-// Tile of a class-2 segment at which a share that begins `off` units into the segment begins.
+// Tile of a class-2 segment at which a share that begins `off` units into the segment begins (a share boundary
+// inside a tile goes down to the tile's beginning).
 __host__ __device__ inline int large_tile_at(int64_t off, int cost, int tiles) {
-  const int64_t t = off <= kLargeSegStart ? 0 : (off - kLargeSegStart) / cost;
+  const int64_t t = off / cost;
   return t > tiles ? tiles : (int)t;
 }
 // First unit of worker w of W over U units (w = W: U).  Every piece of code that cuts the unit space of class 2
@@ -244,12 +243,11 @@ __device__ inline bool offsets_malformed(int base, int next, int total_nodes) {
 }
 
 // The prefix kernel is ONE launch of max(workgroups, kClasses) workgroups; the classes share
-// them in proportion to their work, so that all of them finish together.  A class-2 tile
-// costs more than its bytes (it is multiplied against up to 256 rows).  Every class with
-// work gets at least one workgroup, the shares are rounded down, and what is left over goes
-// to the class with the most work, so the classes never need more workgroups than were
-// launched.  Returns the workers per class and the first workgroup of each class (entry
-// kClasses: one past the last).
+// them in proportion to their cost (kClassTileCost per tile of classes 0 and 1; the units of class 2
+// are costs already), so that all of them finish together.  Every class with work gets at least one
+// workgroup, the shares are rounded down, and what is left over goes to the classes whose workgroups
+// are loaded most, so the classes never need more workgroups than were launched.  Returns the workers
+// per class and the first workgroup of each class (entry kClasses: one past the last).
 // kOnlySmall: the fp8-cache kernel puts every sequence in class 1 (row groups of 64 rows), so that
 // class gets every workgroup.
 template <bool kOnlySmall = false>
@@ -265,31 +263,27 @@ __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroup
     total += cost[c];
   }
   int64_t wg[kClasses], used = 0;
-  double frac[kClasses];
   int biggest = 0;
 #pragma unroll
   for (int c = 0; c < kClasses; ++c) {
     // (binary64 division: exact enough for a share of a few hundred workgroups, far cheaper than
     // a 64-bit integer division, and every wavefront that plans runs this same code)
-    const double share = tot_u[c] > 0 ? (double)cost[c] * (double)launched / (double)(total > 0 ? total : 1) : 0.0;
-    wg[c] = (int64_t)share;
-    frac[c] = share - (double)wg[c];
-    if (tot_u[c] > 0 && wg[c] < 1) wg[c] = 1, frac[c] = 0.0;
+    wg[c] = tot_u[c] > 0 ? (int64_t)((double)cost[c] * (double)launched / (double)(total > 0 ? total : 1)) : 0;
+    if (tot_u[c] > 0 && wg[c] < 1) wg[c] = 1;
     used += wg[c];
     if (cost[c] > cost[biggest]) biggest = c;
   }
-  // What the rounding left over goes one by one to the classes with the largest remainders (a few workgroups
-  // of a small class differ by tens of percent in its finishing time); at most kClasses - 1 shares were raised
-  // to one, which the biggest class gives back.
+  // What the rounding left over (fewer than kClasses workgroups) goes one by one to the class whose workgroups carry
+  // the most cost each: the kernel ends with its slowest class, and a class of four workgroups that is owed 4.5 runs
+  // 12 % longer than the rest.  At most kClasses - 1 shares were raised to one, which the biggest class gives back.
   int64_t rest = launched - used;
   for (int k = 0; k < kClasses && rest > 0; ++k) {
-    int best = -1;
+    int worst = -1;
 #pragma unroll
     for (int c = 0; c < kClasses; ++c)
-      if (tot_u[c] > 0 && frac[c] > 0.0 && (best < 0 || frac[c] > frac[best])) best = c;
-    if (best < 0) break;
-    wg[best] += 1;
-    frac[best] = 0.0;
+      if (tot_u[c] > 0 && (worst < 0 || (double)cost[c] * (double)wg[worst] > (double)cost[worst] * (double)wg[c])) worst = c;
+    if (worst < 0) break;
+    wg[worst] += 1;
     rest -= 1;
   }
 #pragma unroll
@@ -299,7 +293,7 @@ __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroup
 #pragma unroll
   for (int c = 0; c < kClasses; ++c) {
     int64_t w = wg[c];  // a worker is a workgroup in every class
-    const int64_t cap = tot_u[c] / (kMinTilesPerWorker[c] * (c == 2 ? kLargeTileCost[kLargeRows / 32] : 1));
+    const int64_t cap = tot_u[c] / (kMinTilesPerWorker[c] * (c == 2 ? kLargeTileCost[0] : 1));
     if (w > cap) w = cap;
     if (tot_u[c] > 0 && w < 1) w = 1;
     workers[c] = w;
@@ -1680,7 +1674,7 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
       const int64_t seg = (int64_t)__builtin_amdgcn_readlane(win.cum_segs, b - win.first) + seg_local;
       float* slot = a.ws[2] + (size_t)(w + seg) * kLargeSlot;
       if (t1 <= t0) {
-        // The share ends inside the segment's start cost, or covers less than a tile of it (rare).  The combine step
+        // The share covers less than a tile of this segment (rare).  The combine step
         // merges the partial of every worker whose share touches the segment, so this one leaves a partial that adds
         // nothing: row maxima of -inf (weight exp2(-inf) = 0), sums and O of zero.
         for (int i = threadIdx.x; i < kLargeSlot; i += kWgWaves * kWave)
