@@ -174,6 +174,12 @@ __host__ __device__ inline PlanView plan_view(void* base, int batch) {
 }
 
 __host__ __device__ inline int seq_class(int rows) { return rows <= kSmallRows ? 0 : (rows <= kMediumRows ? 1 : 2); }
+// With an fp8 cache there is no class 0: trees of up to 64 rows are class 1 (streamed into registers, one or two row
+// tiles), larger ones class 2 (tiles staged in LDS as for bf16, after conversion).
+template <bool kFp8>
+__host__ __device__ inline int plan_class(int rows) {
+  return kFp8 ? (rows <= kMediumRows ? 1 : 2) : seq_class(rows);
+}
 
 __device__ inline int64_t readlane64(int64_t v, int lane) {
   const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, lane);
@@ -215,7 +221,7 @@ __device__ inline int64_t wave_excl_scan(int64_t v, int lane, int64_t* total) {
 // offsets themselves are checked by offsets_malformed for the whole batch: only a running sum
 // guarantees that the sizes add up to at most total_nodes, which is what the host sized the
 // partial-result slots and the combine grid for.
-// kAllMedium (fp8 cache): every sequence is class 1, in row groups of 64 rows.
+// (The row groups are the same with an fp8 cache: one up to 64 rows, else groups of 256.)
 template <bool kAllMedium = false>
 __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_nodes, int G, int max_blocks) {
   const int cap = max_blocks * kBlock;
@@ -228,10 +234,7 @@ __device__ inline SeqInfo sequence_info(int len, int base, int next, int total_n
   si.len = len;
   si.n = n;
   si.tiles = (len + kTile - 1) / kTile;
-  if (kAllMedium)
-    si.rg = (rows + kMediumRows - 1) / kMediumRows;
-  else
-    si.rg = rows == 0 ? 0 : (seq_class(rows) < 2 ? 1 : (rows + kLargeRows - 1) / kLargeRows);
+  si.rg = rows == 0 ? 0 : (rows <= kMediumRows ? 1 : (rows + kLargeRows - 1) / kLargeRows);
   return si;
 }
 
@@ -248,12 +251,11 @@ __device__ inline bool offsets_malformed(int base, int next, int total_nodes) {
 // workgroup, the shares are rounded down, and what is left over goes to the classes whose workgroups
 // are loaded most, so the classes never need more workgroups than were launched.  Returns the workers
 // per class and the first workgroup of each class (entry kClasses: one past the last).
-// kOnlySmall: the fp8-cache kernel puts every sequence in class 1 (row groups of 64 rows), so that
-// class gets every workgroup.
+// kOnlySmall: the plan of the fp8-cache kernel, which has no class 0 (plan_class).
 template <bool kOnlySmall = false>
 __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
                                  int64_t (&first_wg)[kClasses + 1]) {
-  const int64_t tot_u[kClasses] = {kOnlySmall ? 0 : all_u[0], all_u[1], kOnlySmall ? 0 : all_u[2]};
+  const int64_t tot_u[kClasses] = {kOnlySmall ? 0 : all_u[0], all_u[1], all_u[2]};
   const int64_t weight[kClasses] = {kClassTileCost[0], kClassTileCost[1], kClassTileCost[2]};
   const int64_t launched = workgroups > kClasses ? workgroups : kClasses;
   int64_t cost[kClasses], total = 0;
@@ -320,7 +322,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
     if (malformed) si.n = si.rg = 0;
     pv.info[b] = si;
     const int rows = si.n * G;
-    const int c = kOnlySmall ? 1 : seq_class(rows);
+    const int c = plan_class<kOnlySmall>(rows);
     units[c] += sequence_units(si, c, G, Hkv);
     segs[c] += Hkv * si.rg;
     chunks += Hkv * ((rows + kCombineRows - 1) / kCombineRows);
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(kWave) void tva_plan_kernel(
       pv.info[b] = si;
     }
     const int rows = si.n * G;
-    const int c = kOnlySmall ? 1 : seq_class(rows);
+    const int c = plan_class<kOnlySmall>(rows);
     for (int k = 0; k < kClasses; ++k) {
       pv.cum_units[k][b] = u[k];
       pv.cum_segs[k][b] = (int32_t)s[k];
@@ -400,7 +402,7 @@ __device__ inline void lane_plan(LanePlan& p, const int32_t* prefix_len, const i
   // hint that does not hold; then nothing runs)
   for (int pass = 0; pass < 2; ++pass) {
     const int rows = si.n * G;
-    const int cls = kOnlySmall ? 1 : seq_class(rows);
+    const int cls = plan_class<kOnlySmall>(rows);
     const int64_t my_units = sequence_units(si, cls, G, Hkv);
     const int64_t my_segs = Hkv * si.rg;
     int64_t tot_s, tot_c;
@@ -622,8 +624,10 @@ __device__ inline void softmax_tile(const floatx16& s, float& m, float& l, float
 
 // Writes one 32-row tile of a partial: O as [d / 4][row][4] so that lanes
 // write contiguous 16-byte pieces; then the row maxima and sums.
+// (fp8 cache: the scores were taken against the raw key bytes and O against the raw value bytes, so the row maxima
+// leave multiplied by m_scale = k_scale and O by o_scale = v_scale; both are 1 for a bf16 cache.)
 __device__ inline void store_partial(float* slot, int rows_in_slot, int qt, const floatx16 (&o)[4],
-                                     float m, float l, int lane) {
+                                     float m, float l, int lane, float m_scale = 1.f, float o_scale = 1.f) {
   const int h = lane >> 5, j = lane & 31;
   const float lsum = sum_across_halves(l);
 #pragma unroll
@@ -632,14 +636,14 @@ __device__ inline void store_partial(float* slot, int rows_in_slot, int qt, cons
     for (int r4 = 0; r4 < 4; ++r4) {
       const int chunk = jt * 8 + 2 * r4 + h;
       floatx4 x;
-      x[0] = o[jt][4 * r4 + 0];
-      x[1] = o[jt][4 * r4 + 1];
-      x[2] = o[jt][4 * r4 + 2];
-      x[3] = o[jt][4 * r4 + 3];
+      x[0] = o[jt][4 * r4 + 0] * o_scale;
+      x[1] = o[jt][4 * r4 + 1] * o_scale;
+      x[2] = o[jt][4 * r4 + 2] * o_scale;
+      x[3] = o[jt][4 * r4 + 3] * o_scale;
       *(floatx4*)(slot + ((size_t)(qt * 32 + chunk) * 32 + j) * 4) = x;
     }
   if (h == 0) {
-    slot[rows_in_slot * kD + qt * 32 + j] = m;
+    slot[rows_in_slot * kD + qt * 32 + j] = m * m_scale;  // (-inf stays -inf)
     slot[rows_in_slot * kD + rows_in_slot + qt * 32 + j] = lsum;
   }
 }
@@ -1204,6 +1208,70 @@ __device__ inline void request_tile(const MainArgs& a, const FetchLane& f, int32
   }
 }
 
+// The same tile out of an fp8 cache.  The pages have the same element order with one byte per element, so the two
+// operand vectors a lane is responsible for are 8 bytes each, 256 bytes apart.  They travel HBM -> LDS as four
+// dwords per lane (the LDS-direct load takes 4 or 16 bytes a lane) into this wavefront's 1 KB of a raw slot:
+// plane p of 64 dwords holds dword p of every lane (vector 0 low, vector 0 high, vector 1 low, vector 1 high).
+// convert_tile_fp8 then turns them into the two bf16 operand vectors of the stage, exactly (E4M3 -> bf16).
+__device__ inline FetchLane fetch_lane_fp8(const MainArgs& a, int wv, int lane) {
+  const int h = lane >> 5, j = lane & 31;
+  const uint8_t* kb = (const uint8_t*)a.k_cache;
+  const uint8_t* vb = (const uint8_t*)a.v_cache;
+  FetchLane f;
+  if (wv < 4) {
+    f.base = (const __bf16*)(kb + (h * 16 + sigma(j & 15)) * 8 + wv * 2 * 256);
+    f.second_page = -(int64_t)(j >> 4);
+  } else {
+    f.base = (const __bf16*)(vb + (h * kD + j) * 8 + 2 * ((wv - 4) & 1) * 256);
+    f.second_page = -(int64_t)((wv - 4) >> 1);
+  }
+  return f;
+}
+
+__device__ inline void request_tile_fp8(const MainArgs& a, const FetchLane& f, int32_t blk0, int32_t blk1, int g,
+                                        uint32_t* raw /* this wavefront's 4 x 64 dwords of the slot */, bool again) {
+  const int64_t page0 = clamp_block(blk0, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
+  const int64_t page1 = clamp_block(blk1, a.num_blocks) * a.block_stride + (int64_t)g * a.head_stride;
+  const uint8_t* src = (const uint8_t*)f.base + (page0 ^ ((page0 ^ page1) & f.second_page));
+  if (again) {
+    __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)raw, 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 4), (lds_void*)(raw + kWave), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(raw + 2 * kWave), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 260), (lds_void*)(raw + 3 * kWave), 4, 0, 0);
+  } else {
+    __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)raw, 4, 0, kStreamPolicy);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 4), (lds_void*)(raw + kWave), 4, 0, kStreamPolicy);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 256), (lds_void*)(raw + 2 * kWave), 4, 0, kStreamPolicy);
+    __builtin_amdgcn_global_load_lds((global_void*)(src + 260), (lds_void*)(raw + 3 * kWave), 4, 0, kStreamPolicy);
+  }
+}
+
+// raw_addr: LDS byte address of this lane's dword in plane 0 of the raw slot; dst_addr: that of its first operand
+// vector in the stage (the second is 64 vectors further).  Written as assembly like the operand reads: an LDS access
+// the compiler can see makes it wait for every LDS-direct load in flight.  Ends with the writes done.
+__device__ inline void convert_tile_fp8(uint32_t raw_addr, uint32_t dst_addr) {
+  uint32_t d0, d1, d2, d3;
+  asm volatile(
+      "ds_read_b32 %0, %4\n\t"
+      "ds_read_b32 %1, %4 offset:256\n\t"
+      "ds_read_b32 %2, %4 offset:512\n\t"
+      "ds_read_b32 %3, %4 offset:768\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(d0), "=&v"(d1), "=&v"(d2), "=&v"(d3)
+      : "v"(raw_addr)
+      : "memory");
+  fp8x8 r0, r1;
+  r0[0] = d0, r0[1] = d1, r1[0] = d2, r1[1] = d3;
+  const bf16x8 b0 = operand(r0), b1 = operand(r1);
+  asm volatile(
+      "ds_write_b128 %0, %1\n\t"
+      "ds_write_b128 %0, %2 offset:1024\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      :
+      : "v"(dst_addr), "v"(b0), "v"(b1)
+      : "memory");
+}
+
 // LDS reads of the staged tiles are written as assembly: the compiler would otherwise wait
 // for every outstanding global_load_lds before each read it can see.  The counter waits
 // below carry the registers they release as operands, so that no use can move above them.
@@ -1351,9 +1419,14 @@ __device__ inline void woven_tile(const floatx16& s, floatx16& s_next, floatx16 
 
 // All eight wavefronts of the workgroup run this together (it contains barriers);
 // kRows = false marks a wavefront without rows in this row group: it only helps to fetch.
-template <bool kRows>
+// kFp8: the cache holds E4M3 bytes.  LDS then holds four bf16 stages (a tile is used during two iterations) and,
+// behind them, kStages raw slots of 8 KB; a wavefront converts its own share of tile t + 1 as soon as it has
+// landed (nobody else touches those bytes), before the barrier that publishes the stage.
+template <bool kRows, bool kFp8 = false>
 __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base, int row0, int t0, int t1,
                                       const SeqInfo si, float* slot, int wv, int lane, bf16x8* lds) {
+  constexpr int kRing = kFp8 ? 4 : kStages;  // bf16 stages
+  constexpr int kLoads = kFp8 ? 4 : 2;       // vector-memory loads per tile and wavefront
   const int h = lane >> 5, j = lane & 31;
   const int M = si.n * a.G;
   floatx16 o[4];
@@ -1373,10 +1446,22 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
   const int32_t* bt_row = a.block_table + (int64_t)b * a.max_blocks;
   const int n_blocks = (si.len + kBlock - 1) / kBlock;
   const float c = a.scale_log2e;
-  const FetchLane f = fetch_lane(a, wv, lane);
+  const FetchLane f = kFp8 ? fetch_lane_fp8(a, wv, lane) : fetch_lane(a, wv, lane);
   const uint32_t rd = lds_address(lds + lane);  // this lane's slice of vector 0 of stage 0
   const int last = t1 - 1;
-  auto stage_of = [&](int t) { return lds + (t & (kStages - 1)) * kStageVecs; };
+  auto stage_of = [&](int t) { return lds + (t & (kRing - 1)) * kStageVecs; };
+  // fp8: this wavefront's 4 x 64 dwords of tile t's raw slot, and the conversion of its share of tile t
+  uint32_t* const raw_base = (uint32_t*)(lds + kRing * kStageVecs) + wv * (4 * kWave);
+  auto raw_of = [&](int t) { return raw_base + (t & (kStages - 1)) * (kWgWaves * 4 * kWave); };
+  auto request = [&](int32_t blk0, int32_t blk1, int t, bool again) {
+    if (kFp8) request_tile_fp8(a, f, blk0, blk1, g, raw_of(t), again);
+    else request_tile(a, f, blk0, blk1, g, stage_of(t), wv, again);
+  };
+  auto convert = [&](int t) {
+    if (kFp8)
+      convert_tile_fp8(lds_address(raw_of(t) + lane),
+                       rd + ((t & (kRing - 1)) * kStageVecs + 2 * wv * kWave) * 16);
+  };
   auto block_id = [&](int t, int which) { return sload(bt_row + min(2 * min(t, last) + which, n_blocks - 1)); };
   auto land = [&](int t) {  // after this wavefront's share of tile t arrived: mend a ragged tile
     const int n_valid = si.len - t * kTile;
@@ -1386,33 +1471,35 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
   __builtin_amdgcn_s_barrier();  // the previous segment is done with every stage
 #pragma unroll
   for (int i = 0; i < kStages - 1; ++i)  // tiles t0 .. t0 + kStages - 2; past the end: the last tile again (L2 hits)
-    request_tile(a, f, block_id(t0 + i, 0), block_id(t0 + i, 1), g, stage_of(t0 + i), wv, t0 + i > last || si.rg > 1);
+    request(block_id(t0 + i, 0), block_id(t0 + i, 1), t0 + i, t0 + i > last || si.rg > 1);
   int32_t nb0 = block_id(t0 + kStages - 1, 0), nb1 = block_id(t0 + kStages - 1, 1);
   asm volatile("" ::"s"(nb0), "s"(nb1));
-  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // 2 (kStages - 2): tile t0 is in
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads * (kStages - 2)) : "memory");  // tile t0 is in
+  convert(t0);
   land(t0);
   __builtin_amdgcn_s_barrier();
   floatx16 s;
   if (kRows) {
-    score_tile(s, rd + (t0 & (kStages - 1)) * (kStageVecs * 16), q);
+    score_tile(s, rd + (t0 & (kRing - 1)) * (kStageVecs * 16), q);
     if (si.len - t0 * kTile < kTile) mask_scores(s, si.len - t0 * kTile, h);
   }
   // iteration t: s_in holds the scores of tile t, s_out receives those of tile t + 1.  Only a sequence's last tile
   // can be ragged, so the iterations that land and mask a full tile (kChecked = false) carry no test for it.
   auto iter = [&](auto checked, int t, const floatx16& s_in, floatx16& s_out) {
     constexpr bool kChecked = decltype(checked)::value;
-    asm volatile("s_waitcnt vmcnt(10)" ::: "memory");  // 2 (kStages - 3): tile t + 1 is in
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads * (kStages - 3)) : "memory");  // tile t + 1 is in
+    convert(t + 1);
     if (kChecked) land(t + 1);
     // every share of tile t + 1 is visible, and everyone is done with tile t - 1
     __builtin_amdgcn_s_barrier();
     auto fetch = [&]() {
-      request_tile(a, f, nb0, nb1, g, stage_of(t + kStages - 1), wv, t + kStages - 1 > last || si.rg > 1);
+      request(nb0, nb1, t + kStages - 1, t + kStages - 1 > last || si.rg > 1);
       nb0 = block_id(t + kStages, 0);
       nb1 = block_id(t + kStages, 1);
     };
     if (kRows) {
-      const uint32_t k_addr = rd + ((t + 1) & (kStages - 1)) * (kStageVecs * 16);
-      const uint32_t v_addr = rd + (t & (kStages - 1)) * (kStageVecs * 16) + 8 * kWave * 16;
+      const uint32_t k_addr = rd + ((t + 1) & (kRing - 1)) * (kStageVecs * 16);
+      const uint32_t v_addr = rd + (t & (kRing - 1)) * (kStageVecs * 16) + 8 * kWave * 16;
       woven_tile(s_in, s_out, o, m, l, q, k_addr, v_addr, c, fetch);
       if (kChecked) {
         const int nv_next = si.len - (t + 1) * kTile;
@@ -1437,7 +1524,7 @@ __device__ inline void staged_segment(const MainArgs& a, int b, int g, int base,
     s = s2;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no fetch of this segment may land later
-  if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane);
+  if (kRows) store_partial(slot, kLargeRows, wv, o, m, l, lane, a.m_scale, a.o_scale);
 }
 
 // One staged tile against this wavefront's 32 rows, nothing woven in: all 16 operand reads
@@ -1622,7 +1709,7 @@ __device__ inline void grouped_segment(const MainArgs& a, int b, int g, int base
 }
 
 // Worker of classes 1 and 2 (kCls): a workgroup walks the pieces of its share of the class's units.
-template <int kCls>
+template <int kCls, bool kFp8 = false>
 __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp, bf16x8* lds /* 132 KB: kStages tiles, or eight states */) {
   const PlanView pv = plan_view(a.plan, a.batch);
   const int64_t U = cp.U, W = cp.W;
@@ -1683,15 +1770,15 @@ __device__ inline void staged_worker(const MainArgs& a, int64_t w, ClassPlan& cp
       }
       // rows of the group are dealt to the eight wavefronts in 32-row tiles
       const int row0 = rgi * kLargeRows + wv * 32;
-      if (row0 < si.n * a.G) staged_segment<true>(a, b, g, base, row0, t0, t1, si, slot, wv, lane, lds);
-      else staged_segment<false>(a, b, g, base, row0, t0, t1, si, slot, wv, lane, lds);
+      if (row0 < si.n * a.G) staged_segment<true, kFp8>(a, b, g, base, row0, t0, t1, si, slot, wv, lane, lds);
+      else staged_segment<false, kFp8>(a, b, g, base, row0, t0, t1, si, slot, wv, lane, lds);
     }
   }
 }
 
 // ---- the prefix kernel: one launch, workgroups apportioned to the classes by the plan ------
-// kFp8: the cache holds E4M3 bytes; every sequence is class 1 (row groups of 64 rows) and streamed
-// into registers by fp8_worker (a sequence with more rows re-reads its tiles once per row group).
+// kFp8: the cache holds E4M3 bytes; trees of up to 64 rows are class 1 and streamed into registers by
+// fp8_worker, larger ones are class 2 and go through the staged loop after conversion to bf16 in LDS.
 template <bool kFp8>
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
@@ -1784,6 +1871,7 @@ void tva_prefix_kernel(MainArgs a) {
   if (wg >= end) return;
   if (kFp8) {
     if (wg >= first1 && wg < first2) fp8_worker(a, wg - first1, cp, (float*)lds_raw);
+    else if (wg >= first2) staged_worker<2, true>(a, wg - first2, cp, (bf16x8*)lds_raw);
     return;
   }
   if (wg < first1) {
@@ -1810,7 +1898,7 @@ struct CombineArgs {
   float* lse;
   int32_t batch, Hq, Hkv, G;
   float scale, scale_log2e;
-  int32_t only_small;  // fp8 cache: every sequence was streamed as class 1, in row groups of 64 rows
+  int32_t only_small;  // fp8 cache: the classes are those of plan_class<true>
   // block-table check (status may be null: no check)
   const int32_t* block_table;
   const int32_t* prefix_len;
@@ -1857,7 +1945,7 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
     b = lo;
   }
   const SeqInfo si = sload(pv.info + b);
-  const int cls = a.only_small ? 1 : seq_class(si.n * a.G);
+  const int cls = a.only_small ? plan_class<true>(si.n * a.G) : seq_class(si.n * a.G);
   const int chunk_base = sload(pv.cum_chunks + b);
   const int base = sload(a.cu_nodes + b);
   const int64_t U = sload(pv.header + 2 * cls), W = sload(pv.header + 2 * cls + 1);
@@ -2017,7 +2105,7 @@ static void segment_bounds(int32_t batch, int32_t total_nodes, int32_t num_q_hea
                            int64_t (&segs)[kClasses]) {
   const int64_t G = num_q_heads / num_kv_heads;
   segs[0] = (int64_t)num_kv_heads * batch;
-  segs[1] = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kMediumRows - 1) / kMediumRows + batch);
+  segs[1] = (int64_t)num_kv_heads * batch;
   segs[2] = (int64_t)num_kv_heads * (((int64_t)total_nodes * G + kLargeRows - 1) / kLargeRows + batch);
 }
 
@@ -2034,8 +2122,8 @@ static bool segment_counts(const int32_t* h_cu_nodes, int32_t batch, int32_t tot
     n = n > SMART_MAX_NODES ? SMART_MAX_NODES : n;
     const int rows = (int)n * G;
     if (rows == 0) continue;
-    if (fp8) segs[1] += (int64_t)num_kv_heads * ((rows + kMediumRows - 1) / kMediumRows);
-    else if (seq_class(rows) < 2) segs[seq_class(rows)] += num_kv_heads;
+    const int cls = fp8 ? plan_class<true>(rows) : seq_class(rows);
+    if (cls < 2) segs[cls] += num_kv_heads;
     else segs[2] += (int64_t)num_kv_heads * ((rows + kLargeRows - 1) / kLargeRows);
   }
   return true;

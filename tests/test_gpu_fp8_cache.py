@@ -236,6 +236,21 @@ def test_fp8_scales_are_applied(lib, oracle_attention):
         _run_fp8(lib, oracle_attention, w, cu, parent, lens, 5, k_scale=ks, v_scale=vs)
 
 
+def test_fp8_scales_and_row_groups_of_large_trees(lib, oracle_attention):
+    """Trees of more than 64 rows per kv head go through the LDS-staged loop (fp8 bytes converted to bf16 in LDS):
+    one, two and three row groups of 256 rows at 8 heads per kv head, the last group with 1, 3 and 8 row tiles,
+    ragged and exact prefix ends, an empty prefix, keys and values scaled apart."""
+    rng = np.random.default_rng(12)
+    sizes = [9, 33, 35, 64, 12, 60]                 # 72, 264, 280, 512, 96 and 480 rows per kv head
+    trees = [W.random_tree(n, rng, s) for n, s in zip(sizes, ["random", "chain", "random", "random", "star", "random"])]
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate(trees).astype(np.int32)
+    lens = np.array([1500, 257, 96, 1029, 0, 33], np.int32)
+    w = W.Workload("fp8_large", "bf16", len(sizes), 16, 2, 128, 0, 0, seed=44)
+    for ks, vs in ((0.05, 0.02), (0.011, 0.4)):
+        _run_fp8(lib, oracle_attention, w, cu, parent, lens, 44, k_scale=ks, v_scale=vs)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_tree_commit_into_an_fp8_cache(lib, dtype):
     """The accepted path's rows go into the fp8 cache as the writer would quantise them; the oracle commits the
