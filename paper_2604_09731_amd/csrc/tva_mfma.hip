@@ -100,6 +100,7 @@ struct SeqInfo {
 constexpr int kLargeTileCost[kLargeRows / 32 + 1] = {11, 11, 11, 12, 12, 16, 16, 17, 17};
 // (the same currency for a tile of classes 0 and 1, for dealing the workgroups to the classes)
 constexpr int kClassTileCost[kClasses] = {10, 10, 1};
+constexpr int kFp8StreamTileCost = 5;
 
 // What the unit space of class 2 holds of one sequence: per kv head its row groups in order, all but the last
 // with eight row tiles.
@@ -256,7 +257,10 @@ template <bool kOnlySmall = false>
 __device__ inline void apportion(const int64_t (&all_u)[kClasses], int workgroups, int64_t (&workers)[kClasses],
                                  int64_t (&first_wg)[kClasses + 1]) {
   const int64_t tot_u[kClasses] = {kOnlySmall ? 0 : all_u[0], all_u[1], all_u[2]};
-  const int64_t weight[kClasses] = {kClassTileCost[0], kClassTileCost[1], kClassTileCost[2]};
+  // (fp8 cache: class 1 is the register stream of half as many bytes per tile; measured 4 .. 8 units per tile
+  // against class 2's 11 .. 17, the higher figure where the whole launch is bound by memory)
+  const int64_t weight[kClasses] = {kClassTileCost[0], kOnlySmall ? kFp8StreamTileCost : kClassTileCost[1],
+                                    kClassTileCost[2]};
   const int64_t launched = workgroups > kClasses ? workgroups : kClasses;
   int64_t cost[kClasses], total = 0;
 #pragma unroll
