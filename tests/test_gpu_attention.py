@@ -546,3 +546,34 @@ def test_long_prefix_few_workers_shares_of_several_chunks(lib, oracle_attention)
             check_full(lib, oracle_attention, case)
         finally:
             lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
+
+
+# ----- class 2: shares cut in a space of costs, for every number of workers from 1 to 40 ---------------
+def test_large_trees_with_every_number_of_workers(lib, oracle_attention):
+    """Trees of 96, 160 and 280 rows per kv head (three, five and eight + one row tiles: the last one has two row
+    groups of unequal cost) over ragged prefixes of 22 to 33 tiles, split among 1 .. 40 workers: the share boundaries
+    fall everywhere inside the segments, also less than a tile into one (a share that holds no tile of a segment it
+    touches leaves an empty partial) and inside a tree's second row group."""
+    rng = np.random.default_rng(23)
+    sizes = [12, 20, 35]                                             # x 8 heads per kv head
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([W.random_tree(n, rng, s) for n, s in zip(sizes, ["random", "chain", "random"])]).astype(np.int32)
+    w = W.Workload("large_workers", "bf16", 3, 16, 2, 128, 0, 0, seed=29)
+    case = make_case(w, B.SMART_KV_INTERLEAVED, prefix_len=np.array([700, 1043, 801], np.int32), trees=(cu, parent), seed=29)
+    ref, ref_lse = case.oracle(oracle_attention)
+    first = None
+    for workers in range(1, 41):
+        lib.set_option(B.SMART_OPT_TVA_WORKERS, workers)
+        try:
+            out, lse = case.run(lib)
+        finally:
+            lib.set_option(B.SMART_OPT_TVA_WORKERS, 0)
+        got = H.out_to_f64(out, "bf16")
+        assert np.isfinite(got).all(), workers
+        err = H.rel_err(got, ref)
+        assert err <= H.TOL["bf16"], (workers, err)
+        assert np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max() <= 2e-2, workers
+        if first is None:
+            first = lse.cpu().numpy().copy()
+        # however the prefix is split, the log-sum-exp of a row is the same up to rounding
+        assert np.abs(lse.cpu().numpy() - first).max() <= 1e-4, workers
