@@ -41,6 +41,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 KERNEL_SAMPLES = 10             # the dominant kernel is event-timed on about this many of the timed steps (a recorded
                                 # dispatch costs its step about 4 us, so not on every one)
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+STAGE_RING = 8                  # pinned staging buffers for the selected trees, used in turn from step to step
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 
@@ -166,10 +167,10 @@ def measure(args, workload, steps, warmup, cpu_baseline):
     Bsz = w.batch
     cap = Bsz * B.SMART_MAX_NODES
 
-    # pinned staging: [cu_nodes (B+1) | parent (cap) | token (cap)] x 2, plus host-only outputs
+    # pinned staging: [cu_nodes (B+1) | parent (cap) | token (cap)] x STAGE_RING, plus host-only outputs
     n_stage = (Bsz + 1) + 2 * cap
-    stage = [torch.empty(n_stage, dtype=torch.int32).pin_memory() for _ in range(2)]
-    d_stage = [torch.empty(n_stage, dtype=torch.int32, device=dev) for _ in range(2)]
+    stage = [torch.empty(n_stage, dtype=torch.int32).pin_memory() for _ in range(STAGE_RING)]
+    d_stage = [torch.empty(n_stage, dtype=torch.int32, device=dev) for _ in range(STAGE_RING)]
     h_cand = np.zeros(cap, np.int32)
     h_pp = np.zeros(cap, np.float64)
     h_L = np.zeros(Bsz, np.float64)
@@ -214,7 +215,7 @@ def measure(args, workload, steps, warmup, cpu_baseline):
             tok[:len(ftok)] = ftok
         return run
 
-    select = [make_select(stage[0]), make_select(stage[1])]
+    select = [make_select(buf) for buf in stage]
     select[0]()
     a0 = stage[0].numpy()
     cu_nodes = a0[:Bsz + 1].copy()
@@ -257,7 +258,7 @@ def measure(args, workload, steps, warmup, cpu_baseline):
     # a cache of a few hundred MB or less (the fp8 cache of cfg3a, 233 MB; cfg2's 34 MB) would otherwise stay in
     # the 256 MB last-level cache from one step to the next, which a real model's many layers never allow.
     cache_bytes = kc.numel() * kc.element_size() + vc.numel() * vc.element_size()
-    n_caches = max(2, 2 * int(np.ceil((1 << 30) / cache_bytes / 2)))     # even: copy j pairs with staging buffer j & 1
+    n_caches = max(2, int(np.ceil((1 << 30) / cache_bytes)))
     caches = [(kc, vc)] + [(kc.clone(), vc.clone()) for _ in range(n_caches - 1)]
     block_table = torch.from_numpy(np.ascontiguousarray(block_table_np)).to(dev)
     prefix_len = torch.from_numpy(inp.prefix_len).to(dev)
@@ -296,9 +297,11 @@ def measure(args, workload, steps, warmup, cpu_baseline):
     ctx = lib._h
     vp = lambda t: ctypes.c_void_p(t.data_ptr())
 
-    stage_np = [stage[0].numpy(), stage[1].numpy()]
+    stage_np = [buf.numpy() for buf in stage]
 
-    def device_calls(ds, ds_index):
+    def device_calls(slot, ci):
+        """The calls of a step that reads staging buffer `slot` and cache copy `ci`."""
+        ds = d_stage[slot]
         d_cu, d_par, d_tok = ds[:Bsz + 1], ds[Bsz + 1:Bsz + 1 + cap], ds[Bsz + 1 + cap:]
         pack_args = (ctx, stream, Bsz, N, vp(d_cu), vp(d_par), vp(prefix_len), vp(depth), vp(position),
                      vp(node_seq), vp(anc_mask), vp(status))
@@ -310,7 +313,7 @@ def measure(args, workload, steps, warmup, cpu_baseline):
         P.block_size, P.max_blocks_per_seq, P.num_blocks = 16, block_table.shape[1], kc.shape[0]
         P.softmax_scale = inp.scale
         P.d_q, P.d_k_tree, P.d_v_tree = q.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr()
-        P.d_k_cache, P.d_v_cache = caches[ds_index][0].data_ptr(), caches[ds_index][1].data_ptr()
+        P.d_k_cache, P.d_v_cache = caches[ci][0].data_ptr(), caches[ci][1].data_ptr()
         P.cache_block_stride, P.cache_head_stride, P.cache_token_stride = kc.stride(0), kc.stride(1), w.head_dim
         P.d_block_table, P.d_prefix_len = block_table.data_ptr(), prefix_len.data_ptr()
         P.d_cu_nodes, P.d_anc_mask = d_cu.data_ptr(), anc_mask.data_ptr()
@@ -318,7 +321,7 @@ def measure(args, workload, steps, warmup, cpu_baseline):
         if args.kv == "fp8":
             P.kv_cache_dtype = B.SMART_FP8_E4M3
             P.k_scale, P.v_scale = KV_SCALES
-        P.h_cu_nodes = stage_np[ds_index & 1][:Bsz + 1].ctypes.data   # selection wrote it on the host
+        P.h_cu_nodes = stage_np[slot][:Bsz + 1].ctypes.data   # selection wrote it on the host
         acc_args = (ctx, stream, Bsz, w.max_depth, vp(d_cu), vp(d_par), vp(d_tok), vp(target_next),
                     vp(accept_len), vp(accept_path), vp(bonus))
         if target_prob is not None:
@@ -331,23 +334,25 @@ def measure(args, workload, steps, warmup, cpu_baseline):
                          500000.0, vp(position), vp(q), vp(k_tree))
             commit_args = (ctx, stream, dt, B.SMART_KV_INTERLEAVED, Bsz, w.max_depth, w.num_kv_heads, w.head_dim, 16,
                            block_table.shape[1], kc.shape[0], vp(d_cu), vp(accept_len), vp(accept_path), vp(k_tree),
-                           vp(v_tree), vp(block_table), vp(prefix_len), vp(caches[ds_index][0]), vp(caches[ds_index][1]),
+                           vp(v_tree), vp(block_table), vp(prefix_len), vp(caches[ci][0]), vp(caches[ci][1]),
                            kc.stride(0), kc.stride(1), w.head_dim, vp(new_len), vp(commit_status))
         return pack_args, P, acc_args, rope_args, commit_args
 
     new_len = torch.empty(Bsz, dtype=torch.int32, device=dev)
     commit_status = torch.zeros(Bsz, dtype=torch.int32, device=dev)
     accept_call = L.tree_accept if target_prob is None else L.tree_accept_sample
-    calls = [device_calls(d_stage[j & 1], j) for j in range(n_caches)]
+    # step i reads staging buffer i % STAGE_RING and cache copy i % n_caches: one set of calls per pair that occurs
+    n_calls = int(np.lcm(STAGE_RING, n_caches))
+    calls = [device_calls(j % STAGE_RING, j % n_caches) for j in range(n_calls)]
     hp = lambda t, off: ctypes.c_void_p(t.data_ptr() + 4 * off)
     upload_pack_args = [(ctx, stream, Bsz, N, hp(stage[i], 0), hp(stage[i], Bsz + 1), hp(stage[i], Bsz + 1 + cap),
                          hp(d_stage[i], 0), hp(d_stage[i], Bsz + 1), hp(d_stage[i], Bsz + 1 + cap), vp(prefix_len),
-                         vp(depth), vp(position), vp(node_seq), vp(anc_mask), vp(status)) for i in range(2)]
+                         vp(depth), vp(position), vp(node_seq), vp(anc_mask), vp(status)) for i in range(STAGE_RING)]
 
     def step(i):
-        s = i & 1
+        s = i % STAGE_RING
         select[s]()                                              # a1: host selection
-        _, P, acc_args, rope_args, commit_args = calls[i % n_caches]
+        _, P, acc_args, rope_args, commit_args = calls[i % n_calls]
         rc = L.tree_upload_pack(*upload_pack_args[s])            # tree CSR to the GPU + a2, one launch
         if rope_args is not None:
             rc = rc or L.tree_rope(*rope_args)                   # rotary embedding by the tree's position ids
@@ -358,18 +363,24 @@ def measure(args, workload, steps, warmup, cpu_baseline):
         if rc:
             raise B.SmartError(rc, "verify step")
 
-    # the staging buffers alternate, so a buffer is rewritten by the host two steps after its
-    # copy was enqueued; guard that with an event per buffer
-    copy_done = [torch.cuda.Event(), torch.cuda.Event()]
+    # The host rewrites a staging buffer STAGE_RING steps after the copy out of it was enqueued, and must not do so
+    # before that copy ran.  The steps go in blocks of STAGE_RING / 2: one event is recorded behind a block, and a
+    # block starts once the block two before it has finished (an event between two kernels costs the stream about
+    # 6 us on this machine, so one per step would be 5 % of cfg3a's step; one per four steps is what a serving loop
+    # that hands results over in groups would pay).
+    block = STAGE_RING // 2
+    block_done = [torch.cuda.Event(), torch.cuda.Event()]
 
     def guarded_step(i):
-        s = i & 1
-        copy_done[s].synchronize()
+        b = (i // block) & 1
+        if i % block == 0:
+            block_done[b].synchronize()
         step(i)
-        copy_done[s].record()
+        if i % block == block - 1:
+            block_done[b].record()
 
-    copy_done[0].record()
-    copy_done[1].record()
+    block_done[0].record()
+    block_done[1].record()
     for i in range(warmup):
         guarded_step(i)
     torch.cuda.synchronize()
@@ -408,7 +419,7 @@ def measure(args, workload, steps, warmup, cpu_baseline):
 
     pack_args, P, acc_args, rope_args, commit_args = calls[0]
     import itertools
-    flip = itertools.cycle(range(n_caches))                     # go round the cache copies here too
+    flip = itertools.cycle(range(n_calls))                      # go round the cache copies here too
     att_us = time_device(lambda: L.tree_verify_attention(ctx, stream, ctypes.byref(calls[next(flip)][1])))
     pack_us = time_device(lambda: L.tree_upload_pack(*upload_pack_args[0]))
     acc_us = time_device(lambda: accept_call(*acc_args))
