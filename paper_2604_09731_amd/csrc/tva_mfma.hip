@@ -1934,6 +1934,14 @@ struct CombineArgs {
 };
 
 __device__ inline float bf16_to_f32(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+typedef __attribute__((ext_vector_type(2))) uint32_t uintx2;
+typedef __attribute__((ext_vector_type(2))) float floatx2;
+// A dword as a pair of bf16 values.  (The dword goes through a register of its own first: a bit cast applied
+// directly to an element of a two-dword vector has been seen to read the vector's first element for both.)
+__device__ inline bf16x2 bf16_pair(uint32_t w) {
+  asm volatile("" : "+v"(w));
+  return __builtin_bit_cast(bf16x2, w);
+}
 __device__ inline uint16_t f32_to_bf16(float v) {
   uint32_t u = __float_as_uint(v);
   if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
@@ -1942,10 +1950,11 @@ __device__ inline uint16_t f32_to_bf16(float v) {
 }
 
 // 8 lanes per query row; lane e of a row owns d = 4c .. 4c+3 for c = e, e+8, e+16, e+24.
-// Memory round trips are the cost here, so independent loads are issued in
-// batches: the plan entries together, four tree keys (K and V rows) at a time,
-// and all of a partial's pieces at once.
-constexpr int kKeyBatch = 2;  // (4 and 8 measured slower: the registers they hold cost resident wavefronts)
+// With one wavefront per SIMD (small batches of small trees) memory round trips are the cost here, so independent
+// loads are issued together: the plan entries, the K and V rows of a step's tree keys, all of a partial's pieces.
+// With several wavefronts per SIMD (large trees) the vector instructions of the tree part are, so it works on
+// packed bf16 pairs (below), which also leaves room for five resident wavefronts per SIMD.
+constexpr int kKeyPairs = 1;  // pairs of tree keys per step (2 and 4 measured slower: their registers cost resident wavefronts)
 
 __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   const int wc = blockIdx.x;
@@ -1995,14 +2004,14 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   // tree keys: the set bits of this row's ancestor mask, lowest first
   uint64_t mlo = active ? a.anc_mask[2 * (size_t)node] : 0ull;
   uint64_t mhi = active ? a.anc_mask[2 * (size_t)node + 1] : 0ull;
-  float qv[16];
+  uint32_t qw[8];  // the lane's 16 query elements as 8 bf16 pairs (dims 4 (e + 8 k) + 2 w, + 1)
   {
     const uint16_t* qp = a.q + ((int64_t)node * a.Hq + head) * kD;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const ushortx4 x = *(const ushortx4*)(qp + 4 * (e + 8 * k));
-#pragma unroll
-      for (int i = 0; i < 4; ++i) qv[4 * k + i] = bf16_to_f32(x[i]);
+      const uintx2 x = *(const uintx2*)(qp + 4 * (e + 8 * k));
+      qw[2 * k] = x[0];
+      qw[2 * k + 1] = x[1];
     }
   }
   if (si.n < 64) mlo &= (1ull << si.n) - 1ull, mhi = 0ull;           // never index past the tree
@@ -2012,47 +2021,66 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 
+  // Two keys per step, on the packed bf16 dot product: the score is q . k over bf16 pairs (products exact, sums in
+  // binary32, as before); the two probabilities are rounded to bf16 like those of the matrix-core path, and one
+  // instruction adds p0 v0[d] + p1 v1[d] to an output element (the V elements of the two keys paired by a byte
+  // permute).  With several wavefronts per SIMD this loop is bound by its vector instructions, not by its loads.
   while (__any((mlo | mhi) != 0ull)) {
-    int jn[kKeyBatch];
-    bool have[kKeyBatch];
+    int jn[2 * kKeyPairs];
+    bool have[2 * kKeyPairs];
 #pragma unroll
-    for (int u = 0; u < kKeyBatch; ++u) {
+    for (int u = 0; u < 2 * kKeyPairs; ++u) {
       have[u] = (mlo | mhi) != 0ull;
       jn[u] = 0;
       if (mlo) { jn[u] = __ffsll((unsigned long long)mlo) - 1; mlo &= mlo - 1; }
       else if (mhi) { jn[u] = 64 + __ffsll((unsigned long long)mhi) - 1; mhi &= mhi - 1; }
     }
-    ushortx4 kx[kKeyBatch][4], vx[kKeyBatch][4];
+    uint32_t kw[2 * kKeyPairs][8], vw[2 * kKeyPairs][8];
 #pragma unroll
-    for (int u = 0; u < kKeyBatch; ++u) {
+    for (int u = 0; u < 2 * kKeyPairs; ++u) {
       const uint16_t* kp = a.k_tree + ((int64_t)(base + jn[u]) * a.Hkv + g) * kD;
       const uint16_t* vp = a.v_tree + ((int64_t)(base + jn[u]) * a.Hkv + g) * kD;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        kx[u][k] = *(const ushortx4*)(kp + 4 * (e + 8 * k));
-        vx[u][k] = *(const ushortx4*)(vp + 4 * (e + 8 * k));
+        const uintx2 x = *(const uintx2*)(kp + 4 * (e + 8 * k));
+        const uintx2 y = *(const uintx2*)(vp + 4 * (e + 8 * k));
+        kw[u][2 * k] = x[0];
+        kw[u][2 * k + 1] = x[1];
+        vw[u][2 * k] = y[0];
+        vw[u][2 * k + 1] = y[1];
       }
     }
 #pragma unroll
-    for (int u = 0; u < kKeyBatch; ++u) {
-      float dot = 0.f;
+    for (int pr = 0; pr < kKeyPairs; ++pr) {
+      float dot[2];
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int u = 0; u < 2; ++u) {
+        float d0 = 0.f, d1 = 0.f;  // two chains
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dot = fmaf(qv[4 * k + i], bf16_to_f32(kx[u][k][i]), dot);
-      dot += __shfl_xor(dot, 1);
-      dot += __shfl_xor(dot, 2);
-      dot += __shfl_xor(dot, 4);
-      if (have[u]) {
-        const float m_new = fmaxf(m, dot);
-        const float al = __builtin_amdgcn_exp2f((m - m_new) * c);
-        const float p = __builtin_amdgcn_exp2f((dot - m_new) * c);
-        l = l * al + p;
+        for (int i = 0; i < 8; i += 2) {
+          d0 = __builtin_amdgcn_fdot2_f32_bf16(bf16_pair(qw[i]), bf16_pair(kw[2 * pr + u][i]), d0, false);
+          d1 = __builtin_amdgcn_fdot2_f32_bf16(bf16_pair(qw[i + 1]), bf16_pair(kw[2 * pr + u][i + 1]), d1, false);
+        }
+        float d = d0 + d1;
+        d += __shfl_xor(d, 1);
+        d += __shfl_xor(d, 2);
+        d += __shfl_xor(d, 4);
+        dot[u] = have[2 * pr + u] ? d : -INFINITY;
+      }
+      const float m_new = fmaxf(m, fmaxf(dot[0], dot[1]));
+      const float al = m_new == m ? 1.f : __builtin_amdgcn_exp2f((m - m_new) * c);  // (also when both are -inf)
+      floatx2 p;
+      p[0] = have[2 * pr] ? __builtin_amdgcn_exp2f((dot[0] - m_new) * c) : 0.f;
+      p[1] = have[2 * pr + 1] ? __builtin_amdgcn_exp2f((dot[1] - m_new) * c) : 0.f;
+      l = l * al + (p[0] + p[1]);
+      m = m_new;
+      const bf16x2 pp = __builtin_convertvector(p, bf16x2);
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) acc[4 * k + i] = acc[4 * k + i] * al + p * bf16_to_f32(vx[u][k][i]);
-        m = m_new;
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t lo = __builtin_amdgcn_perm(vw[2 * pr + 1][i], vw[2 * pr][i], 0x05040100u);  // (v0[d], v1[d])
+        const uint32_t hi = __builtin_amdgcn_perm(vw[2 * pr + 1][i], vw[2 * pr][i], 0x07060302u);  // (v0[d + 1], v1[d + 1])
+        acc[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(bf16_pair(lo), pp, acc[2 * i] * al, false);
+        acc[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(bf16_pair(hi), pp, acc[2 * i + 1] * al, false);
       }
     }
   }
