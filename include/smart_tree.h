@@ -235,7 +235,7 @@ int32_t smart_baseline_tree(
  * included (ties: smaller depth, then the lexicographically smaller index
  * sequence), listed in that order, so a parent precedes its children.  The
  * result has the layout smart_select_tree and smart_baseline_tree read; its
- * first g + 1 candidates are the tree "pruned to the top g".
+ * first g + 1 candidates are the tree cut to its g most probable nodes.
  *
  * Inputs (host): h_pos_prob, h_pos_token [batch][depth][k] (probabilities in
  * [0,1], in any order).  Outputs (host): h_cand_cu[batch+1]; per candidate the

@@ -1,6 +1,6 @@
 """CPU oracle: temperature-1 (sampling) verification of a draft tree.  TEST INFRASTRUCTURE ONLY.
 
-The paper evaluates at temperatures 0 and 1 "following prior work" and relies on verification
+The paper evaluates at temperatures 0 and 1, as the work it builds on does, and relies on verification
 being lossless (Sec. 4, evaluation paragraph); the tree-based drafters it builds on propose a
 node's children deterministically (the draft model's top-k tokens), and for deterministic
 proposals the lossless rule is:

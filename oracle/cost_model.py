@@ -8,7 +8,7 @@ eta = 0):
     C_draft(x)  = lambda * x
     C_verify(x) = gamma * (exp(delta * x**rho) - 1)
 
-"fitted per device" from a handful of timed forward passes.  Sec. 3.2 then
+with parameters fitted for each device from a handful of timed forward passes.  Sec. 3.2 then
 takes the marginal cost of one more node as the derivative of their sum
 (Eq. "marginal_cost"):
 

@@ -3,8 +3,8 @@
  * in the product path may call, link or import this file.
  *
  * What it computes (the plain definition; the paper only names the step --
- * "verifying an entire tree in a single forward pass", Sec. 1, and leaves the
- * verification mechanism unchanged, Sec. 1 "Contributions"):
+ * the target model checks a whole draft tree in one forward pass, Sec. 1 -- and
+ * leaves the verification mechanism unchanged, Sec. 1, contributions):
  *
  *   for every sequence b, tree node i of b, query head h (kv head g = h / G):
  *     keys(i)  = { cache token t : 0 <= t < prefix_len[b] }

@@ -1,8 +1,8 @@
 // tree_pack and tree_accept: integer-only kernels, one 64-lane wavefront per
 // sequence (trees hold at most 128 nodes, so a lane owns nodes lane, lane+64).
 //
-// The paper verifies "an entire tree in a single forward pass" (Sec. 1) and
-// keeps the prefix of a draft path the target agrees with (Sec. 3.1, below
+// The paper has the target model check a whole draft tree in one forward pass
+// (Sec. 1) and keeps the prefix of a draft path the target agrees with (Sec. 3.1, below
 // Eq. "cum_prob"); these kernels produce what that pass needs (positions,
 // ancestor masks) and what it yields (the accepted path).
 #include "common.h"

@@ -451,7 +451,7 @@ def test_product_forest_bit_exact_against_the_oracle(seed):
 
 def test_product_forest_feeds_both_policies():
     """A forest cut at a cap well above the budget gives the rule the same tree as the whole product, and the
-    tree "pruned to the top g" is the head of the list."""
+    tree cut to its g most probable nodes is the head of the list."""
     rng = np.random.default_rng(5)
     logits = rng.normal(0.0, 2.0, size=(3, 6, 8))
     pp = np.exp(logits) / np.exp(logits).sum(-1, keepdims=True)
