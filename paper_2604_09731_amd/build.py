@@ -1,4 +1,6 @@
-"""Builds the C-ABI library (libsmart_tree.so) in-tree with hipcc for gfx950."""
+"""Builds the C-ABI library (libsmart_tree.so) in-tree with hipcc for gfx950, and beside it the timeline build
+(libsmart_tree_timeline.so: the same library with wall-clock stamps in the attention kernels, for
+`python -m paper_2604_09731_amd.timeline`; nothing else loads it)."""
 from __future__ import annotations
 
 import os
@@ -9,6 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsmart_tree.so")
+TIMELINE_LIB = os.path.join(HERE, "libsmart_tree_timeline.so")
+TIMELINE_SOURCE = "tva_mfma.hip"        # the one source with stamps (-DSMART_TVA_TIMELINE)
 OBJ_DIR = os.path.join(HERE, "_build")
 
 HIP_SOURCES = ["smart_ctx.hip", "tree_pack_accept.hip", "kv_cache_write.hip", "tva_general.hip",
@@ -50,6 +54,14 @@ def build_library(verbose: bool = False) -> str:
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs, "-pthread"])
     if verbose:
         print("built", LIB)
+    # the timeline build: one object compiled again with the stamps, the rest shared
+    plain = os.path.join(OBJ_DIR, TIMELINE_SOURCE + ".o")
+    stamped = os.path.join(OBJ_DIR, TIMELINE_SOURCE + ".timeline.o")
+    _run([HIPCC, *HIP_FLAGS, "-DSMART_TVA_TIMELINE", "-c", os.path.join(CSRC, TIMELINE_SOURCE), "-o", stamped])
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", TIMELINE_LIB,
+          *[stamped if o == plain else o for o in objs], "-pthread"])
+    if verbose:
+        print("built", TIMELINE_LIB)
     return LIB
 
 

@@ -37,6 +37,21 @@
 
 #include "common.h"
 
+// The timeline build (-DSMART_TVA_TIMELINE, a library of its own: libsmart_tree_timeline.so, read by
+// python -m paper_2604_09731_amd.timeline) keeps wall-clock stamps (100 MHz counter) of the LAST launch: per
+// workgroup of the prefix kernel its start, end, shader cycles and class; per wavefront of the combine kernel its
+// start and end.  Nothing of this is in the ordinary library.
+#ifdef SMART_TVA_TIMELINE
+namespace timeline {
+constexpr int kWorkgroups = 1024, kWaves = 16384;
+__device__ unsigned long long wg_stamps[kWorkgroups * 4];  // start, end, shader cycles, class | worker << 8
+__device__ unsigned long long wave_stamps[kWaves * 2];     // start, end
+}  // namespace timeline
+#define SMART_TIMELINE(...) __VA_ARGS__
+#else
+#define SMART_TIMELINE(...)
+#endif
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -1810,6 +1825,7 @@ template <bool kFp8>
 __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tva_prefix_kernel(MainArgs a) {
   __shared__ float4 lds_raw[8448];  // 132 KB, carved up per class (class 0: eight states of 16.5 KB)
+  SMART_TIMELINE(const unsigned long long tl_start = wall_clock64(); const unsigned long long tl_cycles = clock64();)
   // Workgroups are dealt to the eight XCDs round robin; consecutive WORKERS (consecutive unit ranges: the row groups
   // of one segment, the two ends of a segment) are put on one XCD so that what they read in common meets in its L2.
   const int64_t wg = gridDim.x % 8 == 0 ? (int64_t)(blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8 : (int64_t)blockIdx.x;
@@ -1896,9 +1912,20 @@ void tva_prefix_kernel(MainArgs a) {
     cp.resident = false;
   }
   if (wg >= end) return;
+  SMART_TIMELINE(auto tl_end = [&]() {
+    __syncthreads();  // the workgroup's end is its last wavefront's
+    if (threadIdx.x == 0 && blockIdx.x < timeline::kWorkgroups) {
+      unsigned long long* d = timeline::wg_stamps + 4 * blockIdx.x;
+      d[0] = tl_start;
+      d[1] = wall_clock64();
+      d[2] = clock64() - tl_cycles;
+      d[3] = (unsigned long long)(wg < first1 ? 0 : (wg < first2 ? 1 : 2)) | ((unsigned long long)wg << 8) | (1ull << 63);
+    }
+  };)
   if (kFp8) {
     if (wg >= first1 && wg < first2) fp8_worker(a, wg - first1, cp, (float*)lds_raw);
     else if (wg >= first2) staged_worker<2, true>(a, wg - first2, cp, (bf16x8*)lds_raw);
+    SMART_TIMELINE(tl_end();)
     return;
   }
   if (wg < first1) {
@@ -1908,6 +1935,7 @@ void tva_prefix_kernel(MainArgs a) {
   } else {
     staged_worker<2>(a, wg - first2, cp, (bf16x8*)lds_raw);
   }
+  SMART_TIMELINE(tl_end();)
 }
 
 // ---------------------------------------------------------------------------
@@ -1959,6 +1987,7 @@ constexpr int kKeyPairs = 1;  // pairs of tree keys per step (2 and 4 measured s
 __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   const int wc = blockIdx.x;
   const int lane = threadIdx.x;
+  SMART_TIMELINE(const unsigned long long tl_start = wall_clock64();)
   // the first `batch` wavefronts also check one sequence's block-table entries each (the grid has at least that many)
   if (a.status && wc < a.batch)
     smart::tva_validate_block_table(wc, a.block_table, a.prefix_len, a.max_blocks, kBlock, a.num_blocks, a.status, lane);
@@ -2133,6 +2162,10 @@ __global__ __launch_bounds__(kWave) void tva_combine_kernel(CombineArgs a) {
   }
   if (a.lse && e == 0)
     a.lse[(int64_t)node * a.Hq + head] = l > 0.f ? m * a.scale + logf(l) : -INFINITY;
+  SMART_TIMELINE(if (lane == 0 && wc < timeline::kWaves) {  // (lane 0's row always exists)
+    timeline::wave_stamps[2 * wc] = tl_start;
+    timeline::wave_stamps[2 * wc + 1] = wall_clock64();
+  })
 }
 
 }  // namespace
@@ -2329,3 +2362,24 @@ int32_t tva_launch_mfma(smart_ctx* ctx, hipStream_t stream, const tva_params& p,
 }
 
 }  // namespace smart
+
+#ifdef SMART_TVA_TIMELINE
+// Stamps of the last launch on the current device into host arrays of 4 x 1024 and 2 x 16384 words (unused entries
+// are zero after smart_timeline_clear); both calls synchronize the device.
+extern "C" int32_t smart_timeline_read(uint64_t* h_workgroups, uint64_t* h_waves) {
+  if (!h_workgroups || !h_waves) return SMART_EINVAL;
+  SMART_HIP_CHECK(hipDeviceSynchronize());
+  SMART_HIP_CHECK(hipMemcpyFromSymbol(h_workgroups, HIP_SYMBOL(timeline::wg_stamps), sizeof(timeline::wg_stamps)));
+  SMART_HIP_CHECK(hipMemcpyFromSymbol(h_waves, HIP_SYMBOL(timeline::wave_stamps), sizeof(timeline::wave_stamps)));
+  return SMART_OK;
+}
+extern "C" int32_t smart_timeline_clear() {
+  SMART_HIP_CHECK(hipDeviceSynchronize());
+  void* p = nullptr;
+  SMART_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(timeline::wg_stamps)));
+  SMART_HIP_CHECK(hipMemset(p, 0, sizeof(timeline::wg_stamps)));
+  SMART_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(timeline::wave_stamps)));
+  SMART_HIP_CHECK(hipMemset(p, 0, sizeof(timeline::wave_stamps)));
+  return SMART_OK;
+}
+#endif

@@ -26,6 +26,18 @@ def test_library_exports_every_declared_symbol():
     assert B._strerror(0) == "ok" and "tree" in B._strerror(B.SMART_ETREE)
 
 
+def test_timeline_build_exports_the_library_and_its_two_calls():
+    """The timeline build (stamps in the attention kernels, for python -m paper_2604_09731_amd.timeline) is the
+    same library plus smart_timeline_read / smart_timeline_clear; the ordinary library has neither."""
+    from paper_2604_09731_amd import timeline
+    assert os.path.exists(timeline.TIMELINE_LIB), "build it with python -m paper_2604_09731_amd.build"
+    stamped = ctypes.CDLL(timeline.TIMELINE_LIB)
+    for name in list(B.EXPORTS) + ["smart_timeline_read", "smart_timeline_clear"]:
+        assert hasattr(stamped, name), name
+    plain = ctypes.CDLL(B.LIB_PATH)
+    assert not hasattr(plain, "smart_timeline_read") and not hasattr(plain, "smart_timeline_clear")
+
+
 @pytest.mark.parametrize("name", ["cfg2", "cfg3a", "cfg3b", "cfg4", "cfg5a", "cfg5b"])
 def test_selection_bit_exact_on_workloads(name):
     w = W.WORKLOADS[name]
