@@ -417,9 +417,12 @@ int32_t tree_upload(smart_ctx* ctx, void* stream, const void* h_pinned_src, void
  * packs it from LDS, which saves a kernel launch per verify step.
  * total_nodes must equal h_pinned_cu_nodes[batch] (a sequence whose offsets
  * leave [0, total_nodes] gets status SMART_ETREE and nothing of it is copied).
- * The pinned arrays must be complete when this is called (the offsets of a
- * batch of at most 64 sequences are read by the host during the call and
- * travel with the launch) and stay untouched until the kernel has run.
+ * The pinned arrays must be complete when this is called (of a batch of at
+ * most 64 sequences the offsets, and with at most 448 nodes in all the trees
+ * too, are read by the host during the call and travel with the launch) and
+ * stay untouched until the kernel has run.  On a stream that is being
+ * captured into a graph nothing travels with the launch: every replay reads
+ * the pinned arrays when it runs (batch and total_nodes are the graph's).
  * Errors: as tree_pack, plus SMART_EINVAL for pageable host memory and for
  * token pointers of which only one is NULL.
  * ------------------------------------------------------------------------- */

@@ -7,6 +7,8 @@
 // ancestor masks) and what it yields (the accepted path).
 #include "common.h"
 
+#include <cstring>
+
 namespace {
 
 constexpr int kWave = 64;
@@ -74,18 +76,35 @@ struct CuArgs {
   int32_t v[kCuInArgs + 1];
 };
 
+// Small batches of small trees travel whole in the kernel arguments (the host copies parents and tokens out of
+// the pinned arrays when it launches): no round trip over the host link is left in the kernel.
+constexpr int kTreeInArgs = 448;  // nodes; with the offsets 3.9 KB of the 4 KB an argument block may have
+struct TreeArgs {
+  int32_t parent[kTreeInArgs];
+  int32_t token[kTreeInArgs];
+};
+struct HostTrees {  // the trees where the caller left them: pinned host memory
+  const int32_t* parent;
+  const int32_t* token;
+  __device__ int32_t parent_at(int i) const { return parent[i]; }
+  __device__ int32_t token_at(int i) const { return token[i]; }
+};
+struct ArgTrees {  // the trees in the argument block
+  const TreeArgs& t;
+  __device__ int32_t parent_at(int i) const { return t.parent[i]; }
+  __device__ int32_t token_at(int i) const { return t.token[i]; }
+};
+
 // tree_upload of the selected trees and tree_pack in one launch: the wavefront of sequence b
-// fetches its tree from pinned host memory (offsets -- unless they came with the arguments --
-// then nodes: a round trip over the host link each), leaves device copies for the kernels that
-// follow, and packs from LDS.
-__global__ __launch_bounds__(kWave) void tree_upload_pack_kernel(
-    const CuArgs cu_args, int cu_in_args,
-    int batch, int total_nodes, const int32_t* __restrict__ h_cu_nodes, const int32_t* __restrict__ h_parent,
-    const int32_t* __restrict__ h_token, int32_t* __restrict__ cu_nodes, int32_t* __restrict__ parent,
-    int32_t* __restrict__ token, const int32_t* __restrict__ prefix_len, int32_t* __restrict__ depth,
-    int32_t* __restrict__ position, int32_t* __restrict__ node_seq, uint64_t* __restrict__ anc_mask,
-    int32_t* __restrict__ status) {
-  __shared__ int32_t par[SMART_MAX_NODES];
+// fetches its tree (offsets, then nodes: from the arguments, or a round trip over the host link
+// each), leaves device copies for the kernels that follow, and packs from LDS.
+template <typename Trees>
+__device__ inline void upload_pack_sequence(
+    const CuArgs& cu_args, int cu_in_args, const Trees trees, bool with_tokens,
+    int batch, int total_nodes, const int32_t* __restrict__ h_cu_nodes, int32_t* __restrict__ cu_nodes,
+    int32_t* __restrict__ parent, int32_t* __restrict__ token, const int32_t* __restrict__ prefix_len,
+    int32_t* __restrict__ depth, int32_t* __restrict__ position, int32_t* __restrict__ node_seq,
+    uint64_t* __restrict__ anc_mask, int32_t* __restrict__ status, int32_t* par /* LDS, SMART_MAX_NODES */) {
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
   if (b >= batch) return;
@@ -102,13 +121,37 @@ __global__ __launch_bounds__(kWave) void tree_upload_pack_kernel(
   }
   const int n = end - base;
   for (int i = lane; i < n; i += kWave) {
-    const int p = h_parent[base + i];
+    const int p = trees.parent_at(base + i);
     parent[base + i] = p;
     if (i < SMART_MAX_NODES) par[i] = p;
-    if (token) token[base + i] = h_token[base + i];
+    if (with_tokens) token[base + i] = trees.token_at(base + i);
   }
   __syncthreads();
   pack_sequence(b, lane, base, n, len, [&](int i) { return par[i]; }, depth, position, node_seq, anc_mask, status);
+}
+
+__global__ __launch_bounds__(kWave) void tree_upload_pack_kernel(
+    const CuArgs cu_args, int cu_in_args,
+    int batch, int total_nodes, const int32_t* __restrict__ h_cu_nodes, const int32_t* __restrict__ h_parent,
+    const int32_t* __restrict__ h_token, int32_t* __restrict__ cu_nodes, int32_t* __restrict__ parent,
+    int32_t* __restrict__ token, const int32_t* __restrict__ prefix_len, int32_t* __restrict__ depth,
+    int32_t* __restrict__ position, int32_t* __restrict__ node_seq, uint64_t* __restrict__ anc_mask,
+    int32_t* __restrict__ status) {
+  __shared__ int32_t par[SMART_MAX_NODES];
+  upload_pack_sequence(cu_args, cu_in_args, HostTrees{h_parent, h_token}, token != nullptr, batch, total_nodes,
+                       h_cu_nodes, cu_nodes, parent, token, prefix_len, depth, position, node_seq, anc_mask, status,
+                       par);
+}
+
+__global__ __launch_bounds__(kWave) void tree_upload_pack_args_kernel(
+    const CuArgs cu_args, const TreeArgs tree_args, int with_tokens, int batch, int total_nodes,
+    int32_t* __restrict__ cu_nodes, int32_t* __restrict__ parent, int32_t* __restrict__ token,
+    const int32_t* __restrict__ prefix_len, int32_t* __restrict__ depth, int32_t* __restrict__ position,
+    int32_t* __restrict__ node_seq, uint64_t* __restrict__ anc_mask, int32_t* __restrict__ status) {
+  __shared__ int32_t par[SMART_MAX_NODES];
+  // (total_nodes <= kTreeInArgs here, and the offsets are checked against total_nodes before anything is indexed)
+  upload_pack_sequence(cu_args, 1, ArgTrees{tree_args}, with_tokens != 0, batch, total_nodes, nullptr, cu_nodes,
+                       parent, token, prefix_len, depth, position, node_seq, anc_mask, status, par);
 }
 
 // The trees of a layer-at-a-time selection (`stride` entries per sequence, n[b] of them used)
@@ -251,9 +294,26 @@ extern "C" int32_t tree_upload_pack(smart_ctx* ctx, void* stream, int32_t batch,
   if (!device_can_address(h_pinned_cu_nodes) || (total_nodes > 0 && !device_can_address(h_pinned_parent)) ||
       (h_pinned_token && total_nodes > 0 && !device_can_address(h_pinned_token)))
     return SMART_EINVAL;
+  // What travels in the arguments is what the pinned arrays hold NOW.  A launch that is being captured into a graph
+  // runs later, perhaps many times, and must read the arrays when it runs: nothing travels then.
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing((hipStream_t)stream, &capture) != hipSuccess) {
+    (void)hipGetLastError();
+    capture = hipStreamCaptureStatusNone;
+  }
   CuArgs cu_args;
-  const int cu_in_args = batch <= kCuInArgs;
+  const int cu_in_args = capture == hipStreamCaptureStatusNone && batch <= kCuInArgs;
   for (int b = 0; b <= kCuInArgs; ++b) cu_args.v[b] = cu_in_args && b <= batch ? h_pinned_cu_nodes[b] : 0;
+  if (cu_in_args && total_nodes > 0 && total_nodes <= kTreeInArgs) {
+    TreeArgs tree_args;
+    std::memcpy(tree_args.parent, h_pinned_parent, sizeof(int32_t) * (size_t)total_nodes);
+    if (h_pinned_token) std::memcpy(tree_args.token, h_pinned_token, sizeof(int32_t) * (size_t)total_nodes);
+    hipLaunchKernelGGL(tree_upload_pack_args_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, cu_args,
+                       tree_args, h_pinned_token ? 1 : 0, batch, total_nodes, d_cu_nodes, d_parent, d_token,
+                       d_prefix_len, d_depth, d_position, d_node_seq, d_anc_mask, d_status);
+    SMART_HIP_CHECK(hipGetLastError());
+    return SMART_OK;
+  }
   hipLaunchKernelGGL(tree_upload_pack_kernel, dim3(batch), dim3(kWave), 0, (hipStream_t)stream, cu_args, cu_in_args,
                      batch, total_nodes, h_pinned_cu_nodes, h_pinned_parent, h_pinned_token, d_cu_nodes, d_parent,
                      d_token, d_prefix_len, d_depth, d_position, d_node_seq, d_anc_mask, d_status);

@@ -57,3 +57,14 @@ def test_graph_replays_equal_the_eager_step():
         device_step()
         torch.cuda.synchronize()
         p_par.copy_(torch.from_numpy(parent))
+    # A replay reads the pinned arrays when it runs, not what they held at capture: other tokens (same trees)
+    # change what is accepted, and the replay must follow them.
+    p_tok.copy_(torch.from_numpy(np.ascontiguousarray(token[::-1] + 1)))
+    ref2 = device_step()
+    torch.cuda.synchronize()
+    ref2 = [x.clone() for x in ref2]
+    assert not all(torch.equal(a, b) for a, b in zip(ref2, (ref_len, ref_path, ref_bonus))), "tokens changed nothing"
+    res[0].fill_(-7)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(res, ref2))

@@ -293,3 +293,39 @@ def test_tree_upload_pack_offsets_in_the_arguments_or_fetched(lib, batch):
     torch.cuda.synchronize()
     st = out[-1].cpu().numpy()
     assert st[4] == B.SMART_ETREE or st[5] == B.SMART_ETREE
+
+
+@pytest.mark.parametrize("total", [383, 447, 448, 449, 700])
+@pytest.mark.parametrize("with_tokens", [True, False])
+def test_tree_upload_pack_trees_in_the_arguments_or_fetched(lib, total, with_tokens):
+    """With at most 448 nodes in all (and at most 64 sequences) parents and tokens travel with the launch as well,
+    above that the kernel fetches them from the pinned arrays: both sides of the limit leave the same copies and the
+    oracle's packing, with and without tokens; a malformed tree is reported either way."""
+    import torch
+    sizes = [128, 100, 90, 1, 33]
+    rest = total - sum(sizes)
+    while rest > 128:
+        sizes.append(64)
+        rest -= 64
+    sizes.append(rest)
+    assert sum(sizes) == total and all(1 <= n <= 128 for n in sizes)
+    cu, parent, rng = _random_batch(900 + total, sizes, [["random", "chain", "star"][i % 3] for i in range(len(sizes))])
+    token = rng.integers(0, 1 << 30, size=total).astype(np.int32)
+    prefix_len = rng.integers(0, 5000, size=len(sizes)).astype(np.int32)
+    pin = lambda a: torch.from_numpy(np.ascontiguousarray(a)).pin_memory()
+    out = lib.tree_upload_pack(pin(cu), pin(parent), pin(token) if with_tokens else None, _dev(prefix_len))
+    torch.cuda.synchronize()
+    d_cu, d_par, d_tok, depth, position, node_seq, mask, status = out
+    assert np.array_equal(d_cu.cpu().numpy(), cu) and np.array_equal(d_par.cpu().numpy(), parent)
+    assert (d_tok is None) if not with_tokens else np.array_equal(d_tok.cpu().numpy(), token)
+    assert not status.cpu().numpy().any()
+    r_depth, r_pos, r_seq, r_mask = PA.pack(cu, parent, prefix_len)
+    assert np.array_equal(depth.cpu().numpy(), np.array(r_depth)) and np.array_equal(position.cpu().numpy(), np.array(r_pos))
+    assert np.array_equal(node_seq.cpu().numpy(), np.array(r_seq))
+    assert np.array_equal(mask.cpu().numpy().view(np.uint64), _mask_words(r_mask))
+    parent_bad = parent.copy()
+    parent_bad[cu[1] + 3] = 50                       # a parent that does not precede its child
+    st = lib.tree_upload_pack(pin(cu), pin(parent_bad), pin(token) if with_tokens else None, _dev(prefix_len))[-1]
+    torch.cuda.synchronize()
+    st = st.cpu().numpy()
+    assert st[1] == B.SMART_ETREE and not np.delete(st, 1).any()
