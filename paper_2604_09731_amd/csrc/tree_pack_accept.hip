@@ -211,13 +211,19 @@ __global__ __launch_bounds__(kWave) void tree_accept_kernel(
     if (lane == 0) { accept_len[b] = -1; bonus_token[b] = -1; }
     return;
   }
-  // this lane's two nodes
+  // this lane's two nodes, and what the target puts after each (fetched with them: the walk below then needs no
+  // further round trip, whatever its depth)
   const int i0 = lane, i1 = lane + kWave;
   const int p0 = i0 < n ? parent[base + i0] : -2, t0 = i0 < n ? token[base + i0] : 0;
   const int p1 = i1 < n ? parent[base + i1] : -2, t1 = i1 < n ? token[base + i1] : 0;
+  const int next0 = i0 < n ? target_next[base + i0] : 0, next1 = i1 < n ? target_next[base + i1] : 0;
+  auto target_after = [&](int node) {  // node is wave-uniform
+    const int j = __builtin_amdgcn_readfirstlane(node);
+    return j < kWave ? __builtin_amdgcn_readlane(next0, j) : __builtin_amdgcn_readlane(next1, j - kWave);
+  };
   int cur = 0, len = 0;
   while (len < max_depth) {  // at most max_depth iterations, wave-uniform
-    const int want = target_next[base + cur];
+    const int want = target_after(cur);
     const uint64_t m0 = __ballot(p0 == cur && t0 == want);
     const uint64_t m1 = __ballot(p1 == cur && t1 == want);
     int nxt;
@@ -228,10 +234,11 @@ __global__ __launch_bounds__(kWave) void tree_accept_kernel(
     ++len;
     if (lane == 0) path[len] = cur;
   }
+  const int bonus = target_after(cur);
   if (lane == 0) {
     path[0] = 0;
     accept_len[b] = len;
-    bonus_token[b] = target_next[base + cur];
+    bonus_token[b] = bonus;
   }
 }
 
