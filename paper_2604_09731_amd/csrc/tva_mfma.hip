@@ -822,13 +822,23 @@ __device__ inline void small_segment(SmallState& S, const MainArgs& a, int b, in
 // A wavefront's running softmax state in LDS: register by register, lane by lane.
 constexpr int kStateFloats = (64 + 2) * kWave;  // 64 accumulator registers + max + sum, per lane
 
+// (four registers of a lane lie together: 16-byte LDS accesses on both sides of the fold)
 __device__ inline void state_to_lds(const SmallState& S, float* region, int lane) {
 #pragma unroll
   for (int jt = 0; jt < 4; ++jt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) region[(jt * 16 + r) * kWave + lane] = S.o[jt][r];
+    for (int r4 = 0; r4 < 4; ++r4) {
+      floatx4 x;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[i] = S.o[jt][4 * r4 + i];
+      ((floatx4*)region)[(jt * 4 + r4) * kWave + lane] = x;
+    }
   region[64 * kWave + lane] = S.m;
   region[65 * kWave + lane] = S.l;
+}
+// Accumulator registers 4 quad .. 4 quad + 3 of a lane out of a state in LDS.
+__device__ inline floatx4 state_quad(const float* state, int quad, int lane) {
+  return ((const floatx4*)state)[quad * kWave + lane];
 }
 
 
@@ -859,9 +869,7 @@ __device__ inline void fold_and_store(const SmallState& S, float* lds, float* sl
 #pragma unroll
   for (int k = 0; k < kWgWaves; ++k)
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) part[k][u][i] = lds[k * kStateFloats + (8 * wv + 4 * u + i) * kWave + lane];
+    for (int u = 0; u < 2; ++u) part[k][u] = state_quad(lds + k * kStateFloats, 2 * wv + u, lane);
   float m_new = mk[0];
 #pragma unroll
   for (int k = 1; k < kWgWaves; ++k) m_new = fmaxf(m_new, mk[k]);
@@ -1117,10 +1125,7 @@ __device__ inline void fold_halves_and_store(const SmallState& S, float* lds, fl
     l_new += lk[k] * sc;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      floatx4 r;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] = lds[(4 * rt + k) * kStateFloats + (16 * part + 4 * u + i) * kWave + lane];
-      x[u] += r * sc;
+      x[u] += state_quad(lds + (4 * rt + k) * kStateFloats, 4 * part + u, lane) * sc;
     }
   }
   // accumulator register 16 jt + 4 r4 + i of lane (h, j) is row j, head dims 4 (8 jt + 2 r4 + h) + i; here jt = part, r4 = u
@@ -1632,9 +1637,7 @@ __device__ inline void fold_groups(const SmallState& S, float* lds, float* slot,
   for (int k = 0; k < K; ++k)
 #pragma unroll
     for (int u = 0; u < kRegs / 4; ++u)
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        part[k][u][i] = lds[(rt * K + k) * kStateFloats + (part_index * kRegs + 4 * u + i) * kWave + lane];
+      part[k][u] = state_quad(lds + (rt * K + k) * kStateFloats, part_index * (kRegs / 4) + u, lane);
   float m_new = mk[0];
 #pragma unroll
   for (int k = 1; k < K; ++k) m_new = fmaxf(m_new, mk[k]);
