@@ -303,8 +303,9 @@ extern "C" int32_t tree_upload_pack(smart_ctx* ctx, void* stream, int32_t batch,
     return SMART_EINVAL;
   // What travels in the arguments is what the pinned arrays hold NOW.  A launch that is being captured into a graph
   // runs later, perhaps many times, and must read the arrays when it runs: nothing travels then.
+  // (the default stream cannot be captured, and asking about it while another stream is captured is an error)
   hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing((hipStream_t)stream, &capture) != hipSuccess) {
+  if (stream != nullptr && hipStreamIsCapturing((hipStream_t)stream, &capture) != hipSuccess) {
     (void)hipGetLastError();
     capture = hipStreamCaptureStatusNone;
   }
